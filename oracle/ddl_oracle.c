@@ -1,0 +1,291 @@
+/*
+ * ddl_oracle.c -- TEST INFRASTRUCTURE ONLY.
+ *
+ * Plain, slow, fp64 CPU statement of what the Decoupled DiLoCo synchronizer
+ * computes for one fragment: Weight -> Merge -> OuterOpt (Algorithm 2, steps
+ * "Weight", "mergeFn" and "OuterOpt").  It exists so that the HIP path can be
+ * checked against something that a reader can compare with the paper by eye.
+ * It shares no code, header, table or helper with the HIP library, and nothing
+ * in the product path may call it: only the tests, the smoke check and the
+ * CPU-baseline leg of the benchmark do.
+ *
+ * All pointers are HOST pointers.  Inputs keep their storage type (fp32 or
+ * bf16); every input is widened exactly to double before any arithmetic and
+ * every result is returned in double.
+ *
+ * Nothing here is blocked, fused, vectorised or reordered: one loop over the
+ * elements, one inner loop over the learners, in the order the paper writes the
+ * sums.
+ */
+#include <math.h>
+#include <pthread.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORACLE_OK = 0, ORACLE_BAD_ARG = 1, ORACLE_EMPTY_QUORUM = 2 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+#define ORACLE_MAX_LEARNERS 64
+
+/* bf16 is the upper half of an IEEE fp32 word: widening is exact. */
+static double widen_bf16(uint16_t h)
+{
+    uint32_t bits = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+static double learner_value(const void* base, int dtype, size_t i)
+{
+    if (dtype == ORACLE_BF16)
+        return widen_bf16(((const uint16_t*)base)[i]);
+    return (double)((const float*)base)[i];
+}
+
+/*
+ * Weight, tokens-only form, normalised over the quorum.
+ *
+ * Raw weight of learner m is q_m * n_m: its token counter c^tokens since the
+ * last sync of this fragment (Algorithm 1, counter update) if it is a member of
+ * the reporting set M_t (Section 3.2), zero if it is absent (Section 4, "Syncer
+ * worker": an absent learner takes part in the same Merge with weight 0).  The
+ * weighted Merge divides by the sum of the weights over M_t (Appendix D.2,
+ * weighted direct averaging), so the normalised weight is
+ *     w_m = q_m n_m / sum_k q_k n_k.
+ * A quorum whose weights sum to zero has no defined merge: ORACLE_EMPTY_QUORUM.
+ */
+int ddl_oracle_weights(const uint64_t* token_counts, const uint8_t* quorum_mask,
+                       int M, double* w_out)
+{
+    if (!token_counts || !quorum_mask || !w_out || M < 1 || M > ORACLE_MAX_LEARNERS)
+        return ORACLE_BAD_ARG;
+    double S = 0.0;
+    for (int m = 0; m < M; ++m) {
+        if (quorum_mask[m] > 1)
+            return ORACLE_BAD_ARG;
+        if (quorum_mask[m])
+            S += (double)token_counts[m];
+    }
+    if (S == 0.0)
+        return ORACLE_EMPTY_QUORUM;
+    for (int m = 0; m < M; ++m)
+        w_out[m] = quorum_mask[m] ? (double)token_counts[m] / S : 0.0;
+    return ORACLE_OK;
+}
+
+/*
+ * The paper's own Weight function (Section 3.2): quantity x quality,
+ *     Weight(c_tokens, c_steps) = c_tokens * (c_tokens / c_steps),
+ * again zero for absent learners and normalised over the quorum.  A member of
+ * the quorum with c_steps = 0 has taken no step since the last sync and so has
+ * c_tokens = 0 too (both counters move together in Algorithm 1); its raw
+ * weight is taken as 0.  c_steps = 0 with c_tokens > 0 cannot happen in the
+ * protocol and is rejected.
+ */
+int ddl_oracle_weights_quality(const uint64_t* token_counts, const uint64_t* step_counts,
+                               const uint8_t* quorum_mask, int M, double* w_out)
+{
+    if (!token_counts || !step_counts || !quorum_mask || !w_out || M < 1 ||
+        M > ORACLE_MAX_LEARNERS)
+        return ORACLE_BAD_ARG;
+    double raw[ORACLE_MAX_LEARNERS];
+    double S = 0.0;
+    for (int m = 0; m < M; ++m) {
+        raw[m] = 0.0;
+        if (quorum_mask[m] > 1)
+            return ORACLE_BAD_ARG;
+        if (!quorum_mask[m])
+            continue;
+        if (step_counts[m] == 0) {
+            if (token_counts[m] != 0)
+                return ORACLE_BAD_ARG;
+            continue;
+        }
+        double c_tok = (double)token_counts[m];
+        raw[m] = c_tok * (c_tok / (double)step_counts[m]);
+        S += raw[m];
+    }
+    if (S == 0.0)
+        return ORACLE_EMPTY_QUORUM;
+    for (int m = 0; m < M; ++m)
+        w_out[m] = raw[m] / S;
+    return ORACLE_OK;
+}
+
+/*
+ * Merge (weighted direct averaging, Appendix D.2) followed by OuterOpt (SGD
+ * with Nesterov momentum, Sections 2 and 3.2) on elements [lo, hi) of one flat
+ * fragment, given already-normalised weights.
+ *
+ *   Delta_i = sum_{m in quorum} w_m * (Theta_i - theta_{m,i})
+ *
+ * The outer gradient is "old global minus learner" (Eq. 1, Eq. 2, Appendix
+ * D.2).  Learners with w_m = 0 are skipped, not multiplied by zero, so whatever
+ * an absent learner's buffer holds (garbage, NaN, nothing at all) cannot reach
+ * the result.
+ *
+ * The paper names the outer optimiser but does not print its update.  The
+ * reading taken is the momentum-buffer form with no dampening and no weight
+ * decay,
+ *   v'     = mu * v + Delta
+ *   Theta' = Theta - lr * (Delta + mu * v')
+ * which at mu = 0 is plain SGD, and at mu = 0, lr = 1 is weight averaging, as
+ * Section 2 says it must be.
+ */
+static void merge_range(double* theta_out, double* v_out, const float* theta, const float* v,
+                        const void* const* learner_params, int learner_dtype, const double* w,
+                        int M, size_t lo, size_t hi, double lr, double mu)
+{
+    for (size_t i = lo; i < hi; ++i) {
+        double Theta = (double)theta[i];
+        double Delta = 0.0;
+        for (int m = 0; m < M; ++m) {
+            if (w[m] == 0.0)
+                continue;
+            Delta += w[m] * (Theta - learner_value(learner_params[m], learner_dtype, i));
+        }
+        double v_new = mu * (double)v[i] + Delta;
+        double Theta_new = Theta - lr * (Delta + mu * v_new);
+        theta_out[i] = Theta_new;
+        v_out[i] = v_new;
+    }
+}
+
+static int check_merge_args(const void* theta_out, const void* v_out, const void* theta,
+                            const void* v, const void* const* learner_params, int learner_dtype,
+                            const double* w, int M, size_t n, float lr, float mu)
+{
+    if (M < 1 || M > ORACLE_MAX_LEARNERS || !learner_params)
+        return ORACLE_BAD_ARG;
+    if (learner_dtype != ORACLE_F32 && learner_dtype != ORACLE_BF16)
+        return ORACLE_BAD_ARG;
+    if (!(lr >= 0.0f) || !(mu >= 0.0f) || isinf(lr) || isinf(mu))
+        return ORACLE_BAD_ARG;
+    if (n > 0 && (!theta_out || !v_out || !theta || !v))
+        return ORACLE_BAD_ARG;
+    for (int m = 0; m < M; ++m)
+        if (w[m] != 0.0 && n > 0 && !learner_params[m])
+            return ORACLE_BAD_ARG;
+    return ORACLE_OK;
+}
+
+/*
+ * One fragment sync on one flat array: Weight, Merge, OuterOpt.
+ * theta_out / v_out receive the new global fragment and momentum in double;
+ * theta / v are not modified.  On any error nothing is written.
+ */
+int ddl_oracle_merge_fragment(double* theta_out, double* v_out, const float* theta,
+                              const float* v, const void* const* learner_params,
+                              int learner_dtype, const uint64_t* token_counts,
+                              const uint8_t* quorum_mask, int M, size_t n, float lr, float mu)
+{
+    double w[ORACLE_MAX_LEARNERS];
+    int rc = ddl_oracle_weights(token_counts, quorum_mask, M, w);
+    if (rc != ORACLE_OK)
+        return rc;
+    rc = check_merge_args(theta_out, v_out, theta, v, learner_params, learner_dtype, w, M, n, lr,
+                          mu);
+    if (rc != ORACLE_OK)
+        return rc;
+    merge_range(theta_out, v_out, theta, v, learner_params, learner_dtype, w, M, 0, n,
+                (double)lr, (double)mu);
+    return ORACLE_OK;
+}
+
+/*
+ * Same, but with the normalised weights handed in (any non-negative weights
+ * that the caller has already divided by their sum): lets a caller use the
+ * quality-weighted form or any other Weight function.
+ */
+int ddl_oracle_merge_fragment_weighted(double* theta_out, double* v_out, const float* theta,
+                                       const float* v, const void* const* learner_params,
+                                       int learner_dtype, const double* w, int M, size_t n,
+                                       float lr, float mu)
+{
+    if (!w)
+        return ORACLE_BAD_ARG;
+    int rc = check_merge_args(theta_out, v_out, theta, v, learner_params, learner_dtype, w, M, n,
+                              lr, mu);
+    if (rc != ORACLE_OK)
+        return rc;
+    merge_range(theta_out, v_out, theta, v, learner_params, learner_dtype, w, M, 0, n,
+                (double)lr, (double)mu);
+    return ORACLE_OK;
+}
+
+/*
+ * The identical scalar loop, with the element range cut into `nthreads`
+ * contiguous chunks that run on their own threads.  Elements are independent,
+ * so the result is bit-identical to ddl_oracle_merge_fragment.  Used only to
+ * time the oracle on all host cores.
+ */
+struct chunk_job {
+    double* theta_out;
+    double* v_out;
+    const float* theta;
+    const float* v;
+    const void* const* learner_params;
+    int learner_dtype;
+    const double* w;
+    int M;
+    size_t lo, hi;
+    double lr, mu;
+};
+
+static void* chunk_main(void* arg)
+{
+    struct chunk_job* j = (struct chunk_job*)arg;
+    merge_range(j->theta_out, j->v_out, j->theta, j->v, j->learner_params, j->learner_dtype, j->w,
+                j->M, j->lo, j->hi, j->lr, j->mu);
+    return NULL;
+}
+
+int ddl_oracle_merge_fragment_mt(double* theta_out, double* v_out, const float* theta,
+                                 const float* v, const void* const* learner_params,
+                                 int learner_dtype, const uint64_t* token_counts,
+                                 const uint8_t* quorum_mask, int M, size_t n, float lr, float mu,
+                                 int nthreads)
+{
+    double w[ORACLE_MAX_LEARNERS];
+    int rc = ddl_oracle_weights(token_counts, quorum_mask, M, w);
+    if (rc != ORACLE_OK)
+        return rc;
+    rc = check_merge_args(theta_out, v_out, theta, v, learner_params, learner_dtype, w, M, n, lr,
+                          mu);
+    if (rc != ORACLE_OK)
+        return rc;
+    if (nthreads < 1 || nthreads > 1024)
+        return ORACLE_BAD_ARG;
+    pthread_t* tid = (pthread_t*)malloc(sizeof(pthread_t) * (size_t)nthreads);
+    struct chunk_job* job = (struct chunk_job*)malloc(sizeof(struct chunk_job) * (size_t)nthreads);
+    if (!tid || !job) {
+        free(tid);
+        free(job);
+        return ORACLE_BAD_ARG;
+    }
+    size_t per = (n + (size_t)nthreads - 1) / (size_t)nthreads;
+    int started = 0;
+    for (int t = 0; t < nthreads; ++t) {
+        size_t lo = per * (size_t)t;
+        size_t hi = lo + per < n ? lo + per : n;
+        if (lo >= hi)
+            break;
+        struct chunk_job j = {theta_out, v_out, theta, v, learner_params, learner_dtype, w,
+                              M, lo, hi, (double)lr, (double)mu};
+        job[t] = j;
+        if (pthread_create(&tid[t], NULL, chunk_main, &job[t]) != 0) {
+            chunk_main(&job[t]); /* could not start a thread: do the chunk here */
+            tid[t] = pthread_self();
+            job[t].M = -1;
+        }
+        started = t + 1;
+    }
+    for (int t = 0; t < started; ++t)
+        if (job[t].M != -1)
+            pthread_join(tid[t], NULL);
+    free(tid);
+    free(job);
+    return ORACLE_OK;
+}

@@ -1,0 +1,459 @@
+"""Pins of the fp64 oracle to things other than itself.
+
+Every function takes an ``OracleApi`` (the oracle's Python wrapper bound to one compiled
+library) and raises AssertionError when the pin does not hold.  ``test_oracle_pins.py`` runs
+them on the real oracle; ``test_oracle_mutants.py`` runs them on deliberately broken copies
+of the oracle's source and requires that each mistake is caught by at least one pin.
+
+What the pins rest on: values worked by hand from the paper's definitions
+(tests/golden/merge_worked.json), library routines used as special cases (numpy's weighted
+average and mean, torch's SGD with nesterov=True, torch's bf16 -> fp64 cast), exact rational
+arithmetic on tiny inputs, and invariants the definitions imply.
+"""
+from __future__ import annotations
+
+import json
+import os
+from fractions import Fraction
+
+import numpy as np
+import torch
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "merge_worked.json")
+
+
+class OracleApi:
+    """The oracle's Python functions bound to a particular compiled library."""
+
+    def __init__(self, lib=None):
+        self.lib = lib or oracle.load()
+
+    def weights(self, t, q):
+        return oracle.weights(t, q, lib=self.lib)
+
+    def weights_quality(self, t, s, q):
+        return oracle.weights_quality(t, s, q, lib=self.lib)
+
+    def merge(self, theta, v, learners, t, q, lr, mu, nthreads=0):
+        return oracle.merge_fragment(theta, v, learners, t, q, lr, mu, nthreads=nthreads,
+                                     lib=self.lib)
+
+    def merge_weighted(self, theta, v, learners, w, lr, mu):
+        return oracle.merge_fragment_weighted(theta, v, learners, w, lr, mu, lib=self.lib)
+
+
+def f32(x):
+    return np.ascontiguousarray(np.asarray(x, dtype=np.float32))
+
+
+def bf16_bits(x32: np.ndarray) -> np.ndarray:
+    """fp32 -> bf16 bit patterns through torch's cast (round to nearest even)."""
+    t = torch.from_numpy(np.ascontiguousarray(x32, dtype=np.float32)).to(torch.bfloat16)
+    return t.view(torch.int16).numpy().view(np.uint16).copy()
+
+
+def bf16_to_f64(bits: np.ndarray) -> np.ndarray:
+    t = torch.from_numpy(bits.view(np.int16).copy()).view(torch.bfloat16)
+    return t.to(torch.float64).numpy()
+
+
+def _problem(seed, n=257, M=5, dtype="f32", quorum=None, v_sigma=1e-4):
+    rng = np.random.default_rng(seed)
+    theta = f32(rng.normal(0, 0.02, n))
+    v = f32(rng.normal(0, v_sigma, n)) if v_sigma else np.zeros(n, np.float32)
+    learners = [f32(theta + rng.normal(0, 1e-3, n).astype(np.float32)) for _ in range(M)]
+    if dtype == "bf16":
+        learners = [bf16_bits(x) for x in learners]
+    tokens = rng.integers(1, 1 << 22, size=M).astype(np.uint64)
+    mask = np.ones(M, np.uint8) if quorum is None else np.asarray(quorum, np.uint8)
+    return theta, v, learners, tokens, mask
+
+
+def _as_f64(learner):
+    return bf16_to_f64(learner) if learner.dtype == np.uint16 else learner.astype(np.float64)
+
+
+# --------------------------------------------------------------------------------------
+# golden, hand-worked values
+# --------------------------------------------------------------------------------------
+
+def pin_golden_worked_cases(o: OracleApi):
+    data = json.load(open(GOLDEN))
+    for c in data["cases"]:
+        n = len(c["theta"])
+        learners = [f32(x) if x is not None else f32([np.nan] * n) for x in c["learners"]]
+        w = o.weights(c["token_counts"], c["quorum_mask"])
+        assert np.array_equal(w, np.asarray(c["weights"], np.float64)), (c["name"], w)
+        th, v = o.merge(f32(c["theta"]), f32(c["v"]), learners, c["token_counts"],
+                        c["quorum_mask"], c["lr"], c["mu"])
+        assert np.array_equal(th, np.asarray(c["theta_new"], np.float64)), (c["name"], th)
+        assert np.array_equal(v, np.asarray(c["v_new"], np.float64)), (c["name"], v)
+        # Delta itself: mu = 0 makes v' = Delta
+        _, d = o.merge(f32(c["theta"]), f32(c["v"]), learners, c["token_counts"],
+                       c["quorum_mask"], c["lr"], 0.0)
+        assert np.array_equal(d, np.asarray(c["delta"], np.float64)), (c["name"], d)
+        # NULL instead of a NaN-filled buffer for absent learners
+        if any(x is None for x in c["learners"]):
+            ln = [f32(x) if x is not None else None for x in c["learners"]]
+            th2, v2 = o.merge(f32(c["theta"]), f32(c["v"]), ln, c["token_counts"],
+                              c["quorum_mask"], c["lr"], c["mu"])
+            assert np.array_equal(th2, th) and np.array_equal(v2, v)
+
+
+def pin_golden_quality_weights(o: OracleApi):
+    data = json.load(open(GOLDEN))
+    for c in data["weight_quality_cases"]:
+        w = o.weights_quality(c["token_counts"], c["step_counts"], c["quorum_mask"])
+        assert np.array_equal(w, np.asarray(c["weights"], np.float64)), w
+
+
+# --------------------------------------------------------------------------------------
+# weights
+# --------------------------------------------------------------------------------------
+
+def pin_weights_sum_to_one(o: OracleApi):
+    rng = np.random.default_rng(1)
+    for M in (1, 2, 3, 8, 16):
+        for _ in range(20):
+            t = rng.integers(0, 1 << 40, size=M).astype(np.uint64)
+            q = rng.integers(0, 2, size=M).astype(np.uint8)
+            if (t * q).sum() == 0:
+                continue
+            w = o.weights(t, q)
+            assert abs(w.sum() - 1.0) <= 4 * np.finfo(np.float64).eps
+            assert np.all(w[q == 0] == 0.0) and np.all(w >= 0.0)
+            # exact rational comparison of every weight
+            S = sum(int(a) * int(b) for a, b in zip(t, q))
+            for m in range(M):
+                exact = Fraction(int(t[m]) * int(q[m]), S)
+                assert abs(Fraction(float(w[m])) - exact) <= exact * Fraction(1, 2 ** 51)
+
+
+def pin_weights_match_numpy_average(o: OracleApi):
+    """sum_m w_m x_m is numpy's weighted average with raw weights q_m n_m."""
+    rng = np.random.default_rng(2)
+    t = rng.integers(1, 1000, size=6).astype(np.uint64)
+    q = np.array([1, 0, 1, 1, 0, 1], np.uint8)
+    x = rng.normal(size=6)
+    w = o.weights(t, q)
+    ref = np.average(x, weights=(t * q).astype(np.float64))
+    assert abs(float(w @ x) - ref) <= 1e-15 * (1 + abs(ref))
+
+
+def pin_weights_errors(o: OracleApi):
+    for t, q in (([0, 0], [1, 1]), ([5, 7], [0, 0]), ([0, 9], [1, 0])):
+        try:
+            o.weights(t, q)
+        except oracle.OracleError as e:
+            assert e.code == oracle.EMPTY_QUORUM
+        else:
+            raise AssertionError("empty quorum accepted")
+    try:
+        o.weights([1, 2], [1, 2])
+    except oracle.OracleError as e:
+        assert e.code == oracle.BAD_ARG
+    else:
+        raise AssertionError("mask value 2 accepted")
+
+
+def pin_quality_weights_reduce_to_tokens(o: OracleApi):
+    """tokens^2/steps with steps proportional to tokens is the tokens-only weight; with
+    equal steps it weights by tokens squared."""
+    t = np.array([100, 300, 50, 700], np.uint64)
+    q = np.array([1, 1, 0, 1], np.uint8)
+    w_tok = o.weights(t, q)
+    w = o.weights_quality(t, t // 50, q)     # tokens per step = 50 for all
+    assert np.allclose(w, w_tok, rtol=1e-15, atol=0)
+    w2 = o.weights_quality(t, [4, 4, 4, 4], q)
+    sq = (t.astype(np.float64) ** 2) * q
+    assert np.allclose(w2, sq / sq.sum(), rtol=1e-15, atol=0)
+
+
+# --------------------------------------------------------------------------------------
+# invariants of merge + outer step
+# --------------------------------------------------------------------------------------
+
+def pin_learners_equal_theta_gives_zero_delta(o: OracleApi):
+    theta, v, _, t, q = _problem(3, M=4)
+    learners = [theta.copy() for _ in range(4)]
+    zeros = np.zeros_like(v)
+    th, vn = o.merge(theta, zeros, learners, t, q, 0.7, 0.9)
+    assert np.array_equal(th, theta.astype(np.float64)) and np.all(vn == 0.0)
+    # with momentum present the step is pure momentum decay: v' = mu v, th' = th - lr mu v'
+    th, vn = o.merge(theta, v, learners, t, q, 0.5, 0.5)
+    assert np.array_equal(vn, 0.5 * v.astype(np.float64))
+    assert np.array_equal(th, theta.astype(np.float64) - 0.5 * (0.5 * (0.5 * v.astype(np.float64))))
+
+
+def pin_permutation_invariance(o: OracleApi):
+    theta, v, learners, t, q = _problem(4, M=6, quorum=[1, 0, 1, 1, 0, 1])
+    th0, v0 = o.merge(theta, v, learners, t, q, 0.7, 0.9)
+    rng = np.random.default_rng(40)
+    for _ in range(5):
+        p = rng.permutation(6)
+        th, vn = o.merge(theta, v, [learners[i] for i in p], t[p], q[p], 0.7, 0.9)
+        assert np.allclose(th, th0, rtol=0, atol=1e-17) and np.allclose(vn, v0, rtol=0, atol=1e-17)
+
+
+def pin_single_learner_lr1_mu0_returns_learner(o: OracleApi):
+    for dtype in ("f32", "bf16"):
+        theta, v, learners, t, _ = _problem(5, M=4, dtype=dtype)
+        for m in range(4):
+            q = np.zeros(4, np.uint8)
+            q[m] = 1
+            th, vn = o.merge(theta, v, learners, t, q, 1.0, 0.0)
+            xm = _as_f64(learners[m])
+            # Theta - (Theta - x) in fp64 of fp32-representable values is exact
+            assert np.array_equal(th, xm)
+            assert np.array_equal(vn, theta.astype(np.float64) - xm)
+
+
+def pin_exact_rational_bruteforce(o: OracleApi):
+    """Tiny inputs, exact rational arithmetic, with the merge written the other way round:
+    Delta = Theta - (weighted mean of the learners)."""
+    rng = np.random.default_rng(6)
+    for trial in range(30):
+        M = int(rng.integers(1, 4))
+        n = int(rng.integers(1, 9))
+        theta = f32(rng.integers(-64, 64, n) / 16.0)
+        v = f32(rng.integers(-64, 64, n) / 32.0)
+        learners = [f32(rng.integers(-64, 64, n) / 16.0) for _ in range(M)]
+        t = rng.integers(1, 9, size=M).astype(np.uint64)
+        q = rng.integers(0, 2, size=M).astype(np.uint8)
+        if q.sum() == 0:
+            q[0] = 1
+        lr = float(rng.integers(1, 9)) / 8.0
+        mu = float(rng.integers(0, 8)) / 8.0
+        th, vn = o.merge(theta, v, learners, t, q, lr, mu)
+        S = sum(int(a) * int(b) for a, b in zip(t, q))
+        for i in range(n):
+            mean = sum(Fraction(int(t[m]) * int(q[m]), S) * Fraction(float(learners[m][i]))
+                       for m in range(M))
+            g = Fraction(float(theta[i])) - mean
+            buf = Fraction(mu) * Fraction(float(v[i])) + g
+            p = Fraction(float(theta[i])) - Fraction(lr) * (g + Fraction(mu) * buf)
+            assert abs(Fraction(float(vn[i])) - buf) <= Fraction(1, 2 ** 44), (trial, i)
+            assert abs(Fraction(float(th[i])) - p) <= Fraction(1, 2 ** 44), (trial, i)
+
+
+def pin_zero_momentum_closed_form(o: OracleApi):
+    """v = 0: v' = Delta and Theta' = Theta - lr (1 + mu) Delta, Delta from numpy.average."""
+    theta, _, learners, t, q = _problem(7, M=2, v_sigma=0.0)
+    t = np.array([1000, 3000], np.uint64)
+    v = np.zeros_like(theta)
+    th, vn = o.merge(theta, v, learners, t, q, 0.7, 0.9)
+    L = np.stack([x.astype(np.float64) for x in learners])
+    delta = theta.astype(np.float64) - np.average(L, axis=0, weights=[0.25, 0.75])
+    lr, mu = float(np.float32(0.7)), float(np.float32(0.9))
+    assert np.allclose(vn, delta, rtol=0, atol=1e-17)
+    assert np.allclose(th, theta - lr * (1 + mu) * delta, rtol=0, atol=1e-16)
+
+
+def pin_convex_combination_bounds(o: OracleApi):
+    theta, v, learners, t, q = _problem(8, M=5, quorum=[1, 1, 0, 1, 1])
+    th, _ = o.merge(theta, v, learners, t, q, 1.0, 0.0)
+    L = np.stack([learners[m].astype(np.float64) for m in range(5) if q[m]])
+    eps = 1e-15
+    assert np.all(th >= L.min(axis=0) - eps) and np.all(th <= L.max(axis=0) + eps)
+    # and it is not just one of the learners nor theta
+    assert np.any(np.abs(th - L[0]) > 1e-6) and np.any(np.abs(th - theta) > 1e-6)
+
+
+def pin_equal_tokens_plain_mean(o: OracleApi):
+    theta, v, learners, _, q = _problem(9, M=4, quorum=[1, 1, 0, 1])
+    t = np.full(4, 12345, np.uint64)
+    th, _ = o.merge(theta, v, learners, t, q, 1.0, 0.0)
+    L = np.stack([learners[m].astype(np.float64) for m in (0, 1, 3)])
+    assert np.allclose(th, L.mean(axis=0), rtol=0, atol=1e-16)
+    # full quorum, equal counters: Eq. 2, Delta = (1/M) sum_m (Theta - theta_m)
+    q1 = np.ones(4, np.uint8)
+    _, d = o.merge(theta, np.zeros_like(v), learners, t, q1, 0.3, 0.0)
+    Lall = np.stack([x.astype(np.float64) for x in learners])
+    assert np.allclose(d, (theta.astype(np.float64)[None, :] - Lall).sum(axis=0) / 4.0,
+                       rtol=0, atol=1e-17)
+
+
+def pin_token_scaling_invariance(o: OracleApi):
+    theta, v, learners, t, q = _problem(10, M=4, quorum=[1, 0, 1, 1])
+    a = o.merge(theta, v, learners, t, q, 0.7, 0.9)
+    b = o.merge(theta, v, learners, t * np.uint64(1024), q, 0.7, 0.9)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])   # power-of-two scale: exact
+    c = o.merge(theta, v, learners, t * np.uint64(7), q, 0.7, 0.9)
+    assert np.allclose(a[0], c[0], rtol=0, atol=1e-17) and np.allclose(a[1], c[1], rtol=0, atol=1e-17)
+
+
+def pin_absent_learner_never_read(o: OracleApi):
+    theta, v, learners, t, q = _problem(11, M=5, quorum=[1, 0, 1, 0, 1])
+    ref = o.merge(theta, v, [learners[0], learners[2], learners[4]], t[[0, 2, 4]],
+                  np.ones(3, np.uint8), 0.7, 0.9)
+    poisoned = list(learners)
+    poisoned[1] = np.full_like(theta, np.nan)
+    poisoned[3] = np.full_like(theta, np.inf)
+    got = o.merge(theta, v, poisoned, t, q, 0.7, 0.9)
+    assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1])
+    poisoned[1] = None
+    poisoned[3] = None
+    got = o.merge(theta, v, poisoned, t, q, 0.7, 0.9)
+    assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1])
+    # a quorum member with a zero counter is treated the same way
+    t0 = t.copy()
+    t0[2] = 0
+    poisoned = list(learners)
+    poisoned[2] = np.full_like(theta, np.nan)
+    got = o.merge(theta, v, poisoned, t0, np.ones(5, np.uint8), 0.7, 0.9)
+    ref = o.merge(theta, v, [learners[m] for m in (0, 1, 3, 4)], t[[0, 1, 3, 4]],
+                  np.ones(4, np.uint8), 0.7, 0.9)
+    assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1])
+
+
+def pin_orthogonal_outer_gradients_norm(o: OracleApi):
+    """Exactly orthogonal outer gradients of norm R, equal weights: ||Delta|| = R / sqrt(Mq)
+    (Appendix D.2, the motivation for radial-directional averaging)."""
+    for Mq in (2, 4, 8):
+        n = 64 * Mq
+        theta = f32(np.linspace(-1, 1, n))
+        R = 0.5
+        learners = []
+        for m in range(Mq):
+            g = np.zeros(n)
+            g[m * 64:(m + 1) * 64] = R / 8.0       # 64 entries of R/8: norm R, disjoint supports
+            learners.append(f32(theta.astype(np.float64) - g))
+        _, d = o.merge(theta, np.zeros(n, np.float32), learners, [9] * Mq, [1] * Mq, 1.0, 0.0)
+        assert abs(np.linalg.norm(d) - R / np.sqrt(Mq)) <= 1e-6 * R
+
+
+def pin_split_invariance(o: OracleApi):
+    theta, v, learners, t, q = _problem(12, n=1000, M=3)
+    whole = o.merge(theta, v, learners, t, q, 0.7, 0.9)
+    for cut in (1, 333, 999):
+        a = o.merge(theta[:cut], v[:cut], [x[:cut].copy() for x in learners], t, q, 0.7, 0.9)
+        b = o.merge(theta[cut:], v[cut:], [x[cut:].copy() for x in learners], t, q, 0.7, 0.9)
+        assert np.array_equal(np.concatenate([a[0], b[0]]), whole[0])
+        assert np.array_equal(np.concatenate([a[1], b[1]]), whole[1])
+
+
+def pin_bf16_widening(o: OracleApi):
+    """Every finite bf16 bit pattern widens to the value torch's cast gives; an fp32-typed
+    learner holding bf16-representable values gives the bf16-typed result."""
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    vals = bf16_to_f64(bits)
+    finite = np.isfinite(vals)
+    bits, vals = bits[finite], vals[finite]
+    n = bits.shape[0]
+    theta = np.zeros(n, np.float32)
+    th, vn = o.merge(theta, theta, [bits], [3], [1], 1.0, 0.0)
+    assert np.array_equal(th, vals)             # Theta - (0 - x) = x
+    assert np.array_equal(vn, -vals)
+    as_f32 = vals.astype(np.float32)
+    th2, vn2 = o.merge(theta, theta, [as_f32], [3], [1], 1.0, 0.0)
+    assert np.array_equal(th2, th) and np.array_equal(vn2, vn)
+    # generic problem, both typings
+    theta, v, learners, t, q = _problem(13, M=3, dtype="bf16")
+    a = o.merge(theta, v, learners, t, q, 0.7, 0.9)
+    b = o.merge(theta, v, [bf16_to_f64(x).astype(np.float32) for x in learners], t, q, 0.7, 0.9)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def pin_linearity_shift(o: OracleApi):
+    """Moving every quorum learner by -c e moves Delta by +c e (weights sum to one)."""
+    theta, v, learners, t, q = _problem(14, n=64, M=4, quorum=[1, 1, 0, 1])
+    z = np.zeros_like(v)
+    _, d0 = o.merge(theta, z, learners, t, q, 0.5, 0.0)
+    c = 0.25
+    shifted = [f32(x.astype(np.float64) - c) if q[m] else x for m, x in enumerate(learners)]
+    _, d1 = o.merge(theta, z, shifted, t, q, 0.5, 0.0)
+    sh = np.stack([shifted[m].astype(np.float64) - learners[m].astype(np.float64)
+                   for m in range(4) if q[m]])
+    w = o.weights(t, q)[q.astype(bool)]
+    assert np.allclose(d1 - d0, -(w[:, None] * sh).sum(axis=0), rtol=0, atol=1e-16)
+    assert np.allclose(d1 - d0, c, rtol=0, atol=1e-7)
+
+
+def pin_matches_torch_sgd_nesterov(o: OracleApi):
+    """Several successive syncs of one fragment against torch.optim.SGD(nesterov=True) in
+    fp64, fed with outer gradients Theta - numpy.average(learners)."""
+    rng = np.random.default_rng(15)
+    n, M = 96, 4
+    lr, mu = 0.7, 0.9
+    lr32, mu32 = float(np.float32(lr)), float(np.float32(mu))
+    theta = f32(rng.normal(0, 0.02, n))
+    v = np.zeros(n, np.float32)
+    p = torch.nn.Parameter(torch.from_numpy(theta.astype(np.float64)))
+    opt = torch.optim.SGD([p], lr=lr32, momentum=mu32, nesterov=True)
+    th_cur, v_cur = theta.astype(np.float64), v.astype(np.float64)
+    for step in range(4):
+        q = np.array([1, step % 2, 1, 1], np.uint8)
+        t = rng.integers(1, 1 << 20, size=M).astype(np.uint64)
+        # inputs of this sync: the oracle takes fp32 state, so round the running state
+        th32, v32 = th_cur.astype(np.float32), v_cur.astype(np.float32)
+        learners = [f32(th32 + rng.normal(0, 1e-3, n).astype(np.float32)) for _ in range(M)]
+        th_new, v_new = o.merge(th32, v32, learners, t, q, lr, mu)
+        with torch.no_grad():
+            p.copy_(torch.from_numpy(th32.astype(np.float64)))
+            if step > 0:
+                opt.state[p]["momentum_buffer"].copy_(torch.from_numpy(v32.astype(np.float64)))
+        L = np.stack([x.astype(np.float64) for x in learners])
+        grad = th32.astype(np.float64) - np.average(L, axis=0, weights=(t * q).astype(np.float64))
+        p.grad = torch.from_numpy(grad)
+        opt.step()
+        assert np.allclose(th_new, p.detach().numpy(), rtol=0, atol=1e-15), step
+        assert np.allclose(v_new, opt.state[p]["momentum_buffer"].numpy(), rtol=0, atol=1e-15), step
+        th_cur, v_cur = th_new, v_new
+
+
+def pin_two_successive_syncs(o: OracleApi):
+    """Fixed learners, v0 = 0, exact dyadic values: Delta2 = Delta1 (1 - lr (1 + mu)) and
+    v2 = mu Delta1 + Delta2."""
+    theta = f32([1.0, -3.0, 0.5, 8.0])
+    learners = [f32([0.5, -2.0, 0.5, 4.0]), f32([1.5, -1.0, 2.5, 0.0])]
+    t, q = [1, 1], [1, 1]
+    lr, mu = 0.25, 0.5
+    th1, v1 = o.merge(theta, np.zeros(4, np.float32), learners, t, q, lr, mu)
+    d1 = v1
+    th2, v2 = o.merge(th1.astype(np.float32), v1.astype(np.float32), learners, t, q, lr, mu)
+    d2 = d1 * (1 - lr * (1 + mu))
+    assert np.array_equal(v2, mu * d1 + d2)
+    assert np.array_equal(th2, th1 - lr * (d2 + mu * v2))
+
+
+def pin_threads_bit_identical(o: OracleApi):
+    theta, v, learners, t, q = _problem(16, n=10007, M=4, dtype="bf16", quorum=[1, 1, 0, 1])
+    a = o.merge(theta, v, learners, t, q, 0.7, 0.9)
+    for nt in (1, 3, 8):
+        b = o.merge(theta, v, learners, t, q, 0.7, 0.9, nthreads=nt)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def pin_weighted_entry_matches(o: OracleApi):
+    theta, v, learners, t, q = _problem(17, M=4, quorum=[1, 0, 1, 1])
+    a = o.merge(theta, v, learners, t, q, 0.7, 0.9)
+    b = o.merge_weighted(theta, v, learners, o.weights(t, q), 0.7, 0.9)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def pin_merge_errors(o: OracleApi):
+    theta, v, learners, t, q = _problem(18, n=16, M=2)
+    for bad in (dict(lr=-0.1), dict(mu=-0.5), dict(lr=float("nan")), dict(mu=float("inf"))):
+        kw = dict(lr=0.7, mu=0.9)
+        kw.update(bad)
+        try:
+            o.merge(theta, v, learners, t, q, kw["lr"], kw["mu"])
+        except oracle.OracleError as e:
+            assert e.code == oracle.BAD_ARG
+        else:
+            raise AssertionError(f"accepted {bad}")
+    try:
+        o.merge(theta, v, [learners[0], None], t, q, 0.7, 0.9)   # NULL for a present learner
+    except oracle.OracleError as e:
+        assert e.code == oracle.BAD_ARG
+    else:
+        raise AssertionError("NULL present learner accepted")
+    # n = 0 is a no-op
+    e = np.zeros(0, np.float32)
+    th, vn = o.merge(e, e, [e, e], t, q, 0.7, 0.9)
+    assert th.shape == (0,) and vn.shape == (0,)
+
+
+ALL_PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_") and callable(v)]

@@ -1,0 +1,60 @@
+"""Plant one plausible mistake at a time in a copy of the oracle's source (on the CPU, never in
+the HIP path) and require that the pins notice: a dropped term, a wrong sign, a swapped
+operand, a wrong index, a missing normalisation."""
+import os
+import tempfile
+
+import pytest
+
+import oracle
+import oracle_pins
+
+SRC = open(os.path.join(os.path.dirname(oracle.__file__), "ddl_oracle.c")).read()
+
+# (name, text in the oracle, replacement)
+MUTANTS = [
+    ("delta_sign", "w[m] * (Theta - learner_value(", "w[m] * (-Theta + learner_value("),
+    ("delta_drops_theta", "w[m] * (Theta - learner_value(", "w[m] * (0.0 - learner_value("),
+    ("delta_unweighted", "Delta += w[m] * (Theta", "Delta += (Theta"),
+    ("absent_multiplied_not_skipped", "if (w[m] == 0.0)\n                continue;", ""),
+    ("momentum_dropped", "double v_new = mu * (double)v[i] + Delta;", "double v_new = Delta;"),
+    ("momentum_dampened", "double v_new = mu * (double)v[i] + Delta;",
+     "double v_new = mu * (double)v[i] + (1.0 - mu) * Delta;"),
+    ("heavy_ball_not_nesterov", "Theta - lr * (Delta + mu * v_new)", "Theta - lr * v_new"),
+    ("nesterov_uses_old_v", "Theta - lr * (Delta + mu * v_new)",
+     "Theta - lr * (Delta + mu * (double)v[i])"),
+    ("step_sign", "Theta - lr * (Delta + mu * v_new)", "Theta + lr * (Delta + mu * v_new)"),
+    ("lr_on_buffer", "double v_new = mu * (double)v[i] + Delta;",
+     "double v_new = mu * (double)v[i] + lr * Delta;"),
+    ("weights_not_normalised", "(double)token_counts[m] / S : 0.0", "(double)token_counts[m] : 0.0"),
+    ("weights_ignore_mask_in_sum", "if (quorum_mask[m])\n            S +=", "S +="),
+    ("weights_ignore_mask", "quorum_mask[m] ? (double)token_counts[m] / S : 0.0",
+     "(double)token_counts[m] / S"),
+    ("weights_uniform", "quorum_mask[m] ? (double)token_counts[m] / S : 0.0",
+     "quorum_mask[m] ? 1.0 / M : 0.0"),
+    ("bf16_shift", "(uint32_t)h << 16", "(uint32_t)h << 15"),
+    ("learner_index", "return widen_bf16(((const uint16_t*)base)[i]);",
+     "return widen_bf16(((const uint16_t*)base)[i ? i - 1 : 0]);"),
+    ("quality_tokens_only", "raw[m] = c_tok * (c_tok / (double)step_counts[m]);", "raw[m] = c_tok;"),
+    ("quality_inverted", "raw[m] = c_tok * (c_tok / (double)step_counts[m]);",
+     "raw[m] = c_tok * ((double)step_counts[m] / c_tok);"),
+    ("chunk_overlap", "size_t lo = per * (size_t)t;", "size_t lo = per * (size_t)t + (t ? 1 : 0);"),
+]
+
+
+@pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_mutant_is_caught(name, old, new):
+    assert SRC.count(old) == 1, f"mutation site for {name} not found exactly once"
+    with tempfile.TemporaryDirectory() as d:
+        src = os.path.join(d, "mutant.c")
+        out = os.path.join(d, "mutant.so")
+        open(src, "w").write(SRC.replace(old, new))
+        oracle.build(force=True, src=src, out=out, extra=["-w"])
+        api = oracle_pins.OracleApi(oracle.load(out))
+        caught = []
+        for pin in oracle_pins.ALL_PINS:
+            try:
+                pin(api)
+            except (AssertionError, oracle.OracleError):
+                caught.append(pin.__name__)
+        assert caught, f"no pin notices mutant {name}"
