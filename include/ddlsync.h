@@ -1,0 +1,209 @@
+/*
+ * ddlsync.h -- C ABI of the MI355X (gfx950) synchronizer hot path of Decoupled DiLoCo.
+ *
+ * What the library computes, for one fragment p of the model (Algorithm 2, steps "Weight",
+ * "mergeFn" and "OuterOpt"; Appendix D.2 "Direct averaging", weighted form; Section 2 for
+ * the outer optimiser):
+ *
+ *     r_m     = q_m * n_m                       raw weight: token counter of learner m if it
+ *                                               is in the reporting set M_t, else 0
+ *     w_m     = r_m / sum_k r_k                 normalised over the quorum
+ *     Delta_i = sum_m w_m (Theta_i - theta_{m,i})      outer gradient, old global minus learner
+ *     v_i     <- mu v_i + Delta_i                       SGD with Nesterov momentum,
+ *     Theta_i <- Theta_i - lr (Delta_i + mu v_i)        buffer form, v_i being the new buffer
+ *
+ * Theta (the global fragment) and v (its momentum buffer) are fp32 arrays in device memory
+ * and are updated in place by one fused pass; learner fragments are bf16 or fp32 device
+ * arrays that are read exactly once, and only if the learner contributes (q_m = 1 and
+ * n_m > 0).  A learner that does not contribute is never dereferenced: its pointer may be
+ * NULL, dangling, or point at NaNs (Section 4, "Syncer worker": an absent learner takes part
+ * in the same Merge with weight 0).
+ *
+ * Conventions common to all entry points
+ *   - "host" / "device" in a parameter comment says where the memory lives.  The caller owns
+ *     every buffer.  Host arrays are read before the call returns; device buffers must stay
+ *     valid until the stream has run the enqueued work.
+ *   - Calls only enqueue work on `hip_stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream) and return; they do not wait for the GPU.
+ *   - Argument errors are detected before anything is enqueued: on any status other than
+ *     DDL_OK, Theta and v of every fragment in the call are untouched.
+ *   - Theta and v need 4-byte alignment, learner arrays the natural alignment of their
+ *     element.  Arrays whose base addresses are all 16-byte aligned take 128-bit vector
+ *     accesses; anything else is handled by an element-wise path with the same results.
+ *   - Theta and v ranges must not overlap each other nor any contributing learner range
+ *     (DDL_ERR_ALIAS); learner ranges may overlap one another.
+ *   - Entry points may be called from several host threads; calls that touch the same Theta
+ *     or v must be ordered by the caller (same stream, or events).
+ *   - lr and mu must be finite and >= 0.
+ */
+#ifndef DDLSYNC_H
+#define DDLSYNC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Entry points are the library's only exported symbols. */
+#define DDL_API __attribute__((visibility("default")))
+
+typedef enum {
+    DDL_OK = 0,
+    DDL_ERR_INVALID_ARG = 1,  /* NULL where data is needed, M out of range, mask not 0/1, ...  */
+    DDL_ERR_EMPTY_QUORUM = 2, /* sum_k q_k n_k == 0: no merge is defined                        */
+    DDL_ERR_ALIAS = 3,        /* an output range overlaps another range of the call             */
+    DDL_ERR_RUNTIME = 4       /* a HIP call failed (see ddl_last_error_message)                 */
+} ddl_status;
+
+typedef enum { DDL_F32 = 0, DDL_BF16 = 1 } ddl_dtype;
+
+/* The paper runs M in {2, 4, 8, 16} (Tables 1 and 11). */
+#define DDL_MAX_LEARNERS 16
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+DDL_API int ddl_version(void);
+
+/* Static string for a status code. */
+DDL_API const char* ddl_status_string(ddl_status s);
+
+/* Text of the last DDL_ERR_RUNTIME on the calling thread ("" if none). Thread-local storage
+ * owned by the library, valid until the thread's next failing call. */
+DDL_API const char* ddl_last_error_message(void);
+
+/*
+ * Weight, tokens-only form (Algorithm 2 "Weight"; normalisation as in the denominator of the
+ * weighted merge, Appendix D.2): w_out[m] = q_m n_m / sum_k q_k n_k, in fp64.
+ * token_counts, quorum_mask, w_out: host arrays of M entries.  quorum_mask entries are 0 or 1.
+ * Errors: INVALID_ARG (NULL, M < 1, M > DDL_MAX_LEARNERS, mask entry > 1), EMPTY_QUORUM.
+ */
+DDL_API ddl_status ddl_compute_weights(const uint64_t* token_counts, const uint8_t* quorum_mask, int M,
+                               double* w_out);
+
+/*
+ * The paper's own Weight function (Section 3.2): raw weight c_tokens * (c_tokens / c_steps),
+ * "quantity times quality", zero for learners outside the quorum, normalised over the quorum.
+ * A quorum member with c_steps = 0 and c_tokens = 0 gets weight 0; c_steps = 0 with
+ * c_tokens > 0 is INVALID_ARG.  All arrays: host, M entries.
+ */
+DDL_API ddl_status ddl_compute_weights_quality(const uint64_t* token_counts, const uint64_t* step_counts,
+                                       const uint8_t* quorum_mask, int M, double* w_out);
+
+/*
+ * One fragment held as ONE flat array: Weight, Merge and OuterOpt as defined at the top of
+ * this file (Algorithm 2, steps Weight / mergeFn / OuterOpt).
+ *
+ *   theta, v        device, n fp32 elements each, updated in place
+ *   learner_params  HOST array of M DEVICE pointers, learner m's copy of the fragment, n
+ *                   elements of learner_dtype; entries of non-contributing learners are
+ *                   never dereferenced
+ *   token_counts    host, M entries: tokens learner m processed since its last sync of this
+ *                   fragment (Algorithm 1's c^tokens)
+ *   quorum_mask     host, M entries, 1 if learner m is in the reporting set M_t
+ *   n               elements; n == 0 is DDL_OK and enqueues nothing
+ *
+ * Everything the kernel needs travels in its argument block: no device allocation, no copy.
+ */
+DDL_API ddl_status ddl_merge_fragment(float* theta, float* v, const void* const* learner_params,
+                              ddl_dtype learner_dtype, const uint64_t* token_counts,
+                              const uint8_t* quorum_mask, int M, size_t n, float lr, float mu,
+                              void* hip_stream);
+
+/*
+ * As ddl_merge_fragment, with normalised weights supplied by the caller instead of token
+ * counters and mask (for the quantity-times-quality Weight function or any other):
+ * weights is a host array of M non-negative finite fp64 values with a positive sum; they are
+ * divided by their sum in fp64 before use.  w_m == 0 marks a non-contributing learner.
+ */
+DDL_API ddl_status ddl_merge_fragment_weighted(float* theta, float* v, const void* const* learner_params,
+                                       ddl_dtype learner_dtype, const double* weights, int M,
+                                       size_t n, float lr, float mu, void* hip_stream);
+
+/*
+ * A fragment as the paper forms it: a set of whole tensors (Section 5.1 and Appendix C,
+ * balanced tensor fragmentation), each tensor its own flat array ("segment").  All segments of
+ * a fragment share the fragment's counters, mask, lr and mu (per-fragment counters c_{m,p},
+ * Section 3.1).
+ */
+typedef struct ddl_segment {
+    float* theta;                      /* device, n fp32 elements, updated in place            */
+    float* v;                          /* device, n fp32 elements, updated in place            */
+    const void* const* learner_params; /* HOST array of M DEVICE pointers (M of the fragment)  */
+    size_t n;                          /* elements in this tensor; 0 is allowed                */
+} ddl_segment;
+
+typedef struct ddl_fragment {
+    const ddl_segment* segs;      /* host array of num_segs segments                           */
+    int num_segs;                 /* >= 0                                                      */
+    ddl_dtype learner_dtype;      /* element type of every learner array of this fragment     */
+    const uint64_t* token_counts; /* host, M entries                                           */
+    const uint8_t* quorum_mask;   /* host, M entries of 0/1                                    */
+    int M;                        /* 1 .. DDL_MAX_LEARNERS                                     */
+    float lr, mu;                 /* outer learning rate and momentum of this fragment         */
+} ddl_fragment;
+
+/*
+ * Batched streaming variant: merge num_frags fragments, each made of several tensors and each
+ * with its own quorum, counters, lr and mu, as one piece of enqueued work (Section 5.1: one
+ * fragment is synchronised per training step and two are in flight; small tensors such as MoE
+ * experts and routers must still fill the GPU).  Equivalent to calling ddl_merge_fragment on
+ * every segment of every fragment; fragments of one call must be distinct (no Theta or v
+ * range may appear twice: DDL_ERR_ALIAS).
+ *
+ * The segment descriptors are staged through a small library-owned, lazily grown pinned-host
+ * and device buffer ring; a call may therefore allocate (first calls, or growth) and may wait
+ * for a previous call that still uses the ring slot it needs.  Not capturable in a HIP graph.
+ */
+DDL_API ddl_status ddl_merge_batch(const ddl_fragment* frags, int num_frags, void* hip_stream);
+
+/*
+ * Resident plan: the same batched merge for a syncer whose buffers persist across syncs
+ * (Section 4, "Syncer worker": the syncer keeps the global parameters and the outer optimiser
+ * state, and one shard per learner persists even while the learner is away).  The segment
+ * descriptors of ALL fragments of the model are built and uploaded once; each sync then only
+ * passes the per-sync inputs of the fragments that are due, and enqueues kernels with no
+ * allocation and no copy.
+ *
+ * ddl_plan_create reads frags[i].segs / num_segs / learner_dtype / M; token_counts,
+ * quorum_mask, lr and mu of the fragments are ignored there (may be NULL / 0).  Every learner
+ * pointer must be valid device memory or NULL.  The plan is bound to the device that is
+ * current at creation.  *plan_out is NULL on error.
+ */
+typedef struct ddl_plan ddl_plan;
+
+typedef struct ddl_sync {
+    int fragment;                 /* index into the plan's fragments                           */
+    const uint64_t* token_counts; /* host, M entries (M of that fragment)                      */
+    const uint8_t* quorum_mask;   /* host, M entries of 0/1                                    */
+    float lr, mu;
+} ddl_sync;
+
+DDL_API ddl_status ddl_plan_create(const ddl_fragment* frags, int num_frags, ddl_plan** plan_out);
+
+/* Merge the fragments named by syncs[0..count) (distinct fragment indices). A contributing
+ * learner whose pointer was NULL at plan creation is INVALID_ARG. */
+DDL_API ddl_status ddl_plan_merge(ddl_plan* plan, const ddl_sync* syncs, int count, void* hip_stream);
+
+/* Frees the plan's device table. The caller must first make sure no enqueued merge of this
+ * plan is still running. NULL is a no-op. */
+DDL_API ddl_status ddl_plan_destroy(ddl_plan* plan);
+
+/* Number of fragments / total elements of a plan (0 for NULL). */
+DDL_API int ddl_plan_num_fragments(const ddl_plan* plan);
+DDL_API size_t ddl_plan_num_elements(const ddl_plan* plan);
+
+/*
+ * Launch-shape knobs, for measurement.  Names: "tile_elems" (elements per work tile, a
+ * multiple of 8192, default chosen by the library), "blocks_per_cu" (0: one workgroup per
+ * tile; k > 0: a grid of k * #CU workgroups that stride over the tiles).  Affects later calls
+ * and plans created later.  Unknown name or bad value: INVALID_ARG.  ddl_get_option writes
+ * the current value.
+ */
+DDL_API ddl_status ddl_set_option(const char* name, long value);
+DDL_API ddl_status ddl_get_option(const char* name, long* value_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DDLSYNC_H */

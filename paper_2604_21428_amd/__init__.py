@@ -1,0 +1,324 @@
+"""Python binding of libddlsync -- the MI355X synchronizer hot path of Decoupled DiLoCo.
+
+Argument marshalling only: every step of the path (weights, quorum compaction, merge, outer
+Nesterov step) runs inside the C-ABI library declared in ``include/ddlsync.h``; the function
+names here mirror its entry points.  PyTorch supplies device memory and streams, nothing
+else.  There is no fallback: if the library has not been built the import fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libddlsync.so")
+
+DDL_OK, DDL_ERR_INVALID_ARG, DDL_ERR_EMPTY_QUORUM, DDL_ERR_ALIAS, DDL_ERR_RUNTIME = range(5)
+DDL_F32, DDL_BF16 = 0, 1
+DDL_MAX_LEARNERS = 16
+
+
+class DdlError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = _lib.ddl_status_string(status).decode()
+        if status == DDL_ERR_RUNTIME:
+            msg += ": " + _lib.ddl_last_error_message().decode()
+        super().__init__(f"{where}: {msg}")
+
+
+class _Segment(ctypes.Structure):
+    _fields_ = [("theta", ctypes.c_void_p), ("v", ctypes.c_void_p),
+                ("learner_params", ctypes.POINTER(ctypes.c_void_p)), ("n", ctypes.c_size_t)]
+
+
+class _Fragment(ctypes.Structure):
+    _fields_ = [("segs", ctypes.POINTER(_Segment)), ("num_segs", ctypes.c_int),
+                ("learner_dtype", ctypes.c_int),
+                ("token_counts", ctypes.POINTER(ctypes.c_uint64)),
+                ("quorum_mask", ctypes.POINTER(ctypes.c_uint8)), ("M", ctypes.c_int),
+                ("lr", ctypes.c_float), ("mu", ctypes.c_float)]
+
+
+class _Sync(ctypes.Structure):
+    _fields_ = [("fragment", ctypes.c_int), ("token_counts", ctypes.POINTER(ctypes.c_uint64)),
+                ("quorum_mask", ctypes.POINTER(ctypes.c_uint8)), ("lr", ctypes.c_float),
+                ("mu", ctypes.c_float)]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it first (python -m paper_2604_21428_amd.build, or "
+            "__graft_entry__.build()). There is no non-HIP fallback.")
+    lib = ctypes.CDLL(LIB_PATH)
+    u64p, u8p = ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint8)
+    f64p, vpp = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_void_p)
+    lib.ddl_version.restype = ctypes.c_int
+    lib.ddl_status_string.argtypes = [ctypes.c_int]
+    lib.ddl_status_string.restype = ctypes.c_char_p
+    lib.ddl_last_error_message.restype = ctypes.c_char_p
+    lib.ddl_compute_weights.argtypes = [u64p, u8p, ctypes.c_int, f64p]
+    lib.ddl_compute_weights_quality.argtypes = [u64p, u64p, u8p, ctypes.c_int, f64p]
+    lib.ddl_merge_fragment.argtypes = [ctypes.c_void_p, ctypes.c_void_p, vpp, ctypes.c_int, u64p,
+                                       u8p, ctypes.c_int, ctypes.c_size_t, ctypes.c_float,
+                                       ctypes.c_float, ctypes.c_void_p]
+    lib.ddl_merge_fragment_weighted.argtypes = [ctypes.c_void_p, ctypes.c_void_p, vpp,
+                                                ctypes.c_int, f64p, ctypes.c_int, ctypes.c_size_t,
+                                                ctypes.c_float, ctypes.c_float, ctypes.c_void_p]
+    lib.ddl_merge_batch.argtypes = [ctypes.POINTER(_Fragment), ctypes.c_int, ctypes.c_void_p]
+    lib.ddl_plan_create.argtypes = [ctypes.POINTER(_Fragment), ctypes.c_int,
+                                    ctypes.POINTER(ctypes.c_void_p)]
+    lib.ddl_plan_merge.argtypes = [ctypes.c_void_p, ctypes.POINTER(_Sync), ctypes.c_int,
+                                   ctypes.c_void_p]
+    lib.ddl_plan_destroy.argtypes = [ctypes.c_void_p]
+    lib.ddl_plan_num_fragments.argtypes = [ctypes.c_void_p]
+    lib.ddl_plan_num_fragments.restype = ctypes.c_int
+    lib.ddl_plan_num_elements.argtypes = [ctypes.c_void_p]
+    lib.ddl_plan_num_elements.restype = ctypes.c_size_t
+    lib.ddl_set_option.argtypes = [ctypes.c_char_p, ctypes.c_long]
+    lib.ddl_get_option.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_long)]
+    for name in ("ddl_compute_weights", "ddl_compute_weights_quality", "ddl_merge_fragment",
+                 "ddl_merge_fragment_weighted", "ddl_merge_batch", "ddl_plan_create",
+                 "ddl_plan_merge", "ddl_plan_destroy", "ddl_set_option", "ddl_get_option"):
+        getattr(lib, name).restype = ctypes.c_int
+    return lib
+
+
+_lib = _load()
+
+
+def _check(status: int, where: str) -> None:
+    if status != DDL_OK:
+        raise DdlError(status, where)
+
+
+def _u64(xs, M: Optional[int] = None):
+    xs = [int(x) for x in xs]
+    if M is not None and len(xs) != M:
+        raise ValueError(f"expected {M} entries, got {len(xs)}")
+    return (ctypes.c_uint64 * len(xs))(*xs)
+
+
+def _u8(xs, M: Optional[int] = None):
+    xs = [int(x) for x in xs]
+    if M is not None and len(xs) != M:
+        raise ValueError(f"expected {M} entries, got {len(xs)}")
+    return (ctypes.c_uint8 * len(xs))(*xs)
+
+
+def _stream_handle(stream) -> Optional[int]:
+    """hipStream_t of a torch stream (None: torch's current stream)."""
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dtype_code(t: torch.dtype) -> int:
+    if t == torch.float32:
+        return DDL_F32
+    if t == torch.bfloat16:
+        return DDL_BF16
+    raise TypeError(f"learner dtype {t} not supported (float32 or bfloat16)")
+
+
+def _state_ptr(t: torch.Tensor, what: str) -> int:
+    if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous():
+        raise TypeError(f"{what} must be a contiguous float32 device tensor")
+    return t.data_ptr()
+
+
+def _learner_table(learners: Sequence[Optional[torch.Tensor]], n: int, dtype_code=None):
+    """(ctypes pointer table, dtype code).  None entries become NULL."""
+    M = len(learners)
+    table = (ctypes.c_void_p * M)()
+    for m, x in enumerate(learners):
+        if x is None:
+            table[m] = None
+            continue
+        if not x.is_cuda or not x.is_contiguous() or x.numel() != n:
+            raise TypeError(f"learner {m}: need a contiguous device tensor of {n} elements")
+        code = _dtype_code(x.dtype)
+        if dtype_code is not None and code != dtype_code:
+            raise TypeError("all learners of a fragment share one dtype")
+        dtype_code = code
+        table[m] = x.data_ptr()
+    return table, (DDL_F32 if dtype_code is None else dtype_code)
+
+
+def version() -> int:
+    return _lib.ddl_version()
+
+
+def compute_weights(token_counts, quorum_mask) -> List[float]:
+    """ddl_compute_weights: w_m = q_m n_m / sum_k q_k n_k (fp64, host)."""
+    M = len(token_counts)
+    out = (ctypes.c_double * M)()
+    _check(_lib.ddl_compute_weights(_u64(token_counts), _u8(quorum_mask, M), M, out),
+           "ddl_compute_weights")
+    return list(out)
+
+
+def compute_weights_quality(token_counts, step_counts, quorum_mask) -> List[float]:
+    """ddl_compute_weights_quality: raw weight tokens * (tokens / steps), normalised."""
+    M = len(token_counts)
+    out = (ctypes.c_double * M)()
+    _check(_lib.ddl_compute_weights_quality(_u64(token_counts), _u64(step_counts, M),
+                                            _u8(quorum_mask, M), M, out),
+           "ddl_compute_weights_quality")
+    return list(out)
+
+
+def merge_fragment(theta: torch.Tensor, v: torch.Tensor,
+                   learner_params: Sequence[Optional[torch.Tensor]], token_counts, quorum_mask,
+                   lr: float, mu: float, stream=None, learner_dtype=None) -> None:
+    """ddl_merge_fragment: in-place sync of one flat fragment on ``stream``."""
+    n = theta.numel()
+    if v.numel() != n:
+        raise ValueError("theta and v differ in size")
+    M = len(learner_params)
+    table, code = _learner_table(learner_params, n,
+                                 None if learner_dtype is None else _dtype_code(learner_dtype))
+    _check(_lib.ddl_merge_fragment(_state_ptr(theta, "theta"), _state_ptr(v, "v"), table, code,
+                                   _u64(token_counts, M), _u8(quorum_mask, M), M, n, lr, mu,
+                                   _stream_handle(stream)), "ddl_merge_fragment")
+
+
+def merge_fragment_weighted(theta: torch.Tensor, v: torch.Tensor,
+                            learner_params: Sequence[Optional[torch.Tensor]], weights,
+                            lr: float, mu: float, stream=None, learner_dtype=None) -> None:
+    """ddl_merge_fragment_weighted: as merge_fragment with caller-supplied weights."""
+    n = theta.numel()
+    if v.numel() != n:
+        raise ValueError("theta and v differ in size")
+    M = len(learner_params)
+    if len(weights) != M:
+        raise ValueError("one weight per learner")
+    table, code = _learner_table(learner_params, n,
+                                 None if learner_dtype is None else _dtype_code(learner_dtype))
+    w = (ctypes.c_double * M)(*[float(x) for x in weights])
+    _check(_lib.ddl_merge_fragment_weighted(_state_ptr(theta, "theta"), _state_ptr(v, "v"), table,
+                                            code, w, M, n, lr, mu, _stream_handle(stream)),
+           "ddl_merge_fragment_weighted")
+
+
+class Fragment:
+    """Marshalled ddl_fragment: a list of (theta, v, learners) tensor triples that share one
+    quorum.  Keeps the ctypes arrays (and the tensors) alive."""
+
+    def __init__(self, segments, token_counts=None, quorum_mask=None, lr: float = 0.0,
+                 mu: float = 0.0, M: Optional[int] = None, learner_dtype=None):
+        self.tensors = list(segments)
+        if M is None:
+            if not self.tensors:
+                raise ValueError("M is needed for a fragment without segments")
+            M = len(self.tensors[0][2])
+        self.M = M
+        code = None if learner_dtype is None else _dtype_code(learner_dtype)
+        self._tables = []
+        self._segs = (_Segment * max(1, len(self.tensors)))()
+        for i, (theta, v, learners) in enumerate(self.tensors):
+            if len(learners) != M:
+                raise ValueError("every segment of a fragment has M learner entries")
+            n = theta.numel()
+            if v.numel() != n:
+                raise ValueError("theta and v differ in size")
+            table, code = _learner_table(learners, n, code)
+            self._tables.append(table)
+            self._segs[i].theta = _state_ptr(theta, "theta")
+            self._segs[i].v = _state_ptr(v, "v")
+            self._segs[i].learner_params = ctypes.cast(table, ctypes.POINTER(ctypes.c_void_p))
+            self._segs[i].n = n
+        self.dtype_code = DDL_F32 if code is None else code
+        self._tok = _u64(token_counts, M) if token_counts is not None else None
+        self._mask = _u8(quorum_mask, M) if quorum_mask is not None else None
+        self.lr, self.mu = float(lr), float(mu)
+
+    def fill(self, f: _Fragment) -> None:
+        f.segs = ctypes.cast(self._segs, ctypes.POINTER(_Segment))
+        f.num_segs = len(self.tensors)
+        f.learner_dtype = self.dtype_code
+        f.token_counts = (ctypes.cast(self._tok, ctypes.POINTER(ctypes.c_uint64))
+                          if self._tok is not None else None)
+        f.quorum_mask = (ctypes.cast(self._mask, ctypes.POINTER(ctypes.c_uint8))
+                         if self._mask is not None else None)
+        f.M = self.M
+        f.lr, f.mu = self.lr, self.mu
+
+
+def _fragment_array(frags: Sequence[Fragment]):
+    arr = (_Fragment * max(1, len(frags)))()
+    for i, f in enumerate(frags):
+        f.fill(arr[i])
+    return arr
+
+
+def merge_batch(frags: Sequence[Fragment], stream=None) -> None:
+    """ddl_merge_batch: sync several fragments, each a set of tensors, as one enqueue."""
+    arr = _fragment_array(frags)
+    _check(_lib.ddl_merge_batch(arr, len(frags), _stream_handle(stream)), "ddl_merge_batch")
+
+
+class Plan:
+    """ddl_plan_*: resident descriptors of all fragments of a model; ``merge`` passes only the
+    per-sync inputs of the fragments that are due."""
+
+    def __init__(self, frags: Sequence[Fragment]):
+        self._frags = list(frags)           # keeps tensors alive
+        arr = _fragment_array(self._frags)
+        self._h = ctypes.c_void_p()
+        _check(_lib.ddl_plan_create(arr, len(self._frags), ctypes.byref(self._h)),
+               "ddl_plan_create")
+
+    @property
+    def num_fragments(self) -> int:
+        return _lib.ddl_plan_num_fragments(self._h)
+
+    @property
+    def num_elements(self) -> int:
+        return _lib.ddl_plan_num_elements(self._h)
+
+    def prepare(self, syncs):
+        """Marshal [(fragment, token_counts, quorum_mask, lr, mu), ...] once; the result can
+        be passed to ``merge`` repeatedly."""
+        arr = (_Sync * max(1, len(syncs)))()
+        keep = []
+        for i, (frag, tok, mask, lr, mu) in enumerate(syncs):
+            M = self._frags[frag].M if 0 <= frag < len(self._frags) else len(tok)
+            t, q = _u64(tok, M), _u8(mask, M)
+            keep += [t, q]
+            arr[i].fragment = frag
+            arr[i].token_counts = ctypes.cast(t, ctypes.POINTER(ctypes.c_uint64))
+            arr[i].quorum_mask = ctypes.cast(q, ctypes.POINTER(ctypes.c_uint8))
+            arr[i].lr, arr[i].mu = lr, mu
+        return (arr, len(syncs), keep)
+
+    def merge(self, syncs, stream=None) -> None:
+        if not (isinstance(syncs, tuple) and len(syncs) == 3 and isinstance(syncs[1], int)):
+            syncs = self.prepare(syncs)
+        arr, count, _keep = syncs
+        _check(_lib.ddl_plan_merge(self._h, arr, count, _stream_handle(stream)), "ddl_plan_merge")
+
+    def destroy(self) -> None:
+        if self._h:
+            _check(_lib.ddl_plan_destroy(self._h), "ddl_plan_destroy")
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def set_option(name: str, value: int) -> None:
+    _check(_lib.ddl_set_option(name.encode(), value), f"ddl_set_option({name})")
+
+
+def get_option(name: str) -> int:
+    out = ctypes.c_long()
+    _check(_lib.ddl_get_option(name.encode(), ctypes.byref(out)), f"ddl_get_option({name})")
+    return out.value

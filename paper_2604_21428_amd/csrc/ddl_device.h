@@ -1,0 +1,55 @@
+// Structures shared by the host side of libddlsync and its gfx950 kernels.
+//
+// A launch works on "tiles": fixed-size element ranges of the tensors ("segments") of up to
+// DDL_MAX_ITEMS fragments that share learner dtype and number of contributing learners.
+// Segment descriptors live in device memory (or, for the single flat fragment, inside the
+// kernel argument block); everything that changes per sync -- weights, which learners
+// contribute, lr, mu -- travels in the kernel argument block, i.e. in constant memory that
+// the wave reads with scalar loads.
+#pragma once
+#include <stdint.h>
+
+#define DDL_MAXL 16         // learners per fragment, = DDL_MAX_LEARNERS of the public header
+#define DDL_MAX_ITEMS 8     // fragments per launch
+#define DDL_BLOCK 256       // threads per workgroup: 4 wavefronts of 64
+#define DDL_TILE_QUANTUM 8192  // tile sizes are multiples of this many elements
+
+struct DdlSegDesc {
+    float* theta;                   // n fp32, read and written
+    float* v;                       // n fp32, read and written
+    const void* learner[DDL_MAXL];  // learner m's copy (bf16 or fp32), read if it contributes
+    uint64_t n;                     // elements (> 0)
+    uint32_t tile_begin;            // first tile of this segment within its fragment
+    uint16_t learner_aligned;       // bit m: learner[m] is 16-byte aligned
+    uint8_t base_aligned;           // theta and v are 16-byte aligned
+    uint8_t pad;
+};
+static_assert(sizeof(DdlSegDesc) == 160, "descriptor layout");
+
+struct DdlItem {
+    uint32_t seg_begin;     // first descriptor of the fragment in the table
+    uint32_t num_segs;      // its number of (non-empty) segments
+    uint32_t tile_off;      // first tile of the fragment within this launch
+    uint32_t present_bits;  // bit m: learner m contributes
+    float w[DDL_MAXL];      // normalised weights of the contributing learners, compacted
+    uint8_t idx[DDL_MAXL];  // learner index of compacted entry j
+    float lr, mu;
+    uint32_t pad[2];
+};
+static_assert(sizeof(DdlItem) == 112, "item layout");
+
+struct DdlLaunchArgs {
+    const DdlSegDesc* segs;  // device table (unused by the flat variant)
+    uint32_t total_tiles;
+    uint32_t tile_elems;     // multiple of DDL_TILE_QUANTUM
+    int32_t num_items;
+    int32_t pad;
+    DdlItem item[DDL_MAX_ITEMS];
+    DdlSegDesc flat;         // the one segment of the flat variant
+};
+static_assert(sizeof(DdlLaunchArgs) <= 4096, "kernel argument block limit");
+
+// Launches the merge kernel specialised for (learner dtype, contributing learners, flat or
+// table).  dtype: 0 fp32, 1 bf16 (values of ddl_dtype).  Returns a hipError_t as int.
+int ddl_launch_merge(int dtype, int Mq, bool flat, uint32_t grid, void* stream,
+                     const DdlLaunchArgs& args);

@@ -1,0 +1,639 @@
+// Host side of libddlsync: the C ABI of include/ddlsync.h.  Validates arguments, computes the
+// quorum weights once per merge in fp64 (Algorithm 2, step "Weight"), drops learners that do
+// not contribute, lays the fragments' tensors out as tiles, and enqueues the gfx950 kernels.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/ddlsync.h"
+#include "ddl_device.h"
+
+static_assert(DDL_MAXL == DDL_MAX_LEARNERS, "device and public learner limits differ");
+
+namespace {
+
+thread_local std::string g_err;
+
+ddl_status runtime_error(hipError_t e, const char* what)
+{
+    g_err = std::string(what) + ": " + hipGetErrorString(e);
+    return DDL_ERR_RUNTIME;
+}
+
+#define DDL_HIP(call)                                              \
+    do {                                                           \
+        hipError_t e__ = (call);                                   \
+        if (e__ != hipSuccess) return runtime_error(e__, #call);   \
+    } while (0)
+
+// ------------------------------------------------------------------------------------------
+// options and per-device state
+// ------------------------------------------------------------------------------------------
+std::mutex g_mu;  // guards options, device state and the staging ring
+long g_tile_elems = 2 * DDL_TILE_QUANTUM;
+long g_blocks_per_cu = 0;
+
+constexpr int kMaxDevices = 16;
+constexpr int kSlots = 4;
+
+struct Slot {
+    void* host = nullptr;  // pinned
+    void* dev = nullptr;
+    size_t cap = 0;
+    hipEvent_t done = nullptr;
+    bool pending = false;
+};
+
+struct DeviceState {
+    bool init = false;
+    int cus = 0;
+    Slot slot[kSlots];
+    unsigned next = 0;
+};
+DeviceState g_dev[kMaxDevices];
+
+ddl_status device_state(DeviceState** out)
+{
+    int dev = 0;
+    DDL_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) {
+        g_err = "device index out of range";
+        return DDL_ERR_RUNTIME;
+    }
+    DeviceState& s = g_dev[dev];
+    if (!s.init) {
+        int cus = 0;
+        DDL_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        s.cus = cus > 0 ? cus : 256;
+        s.init = true;
+    }
+    *out = &s;
+    return DDL_OK;
+}
+
+uint32_t grid_for(uint32_t total_tiles, const DeviceState& ds)
+{
+    if (g_blocks_per_cu <= 0) return total_tiles;
+    const uint64_t cap = (uint64_t)g_blocks_per_cu * (uint64_t)ds.cus;
+    return (uint32_t)std::min<uint64_t>(total_tiles, cap);
+}
+
+// ------------------------------------------------------------------------------------------
+// weights
+// ------------------------------------------------------------------------------------------
+struct Quorum {
+    int Mq = 0;
+    float w[DDL_MAXL];
+    uint8_t idx[DDL_MAXL];
+    uint32_t present_bits = 0;
+};
+
+bool finite_nonneg(float x) { return std::isfinite(x) && x >= 0.0f; }
+
+ddl_status weights_tokens(const uint64_t* t, const uint8_t* q, int M, double* w)
+{
+    if (!t || !q || !w || M < 1 || M > DDL_MAX_LEARNERS) return DDL_ERR_INVALID_ARG;
+    unsigned __int128 S = 0;  // exact: M counters below 2^64
+    for (int m = 0; m < M; ++m) {
+        if (q[m] > 1) return DDL_ERR_INVALID_ARG;
+        if (q[m]) S += t[m];
+    }
+    if (S == 0) return DDL_ERR_EMPTY_QUORUM;
+    const double Sd = (double)S;
+    for (int m = 0; m < M; ++m) w[m] = q[m] ? (double)t[m] / Sd : 0.0;
+    return DDL_OK;
+}
+
+ddl_status weights_quality(const uint64_t* t, const uint64_t* s, const uint8_t* q, int M, double* w)
+{
+    if (!t || !s || !q || !w || M < 1 || M > DDL_MAX_LEARNERS) return DDL_ERR_INVALID_ARG;
+    double raw[DDL_MAXL];
+    double S = 0.0;
+    for (int m = 0; m < M; ++m) {
+        raw[m] = 0.0;
+        if (q[m] > 1) return DDL_ERR_INVALID_ARG;
+        if (!q[m]) continue;
+        if (s[m] == 0) {
+            if (t[m] != 0) return DDL_ERR_INVALID_ARG;
+            continue;
+        }
+        const double tok = (double)t[m];
+        raw[m] = tok * (tok / (double)s[m]);
+        S += raw[m];
+    }
+    if (S == 0.0) return DDL_ERR_EMPTY_QUORUM;
+    for (int m = 0; m < M; ++m) w[m] = raw[m] / S;
+    return DDL_OK;
+}
+
+// Caller-supplied weights: non-negative, finite, positive sum; normalised here.
+ddl_status weights_given(const double* in, int M, double* w)
+{
+    if (!in || M < 1 || M > DDL_MAX_LEARNERS) return DDL_ERR_INVALID_ARG;
+    double S = 0.0;
+    for (int m = 0; m < M; ++m) {
+        if (!std::isfinite(in[m]) || in[m] < 0.0) return DDL_ERR_INVALID_ARG;
+        S += in[m];
+    }
+    if (!(S > 0.0) || !std::isfinite(S)) return DDL_ERR_EMPTY_QUORUM;
+    for (int m = 0; m < M; ++m) w[m] = in[m] / S;
+    return DDL_OK;
+}
+
+// Drop learners of weight zero; round the rest once to fp32 for the device.
+void compact(const double* w, int M, Quorum& out)
+{
+    out.Mq = 0;
+    out.present_bits = 0;
+    for (int m = 0; m < M; ++m) {
+        if (w[m] > 0.0) {
+            out.w[out.Mq] = (float)w[m];
+            out.idx[out.Mq] = (uint8_t)m;
+            out.present_bits |= 1u << m;
+            ++out.Mq;
+        }
+    }
+    for (int j = out.Mq; j < DDL_MAXL; ++j) {
+        out.w[j] = 0.0f;
+        out.idx[j] = 0;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// overlap check: an output range (Theta, v) may overlap nothing; inputs may overlap inputs
+// ------------------------------------------------------------------------------------------
+struct Range {
+    uintptr_t lo, hi;
+    bool out;
+};
+
+bool ranges_alias(std::vector<Range>& r)
+{
+    std::sort(r.begin(), r.end(), [](const Range& a, const Range& b) { return a.lo < b.lo; });
+    uintptr_t max_hi_any = 0, max_hi_out = 0;
+    for (const Range& x : r) {
+        if (x.out ? x.lo < max_hi_any : x.lo < max_hi_out) return true;
+        max_hi_any = std::max(max_hi_any, x.hi);
+        if (x.out) max_hi_out = std::max(max_hi_out, x.hi);
+    }
+    return false;
+}
+
+inline size_t elem_size(ddl_dtype d) { return d == DDL_BF16 ? 2 : 4; }
+
+inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+// Appends the ranges of one segment; false if a needed pointer is NULL or misaligned for its
+// element type.  `learner_bits` selects which learners' ranges count.
+bool add_segment_ranges(const float* theta, const float* v, const void* const* learners,
+                        uint32_t learner_bits, ddl_dtype dt, size_t n, std::vector<Range>& r)
+{
+    if (!theta || !v || !aligned(theta, 4) || !aligned(v, 4)) return false;
+    r.push_back({(uintptr_t)theta, (uintptr_t)theta + 4 * n, true});
+    r.push_back({(uintptr_t)v, (uintptr_t)v + 4 * n, true});
+    const size_t b = elem_size(dt);
+    for (int m = 0; m < DDL_MAXL; ++m) {
+        if (!(learner_bits >> m & 1)) continue;
+        const void* p = learners[m];
+        if (!p || !aligned(p, b)) return false;
+        r.push_back({(uintptr_t)p, (uintptr_t)p + b * n, false});
+    }
+    return true;
+}
+
+void fill_desc(DdlSegDesc& d, float* theta, float* v, const void* const* learners, int M, size_t n,
+               uint32_t tile_begin)
+{
+    std::memset(&d, 0, sizeof d);
+    d.theta = theta;
+    d.v = v;
+    d.n = n;
+    d.tile_begin = tile_begin;
+    d.base_aligned = aligned(theta, 16) && aligned(v, 16);
+    for (int m = 0; m < M; ++m) {
+        d.learner[m] = learners[m];
+        if (aligned(learners[m], 16)) d.learner_aligned |= (uint16_t)(1u << m);
+    }
+}
+
+void fill_item(DdlItem& it, const Quorum& q, float lr, float mu, uint32_t seg_begin,
+               uint32_t num_segs, uint32_t tile_off)
+{
+    std::memset(&it, 0, sizeof it);
+    it.seg_begin = seg_begin;
+    it.num_segs = num_segs;
+    it.tile_off = tile_off;
+    it.present_bits = q.present_bits;
+    std::memcpy(it.w, q.w, sizeof it.w);
+    std::memcpy(it.idx, q.idx, sizeof it.idx);
+    it.lr = lr;
+    it.mu = mu;
+}
+
+// ------------------------------------------------------------------------------------------
+// table of segment descriptors for a set of fragments
+// ------------------------------------------------------------------------------------------
+struct FragInfo {
+    uint32_t seg_begin = 0, num_segs = 0, tiles = 0;
+    int M = 0;
+    ddl_dtype dt = DDL_F32;
+    uint64_t elems = 0;
+    uint32_t nonnull_bits = 0;  // learners whose pointer is non-NULL in every segment
+};
+
+struct Table {
+    std::vector<DdlSegDesc> segs;  // empty segments are left out
+    std::vector<FragInfo> frags;
+    uint32_t tile_elems = 0;
+    uint64_t elems = 0;
+};
+
+ddl_status check_fragment_shape(const ddl_fragment& f)
+{
+    if (f.M < 1 || f.M > DDL_MAX_LEARNERS) return DDL_ERR_INVALID_ARG;
+    if (f.learner_dtype != DDL_F32 && f.learner_dtype != DDL_BF16) return DDL_ERR_INVALID_ARG;
+    if (f.num_segs < 0 || (f.num_segs > 0 && !f.segs)) return DDL_ERR_INVALID_ARG;
+    for (int s = 0; s < f.num_segs; ++s)
+        if (f.segs[s].n > 0 && !f.segs[s].learner_params) return DDL_ERR_INVALID_ARG;
+    return DDL_OK;
+}
+
+// Builds the descriptors.  learner_bits[i] says which learners of fragment i must be valid
+// and take part in the overlap check.
+ddl_status build_table(const ddl_fragment* frags, int num_frags, const uint32_t* learner_bits,
+                       uint32_t tile_elems, Table& T)
+{
+    T.segs.clear();
+    T.frags.assign((size_t)num_frags, FragInfo());
+    T.tile_elems = tile_elems;
+    T.elems = 0;
+    std::vector<Range> ranges;
+    for (int i = 0; i < num_frags; ++i) {
+        const ddl_fragment& f = frags[i];
+        FragInfo& fi = T.frags[(size_t)i];
+        fi.seg_begin = (uint32_t)T.segs.size();
+        fi.M = f.M;
+        fi.dt = f.learner_dtype;
+        fi.nonnull_bits = (1u << f.M) - 1u;
+        uint64_t tiles = 0;
+        for (int s = 0; s < f.num_segs; ++s) {
+            const ddl_segment& g = f.segs[s];
+            if (g.n == 0) continue;
+            uint32_t bits = learner_bits[i];
+            if (bits == 0xffffffffu) {  // plan creation: every non-NULL learner counts
+                bits = 0;
+                for (int m = 0; m < f.M; ++m)
+                    if (g.learner_params[m]) bits |= 1u << m;
+            }
+            for (int m = 0; m < f.M; ++m)
+                if (!g.learner_params[m]) fi.nonnull_bits &= ~(1u << m);
+            if (!add_segment_ranges(g.theta, g.v, g.learner_params, bits, f.learner_dtype, g.n,
+                                    ranges))
+                return DDL_ERR_INVALID_ARG;
+            if (tiles > 0xffffffffull) return DDL_ERR_INVALID_ARG;
+            DdlSegDesc d;
+            fill_desc(d, g.theta, g.v, g.learner_params, f.M, g.n, (uint32_t)tiles);
+            T.segs.push_back(d);
+            tiles += (g.n + tile_elems - 1) / tile_elems;
+            fi.elems += g.n;
+        }
+        if (tiles > 0x7fffffffull) return DDL_ERR_INVALID_ARG;
+        fi.tiles = (uint32_t)tiles;
+        fi.num_segs = (uint32_t)T.segs.size() - fi.seg_begin;
+        T.elems += fi.elems;
+    }
+    if (ranges_alias(ranges)) return DDL_ERR_ALIAS;
+    return DDL_OK;
+}
+
+// One sync of one fragment, ready to launch.
+struct Work {
+    uint32_t frag;  // index into Table::frags
+    Quorum q;
+    float lr, mu;
+};
+
+// Enqueue the fragments in `work`: one launch per group of up to DDL_MAX_ITEMS fragments with
+// the same learner dtype and number of contributing learners.
+ddl_status launch_work(const Table& T, const DdlSegDesc* d_segs, std::vector<Work>& work,
+                       const DeviceState& ds, void* stream)
+{
+    std::stable_sort(work.begin(), work.end(), [&](const Work& a, const Work& b) {
+        const FragInfo& fa = T.frags[a.frag];
+        const FragInfo& fb = T.frags[b.frag];
+        if (fa.dt != fb.dt) return fa.dt < fb.dt;
+        return a.q.Mq < b.q.Mq;
+    });
+    size_t i = 0;
+    while (i < work.size()) {
+        const FragInfo& f0 = T.frags[work[i].frag];
+        DdlLaunchArgs a;
+        std::memset(&a, 0, sizeof a);
+        a.segs = d_segs;
+        a.tile_elems = T.tile_elems;
+        uint64_t tiles = 0;
+        int items = 0;
+        size_t j = i;
+        for (; j < work.size() && items < DDL_MAX_ITEMS; ++j) {
+            const FragInfo& f = T.frags[work[j].frag];
+            if (f.dt != f0.dt || work[j].q.Mq != work[i].q.Mq) break;
+            if (f.tiles == 0) continue;
+            if (tiles + f.tiles > 0x7fffffffull) break;
+            fill_item(a.item[items], work[j].q, work[j].lr, work[j].mu, f.seg_begin, f.num_segs,
+                      (uint32_t)tiles);
+            tiles += f.tiles;
+            ++items;
+        }
+        if (items > 0) {
+            a.num_items = items;
+            a.total_tiles = (uint32_t)tiles;
+            const int e = ddl_launch_merge((int)f0.dt, work[i].q.Mq, false,
+                                           grid_for(a.total_tiles, ds), stream, a);
+            if (e != (int)hipSuccess) return runtime_error((hipError_t)e, "merge kernel launch");
+        }
+        if (j == i) return DDL_ERR_INVALID_ARG;  // cannot happen: a lone fragment always fits
+        i = j;
+    }
+    return DDL_OK;
+}
+
+ddl_status merge_flat(float* theta, float* v, const void* const* learner_params, ddl_dtype dt,
+                      const double* w, int M, size_t n, float lr, float mu, void* stream)
+{
+    if (dt != DDL_F32 && dt != DDL_BF16) return DDL_ERR_INVALID_ARG;
+    if (!finite_nonneg(lr) || !finite_nonneg(mu)) return DDL_ERR_INVALID_ARG;
+    if (n == 0) return DDL_OK;
+    if (!learner_params) return DDL_ERR_INVALID_ARG;
+    Quorum q;
+    compact(w, M, q);
+    std::vector<Range> ranges;
+    const void* lp[DDL_MAXL] = {};
+    for (int m = 0; m < M; ++m) lp[m] = (q.present_bits >> m & 1) ? learner_params[m] : nullptr;
+    if (!add_segment_ranges(theta, v, lp, q.present_bits, dt, n, ranges)) return DDL_ERR_INVALID_ARG;
+    if (ranges_alias(ranges)) return DDL_ERR_ALIAS;
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState* ds = nullptr;
+    ddl_status st = device_state(&ds);
+    if (st != DDL_OK) return st;
+    const uint64_t tile = (uint64_t)g_tile_elems;
+    const uint64_t tiles = (n + tile - 1) / tile;
+    if (tiles > 0x7fffffffull) return DDL_ERR_INVALID_ARG;
+    DdlLaunchArgs a;
+    std::memset(&a, 0, sizeof a);
+    a.tile_elems = (uint32_t)tile;
+    a.total_tiles = (uint32_t)tiles;
+    a.num_items = 1;
+    fill_desc(a.flat, theta, v, lp, M, n, 0);
+    fill_item(a.item[0], q, lr, mu, 0, 1, 0);
+    const int e = ddl_launch_merge((int)dt, q.Mq, true, grid_for(a.total_tiles, *ds), stream, a);
+    if (e != (int)hipSuccess) return runtime_error((hipError_t)e, "merge kernel launch");
+    return DDL_OK;
+}
+
+}  // namespace
+
+struct ddl_plan {
+    int device = 0;
+    Table table;
+    DdlSegDesc* d_segs = nullptr;
+};
+
+extern "C" {
+
+int ddl_version(void) { return 100; }
+
+const char* ddl_status_string(ddl_status s)
+{
+    switch (s) {
+        case DDL_OK: return "ok";
+        case DDL_ERR_INVALID_ARG: return "invalid argument";
+        case DDL_ERR_EMPTY_QUORUM: return "empty quorum";
+        case DDL_ERR_ALIAS: return "output range overlaps another range";
+        case DDL_ERR_RUNTIME: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+const char* ddl_last_error_message(void) { return g_err.c_str(); }
+
+ddl_status ddl_compute_weights(const uint64_t* token_counts, const uint8_t* quorum_mask, int M,
+                               double* w_out)
+{
+    return weights_tokens(token_counts, quorum_mask, M, w_out);
+}
+
+ddl_status ddl_compute_weights_quality(const uint64_t* token_counts, const uint64_t* step_counts,
+                                       const uint8_t* quorum_mask, int M, double* w_out)
+{
+    return weights_quality(token_counts, step_counts, quorum_mask, M, w_out);
+}
+
+ddl_status ddl_merge_fragment(float* theta, float* v, const void* const* learner_params,
+                              ddl_dtype learner_dtype, const uint64_t* token_counts,
+                              const uint8_t* quorum_mask, int M, size_t n, float lr, float mu,
+                              void* hip_stream)
+{
+    double w[DDL_MAXL];
+    const ddl_status st = weights_tokens(token_counts, quorum_mask, M, w);
+    if (st != DDL_OK) return st;
+    return merge_flat(theta, v, learner_params, learner_dtype, w, M, n, lr, mu, hip_stream);
+}
+
+ddl_status ddl_merge_fragment_weighted(float* theta, float* v, const void* const* learner_params,
+                                       ddl_dtype learner_dtype, const double* weights, int M,
+                                       size_t n, float lr, float mu, void* hip_stream)
+{
+    double w[DDL_MAXL];
+    const ddl_status st = weights_given(weights, M, w);
+    if (st != DDL_OK) return st;
+    return merge_flat(theta, v, learner_params, learner_dtype, w, M, n, lr, mu, hip_stream);
+}
+
+ddl_status ddl_merge_batch(const ddl_fragment* frags, int num_frags, void* hip_stream)
+{
+    if (num_frags < 0 || (num_frags > 0 && !frags)) return DDL_ERR_INVALID_ARG;
+    if (num_frags == 0) return DDL_OK;
+    std::vector<Work> work;
+    std::vector<uint32_t> bits((size_t)num_frags);
+    work.reserve((size_t)num_frags);
+    for (int i = 0; i < num_frags; ++i) {
+        const ddl_fragment& f = frags[i];
+        ddl_status st = check_fragment_shape(f);
+        if (st != DDL_OK) return st;
+        if (!finite_nonneg(f.lr) || !finite_nonneg(f.mu)) return DDL_ERR_INVALID_ARG;
+        double w[DDL_MAXL];
+        st = weights_tokens(f.token_counts, f.quorum_mask, f.M, w);
+        if (st != DDL_OK) return st;
+        Work wk;
+        wk.frag = (uint32_t)i;
+        wk.lr = f.lr;
+        wk.mu = f.mu;
+        compact(w, f.M, wk.q);
+        bits[(size_t)i] = wk.q.present_bits;
+        work.push_back(wk);
+    }
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState* ds = nullptr;
+    ddl_status st = device_state(&ds);
+    if (st != DDL_OK) return st;
+    Table T;
+    st = build_table(frags, num_frags, bits.data(), (uint32_t)g_tile_elems, T);
+    if (st != DDL_OK) return st;
+    if (T.segs.empty()) return DDL_OK;
+
+    // Stage the descriptors: pinned host copy -> device, on the caller's stream.
+    Slot& sl = ds->slot[ds->next];
+    ds->next = (ds->next + 1) % kSlots;
+    if (sl.pending) {
+        DDL_HIP(hipEventSynchronize(sl.done));
+        sl.pending = false;
+    }
+    const size_t bytes = T.segs.size() * sizeof(DdlSegDesc);
+    if (bytes > sl.cap) {
+        if (sl.host) DDL_HIP(hipHostFree(sl.host));
+        if (sl.dev) DDL_HIP(hipFree(sl.dev));
+        sl.host = sl.dev = nullptr;
+        sl.cap = 0;
+        const size_t cap = std::max<size_t>(bytes * 2, 64 * 1024);
+        DDL_HIP(hipHostMalloc(&sl.host, cap, hipHostMallocDefault));
+        DDL_HIP(hipMalloc(&sl.dev, cap));
+        sl.cap = cap;
+    }
+    if (!sl.done) DDL_HIP(hipEventCreateWithFlags(&sl.done, hipEventDisableTiming));
+    std::memcpy(sl.host, T.segs.data(), bytes);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    DDL_HIP(hipMemcpyAsync(sl.dev, sl.host, bytes, hipMemcpyHostToDevice, stream));
+    st = launch_work(T, static_cast<const DdlSegDesc*>(sl.dev), work, *ds, hip_stream);
+    // Record even after a failed launch: the copy above may still be in flight.
+    if (hipEventRecord(sl.done, stream) == hipSuccess) sl.pending = true;
+    return st;
+}
+
+ddl_status ddl_plan_create(const ddl_fragment* frags, int num_frags, ddl_plan** plan_out)
+{
+    if (!plan_out) return DDL_ERR_INVALID_ARG;
+    *plan_out = nullptr;
+    if (num_frags < 1 || !frags) return DDL_ERR_INVALID_ARG;
+    for (int i = 0; i < num_frags; ++i) {
+        const ddl_status st = check_fragment_shape(frags[i]);
+        if (st != DDL_OK) return st;
+    }
+    ddl_plan* p = new (std::nothrow) ddl_plan();
+    if (!p) return DDL_ERR_RUNTIME;
+    std::vector<uint32_t> bits((size_t)num_frags, 0xffffffffu);
+    ddl_status st;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        st = build_table(frags, num_frags, bits.data(), (uint32_t)g_tile_elems, p->table);
+    }
+    if (st != DDL_OK) {
+        delete p;
+        return st;
+    }
+    hipError_t e = hipGetDevice(&p->device);
+    if (e == hipSuccess && !p->table.segs.empty()) {
+        const size_t bytes = p->table.segs.size() * sizeof(DdlSegDesc);
+        e = hipMalloc(reinterpret_cast<void**>(&p->d_segs), bytes);
+        if (e == hipSuccess)
+            e = hipMemcpy(p->d_segs, p->table.segs.data(), bytes, hipMemcpyHostToDevice);
+    }
+    if (e != hipSuccess) {
+        if (p->d_segs) (void)hipFree(p->d_segs);
+        delete p;
+        return runtime_error(e, "plan upload");
+    }
+    *plan_out = p;
+    return DDL_OK;
+}
+
+ddl_status ddl_plan_merge(ddl_plan* plan, const ddl_sync* syncs, int count, void* hip_stream)
+{
+    if (!plan || count < 0 || (count > 0 && !syncs)) return DDL_ERR_INVALID_ARG;
+    if (count == 0) return DDL_OK;
+    const Table& T = plan->table;
+    std::vector<Work> work;
+    work.reserve((size_t)count);
+    std::vector<char> seen(T.frags.size(), 0);
+    for (int i = 0; i < count; ++i) {
+        const ddl_sync& s = syncs[i];
+        if (s.fragment < 0 || (size_t)s.fragment >= T.frags.size()) return DDL_ERR_INVALID_ARG;
+        if (seen[(size_t)s.fragment]) return DDL_ERR_ALIAS;
+        seen[(size_t)s.fragment] = 1;
+        if (!finite_nonneg(s.lr) || !finite_nonneg(s.mu)) return DDL_ERR_INVALID_ARG;
+        const FragInfo& f = T.frags[(size_t)s.fragment];
+        double w[DDL_MAXL];
+        const ddl_status st = weights_tokens(s.token_counts, s.quorum_mask, f.M, w);
+        if (st != DDL_OK) return st;
+        Work wk;
+        wk.frag = (uint32_t)s.fragment;
+        wk.lr = s.lr;
+        wk.mu = s.mu;
+        compact(w, f.M, wk.q);
+        if (f.num_segs > 0 && (wk.q.present_bits & ~f.nonnull_bits)) return DDL_ERR_INVALID_ARG;
+        work.push_back(wk);
+    }
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState* ds = nullptr;
+    const ddl_status st = device_state(&ds);
+    if (st != DDL_OK) return st;
+    return launch_work(T, plan->d_segs, work, *ds, hip_stream);
+}
+
+ddl_status ddl_plan_destroy(ddl_plan* plan)
+{
+    if (!plan) return DDL_OK;
+    ddl_status st = DDL_OK;
+    if (plan->d_segs) {
+        const hipError_t e = hipFree(plan->d_segs);
+        if (e != hipSuccess) st = runtime_error(e, "hipFree");
+    }
+    delete plan;
+    return st;
+}
+
+int ddl_plan_num_fragments(const ddl_plan* plan) { return plan ? (int)plan->table.frags.size() : 0; }
+
+size_t ddl_plan_num_elements(const ddl_plan* plan) { return plan ? (size_t)plan->table.elems : 0; }
+
+ddl_status ddl_set_option(const char* name, long value)
+{
+    if (!name) return DDL_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (!std::strcmp(name, "tile_elems")) {
+        if (value < DDL_TILE_QUANTUM || value % DDL_TILE_QUANTUM || value > (1L << 30))
+            return DDL_ERR_INVALID_ARG;
+        g_tile_elems = value;
+        return DDL_OK;
+    }
+    if (!std::strcmp(name, "blocks_per_cu")) {
+        if (value < 0 || value > 1024) return DDL_ERR_INVALID_ARG;
+        g_blocks_per_cu = value;
+        return DDL_OK;
+    }
+    return DDL_ERR_INVALID_ARG;
+}
+
+ddl_status ddl_get_option(const char* name, long* value_out)
+{
+    if (!name || !value_out) return DDL_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (!std::strcmp(name, "tile_elems")) {
+        *value_out = g_tile_elems;
+        return DDL_OK;
+    }
+    if (!std::strcmp(name, "blocks_per_cu")) {
+        *value_out = g_blocks_per_cu;
+        return DDL_OK;
+    }
+    return DDL_ERR_INVALID_ARG;
+}
+
+}  // extern "C"

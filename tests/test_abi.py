@@ -1,0 +1,143 @@
+"""CPU-only checks of the boundary: the library loads, exports exactly what the header
+declares, and its host-side logic (weights, argument validation that needs no device)
+behaves as documented.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "ddlsync.h")
+
+
+@pytest.fixture(scope="module")
+def ddl():
+    import paper_2604_21428_amd as ddl
+    return ddl
+
+
+def _declared():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"DDL_API[^;(]*?\b(ddl_\w+)\s*\(", text)))
+
+
+def test_header_declares_entry_points():
+    names = _declared()
+    for must in ("ddl_compute_weights", "ddl_merge_fragment", "ddl_merge_batch",
+                 "ddl_plan_create", "ddl_plan_merge", "ddl_plan_destroy"):
+        assert must in names
+    assert len(names) >= 15
+
+
+def test_library_exports_every_declared_symbol(ddl):
+    lib = ctypes.CDLL(ddl.LIB_PATH)
+    for name in _declared():
+        assert hasattr(lib, name), f"{name} declared in ddlsync.h but not exported"
+    assert ddl.version() >= 100
+
+
+def test_header_compiles_as_plain_c(tmp_path):
+    src = tmp_path / "t.c"
+    src.write_text('#include "ddlsync.h"\nint main(void){ddl_fragment f; ddl_sync s; (void)f; (void)s; '
+                   'return DDL_MAX_LEARNERS == 16 ? 0 : 1;}\n')
+    import subprocess
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I",
+                    os.path.join(ROOT, "include"), "-c", str(src), "-o", str(tmp_path / "t.o")],
+                   check=True)
+
+
+def test_weights_match_oracle(ddl):
+    rng = np.random.default_rng(0)
+    for M in (1, 2, 4, 8, 16):
+        for _ in range(25):
+            t = rng.integers(0, 1 << 44, size=M)
+            q = rng.integers(0, 2, size=M)
+            if int((t * q).sum()) == 0:
+                continue
+            w = np.asarray(ddl.compute_weights(t.tolist(), q.tolist()))
+            ref = oracle.weights(t, q)
+            assert np.allclose(w, ref, rtol=4e-16, atol=0)
+            assert abs(w.sum() - 1.0) < 1e-15 and np.all(w[q == 0] == 0)
+    assert ddl.compute_weights([1, 3], [1, 1]) == [0.25, 0.75]
+    assert ddl.compute_weights([2, 5, 6], [1, 0, 1]) == [0.25, 0.0, 0.75]
+    # counters near 2^64 do not overflow the sum
+    big = (1 << 64) - 1
+    assert ddl.compute_weights([big, big], [1, 1]) == [0.5, 0.5]
+
+
+def test_quality_weights_match_oracle(ddl):
+    rng = np.random.default_rng(1)
+    for _ in range(50):
+        M = int(rng.integers(1, 17))
+        s = rng.integers(1, 100, size=M)
+        t = s * rng.integers(1, 1 << 20, size=M)
+        q = rng.integers(0, 2, size=M)
+        if q.sum() == 0:
+            q[0] = 1
+        w = np.asarray(ddl.compute_weights_quality(t.tolist(), s.tolist(), q.tolist()))
+        assert np.allclose(w, oracle.weights_quality(t, s, q), rtol=1e-15, atol=0)
+    assert ddl.compute_weights_quality([6, 2, 100], [3, 1, 1], [1, 1, 0]) == [0.75, 0.25, 0.0]
+
+
+def test_weight_errors(ddl):
+    for t, q, code in (([0, 0], [1, 1], ddl.DDL_ERR_EMPTY_QUORUM),
+                       ([5, 7], [0, 0], ddl.DDL_ERR_EMPTY_QUORUM),
+                       ([1, 2], [1, 2], ddl.DDL_ERR_INVALID_ARG),
+                       ([1] * 17, [1] * 17, ddl.DDL_ERR_INVALID_ARG)):
+        with pytest.raises(ddl.DdlError) as e:
+            ddl.compute_weights(t, q)
+        assert e.value.status == code
+    with pytest.raises(ddl.DdlError) as e:
+        ddl.compute_weights_quality([5, 1], [0, 1], [1, 1])   # tokens without steps
+    assert e.value.status == ddl.DDL_ERR_INVALID_ARG
+
+
+def test_argument_errors_need_no_device(ddl):
+    """Errors that are found before anything is enqueued, exercised with fake addresses:
+    nothing is dereferenced on the host and no kernel is launched."""
+    lib = ddl._lib
+    M = 3
+    tok = (ctypes.c_uint64 * M)(5, 6, 7)
+    table = (ctypes.c_void_p * M)(0x10000000, 0x20000000, 0x30000000)
+    th, v = ctypes.c_void_p(0x40000000), ctypes.c_void_p(0x50000000)
+
+    def call(mask, n=1000, lr=0.7, mu=0.9, theta=th, vv=v, tbl=table, dtype=ddl.DDL_BF16, m=M):
+        return lib.ddl_merge_fragment(theta, vv, tbl, dtype, tok, (ctypes.c_uint8 * M)(*mask), m, n,
+                                      lr, mu, None)
+
+    assert call([0, 0, 0]) == ddl.DDL_ERR_EMPTY_QUORUM
+    assert call([1, 1, 3]) == ddl.DDL_ERR_INVALID_ARG
+    assert call([1, 1, 1], lr=-1.0) == ddl.DDL_ERR_INVALID_ARG
+    assert call([1, 1, 1], mu=float("inf")) == ddl.DDL_ERR_INVALID_ARG
+    assert call([1, 1, 1], dtype=7) == ddl.DDL_ERR_INVALID_ARG
+    assert call([1, 1, 1], m=0) == ddl.DDL_ERR_INVALID_ARG
+    assert call([1, 1, 1], m=17) == ddl.DDL_ERR_INVALID_ARG
+    assert call([1, 1, 1], theta=None) == ddl.DDL_ERR_INVALID_ARG
+    assert call([1, 1, 1], theta=ctypes.c_void_p(0x40000002)) == ddl.DDL_ERR_INVALID_ARG
+    assert call([1, 1, 1], n=0) == ddl.DDL_OK                       # nothing to do
+    nulls = (ctypes.c_void_p * M)(0x10000000, None, 0x30000000)
+    assert call([1, 1, 1], tbl=nulls) == ddl.DDL_ERR_INVALID_ARG
+    odd = (ctypes.c_void_p * M)(0x10000001, 0x20000000, 0x30000000)
+    assert call([1, 1, 1], tbl=odd) == ddl.DDL_ERR_INVALID_ARG      # bf16 needs 2-byte alignment
+    # overlaps: v inside theta; a contributing learner inside theta; absent one may overlap
+    assert call([1, 1, 1], vv=ctypes.c_void_p(0x40000000 + 400)) == ddl.DDL_ERR_ALIAS
+    over = (ctypes.c_void_p * M)(0x10000000, 0x40000000 + 100, 0x30000000)
+    assert call([1, 1, 1], tbl=over) == ddl.DDL_ERR_ALIAS
+    assert ddl._lib.ddl_status_string(ddl.DDL_ERR_ALIAS).decode().startswith("output range")
+    assert lib.ddl_plan_destroy(None) == ddl.DDL_OK
+    assert lib.ddl_plan_num_fragments(None) == 0
+    assert lib.ddl_merge_batch(None, 0, None) == ddl.DDL_OK
+    assert lib.ddl_merge_batch(None, 1, None) == ddl.DDL_ERR_INVALID_ARG
+
+
+def test_options(ddl):
+    assert ddl.get_option("tile_elems") % 8192 == 0
+    with pytest.raises(ddl.DdlError):
+        ddl.set_option("tile_elems", 12345)
+    with pytest.raises(ddl.DdlError):
+        ddl.set_option("blocks_per_cu", -1)

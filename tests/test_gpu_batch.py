@@ -1,0 +1,230 @@
+"""HIP path vs fp64 oracle for fragments made of many tensors: ddl_merge_batch and the
+resident plan (ddl_plan_*), on the five workloads' structure at reduced sizes."""
+import numpy as np
+import pytest
+import torch
+
+import ddl_synth
+import oracle
+from ddl_testutil import check_segment, oracle_segment, random_problem
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+NAMES = ["tiny", "dense_block", "large_dense", "moe", "streaming_model"]
+
+
+@pytest.fixture(scope="module")
+def ddl():
+    import paper_2604_21428_amd as ddl
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return ddl
+
+
+def _materialise(wl, absent="nan"):
+    data = [ddl_synth.make_fragment(wl, f, DEV, absent=absent) for f in wl.fragments]
+    refs = [[oracle_segment(s, f) for s in segs] for f, segs in zip(wl.fragments, data)]
+    return data, refs
+
+
+def _fragment(ddl, f, segs, with_sync=True):
+    triples = [(s.theta, s.v, s.learners) for s in segs]
+    dt = torch.bfloat16 if f.learner_dtype == "bf16" else torch.float32
+    if with_sync:
+        return ddl.Fragment(triples, f.token_counts, f.quorum_mask, f.lr, f.mu, M=f.M,
+                            learner_dtype=dt)
+    return ddl.Fragment(triples, M=f.M, learner_dtype=dt)
+
+
+def _check_all(wl, data, refs, which=None):
+    worst = 0.0
+    for fi, (f, segs) in enumerate(zip(wl.fragments, data)):
+        if which is not None and fi not in which:
+            continue
+        for si, s in enumerate(segs):
+            worst = max(worst, check_segment(s, refs[fi][si], f"{wl.name} frag {fi} seg {si}"))
+    return worst
+
+
+@pytest.mark.parametrize("name", NAMES)
+def test_batch_reduced_workloads(ddl, name):
+    wl = ddl_synth.reduced(name)
+    data, refs = _materialise(wl)
+    print(f"case batch {name}: {len(wl.fragments)} fragments, {wl.num_segments} tensors", flush=True)
+    ddl.merge_batch([_fragment(ddl, f, segs) for f, segs in zip(wl.fragments, data)])
+    torch.cuda.synchronize()
+    _check_all(wl, data, refs)
+
+
+@pytest.mark.parametrize("name", NAMES)
+def test_one_call_per_fragment_in_arrival_order(ddl, name):
+    wl = ddl_synth.reduced(name)
+    data, refs = _materialise(wl, absent="none")
+    for fi in wl.arrival_order:
+        ddl.merge_batch([_fragment(ddl, wl.fragments[fi], data[fi])])
+    torch.cuda.synchronize()
+    _check_all(wl, data, refs)
+
+
+@pytest.mark.parametrize("name", NAMES)
+def test_plan_reduced_workloads(ddl, name):
+    wl = ddl_synth.reduced(name)
+    data, refs = _materialise(wl)
+    plan = ddl.Plan([_fragment(ddl, f, segs, with_sync=False) for f, segs in zip(wl.fragments, data)])
+    assert plan.num_fragments == len(wl.fragments) and plan.num_elements == wl.numel
+    print(f"case plan {name}", flush=True)
+    # fragments arrive one by one in the seeded order (two at a time for the last pair)
+    order = list(wl.arrival_order)
+    while order:
+        take = order[:2] if len(order) == 2 else order[:1]
+        order = order[len(take):]
+        plan.merge([(fi, wl.fragments[fi].token_counts, wl.fragments[fi].quorum_mask,
+                     wl.fragments[fi].lr, wl.fragments[fi].mu) for fi in take])
+    torch.cuda.synchronize()
+    _check_all(wl, data, refs)
+    plan.destroy()
+
+
+def test_plan_whole_model_in_one_call(ddl):
+    """All 33 fragments of the streaming model due at once: several launches grouped by
+    quorum size, more fragments than one launch holds."""
+    wl = ddl_synth.reduced("streaming_model")
+    data, refs = _materialise(wl)
+    plan = ddl.Plan([_fragment(ddl, f, segs, with_sync=False) for f, segs in zip(wl.fragments, data)])
+    plan.merge([(f.index, f.token_counts, f.quorum_mask, f.lr, f.mu) for f in wl.fragments])
+    torch.cuda.synchronize()
+    _check_all(wl, data, refs)
+    plan.destroy()
+
+
+def test_plan_second_sync_with_new_quorum(ddl):
+    """The same plan, a later sync with a different quorum and counters."""
+    wl = ddl_synth.reduced("large_dense")
+    f = wl.fragments[0]
+    segs = ddl_synth.make_fragment(wl, f, DEV, absent="valid")
+    plan = ddl.Plan([_fragment(ddl, f, segs, with_sync=False)])
+    for step, mask in enumerate(([1] * 8, [1, 0, 1, 0, 1, 0, 1, 1], [0, 0, 0, 0, 0, 1, 0, 0])):
+        tokens = [1000 + 37 * step * m for m in range(8)]
+        f2 = ddl_synth.FragmentSpec(0, f.tensors, f.M, f.learner_dtype, tokens, list(mask), f.drift,
+                                    lr=0.5, mu=0.8)
+        refs = [oracle_segment(s, f2) for s in segs]
+        plan.merge([(0, tokens, mask, 0.5, 0.8)])
+        torch.cuda.synchronize()
+        for si, s in enumerate(segs):
+            check_segment(s, refs[si], f"sync {step} seg {si}")
+    plan.destroy()
+
+
+def test_mixed_dtypes_and_quorums_in_one_batch(ddl):
+    """fp32 and bf16 fragments, different quorum sizes, lr and mu, empty tensors, misaligned
+    tensors, in a single call."""
+    frs, datas, specs = [], [], []
+    cfgs = [(torch.float32, 3, [1, 1, 1], 0.7, 0.9), (torch.bfloat16, 3, [1, 0, 1], 0.3, 0.5),
+            (torch.bfloat16, 5, [1, 1, 0, 1, 0], 1.0, 0.0), (torch.float32, 2, [0, 1], 0.1, 0.99),
+            (torch.bfloat16, 3, [1, 1, 1], 0.7, 0.9)]
+    for i, (dt, M, mask, lr, mu) in enumerate(cfgs):
+        segs = []
+        tokens = None
+        for j, n in enumerate((0, 17, 16384 + 3, 40000)):
+            th, v, ls, tok, _ = random_problem(100 * i + j, n, M, dt, DEV, offset=(j == 3) * (i % 3))
+            tokens = tokens or tok
+            segs.append(ddl_synth.SegmentData(th, v, ls))
+        spec = ddl_synth.FragmentSpec(i, [], M, "bf16" if dt == torch.bfloat16 else "f32", tokens,
+                                      mask, [1e-3] * M, lr=lr, mu=mu)
+        specs.append(spec)
+        datas.append(segs)
+        frs.append(ddl.Fragment([(s.theta, s.v, s.learners) for s in segs], tokens, mask, lr, mu,
+                                M=M, learner_dtype=dt))
+    refs = [[oracle_segment(s, f) for s in segs] for f, segs in zip(specs, datas)]
+    ddl.merge_batch(frs)
+    torch.cuda.synchronize()
+    for fi, segs in enumerate(datas):
+        for si, s in enumerate(segs):
+            check_segment(s, refs[fi][si], f"mixed frag {fi} seg {si}")
+
+
+def test_batch_equals_sequence_of_flat_calls_bitwise(ddl):
+    wl = ddl_synth.reduced("moe")
+    f = wl.fragments[0]
+    a = ddl_synth.make_fragment(wl, f, DEV)
+    b = ddl_synth.make_fragment(wl, f, DEV)
+    ddl.merge_batch([_fragment(ddl, f, a)])
+    for s in reversed(b):
+        ddl.merge_fragment(s.theta, s.v, s.learners, f.token_counts, f.quorum_mask, f.lr, f.mu)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x.theta, y.theta) and torch.equal(x.v, y.v)
+
+
+def test_batch_errors_leave_state_untouched(ddl):
+    wl = ddl_synth.reduced("dense_block")
+    f = wl.fragments[0]
+    segs = ddl_synth.make_fragment(wl, f, DEV)
+    before = [(s.theta.clone(), s.v.clone()) for s in segs]
+    good = _fragment(ddl, f, segs)
+    th, v, ls, tok, mask = random_problem(7, 1000, 4, torch.bfloat16, DEV)
+    empty = ddl.Fragment([(th, v, ls)], tok, [0, 0, 0, 0], 0.7, 0.9)
+    with pytest.raises(ddl.DdlError) as e:
+        ddl.merge_batch([good, empty])
+    assert e.value.status == ddl.DDL_ERR_EMPTY_QUORUM
+    with pytest.raises(ddl.DdlError) as e:     # the same fragment twice: outputs overlap
+        ddl.merge_batch([good, _fragment(ddl, f, segs)])
+    assert e.value.status == ddl.DDL_ERR_ALIAS
+    torch.cuda.synchronize()
+    for s, (t0, v0) in zip(segs, before):
+        assert torch.equal(s.theta, t0) and torch.equal(s.v, v0)
+    plan = ddl.Plan([_fragment(ddl, f, segs, with_sync=False)])
+    with pytest.raises(ddl.DdlError) as e:
+        plan.merge([(0, f.token_counts, f.quorum_mask, 0.7, 0.9),
+                    (0, f.token_counts, f.quorum_mask, 0.7, 0.9)])
+    assert e.value.status == ddl.DDL_ERR_ALIAS
+    with pytest.raises(ddl.DdlError) as e:
+        plan.merge([(1, f.token_counts, f.quorum_mask, 0.7, 0.9)])
+    assert e.value.status == ddl.DDL_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    for s, (t0, v0) in zip(segs, before):
+        assert torch.equal(s.theta, t0) and torch.equal(s.v, v0)
+    plan.destroy()
+
+
+def test_many_batches_reuse_the_staging_ring(ddl):
+    """More one-shot calls in flight than the library has staging slots."""
+    wl = ddl_synth.reduced("dense_block")
+    f = wl.fragments[0]
+    runs = []
+    for k in range(10):
+        segs = ddl_synth.make_fragment(wl, f, DEV)
+        refs = [oracle_segment(s, f) for s in segs]
+        runs.append((segs, refs))
+    for segs, _ in runs:
+        ddl.merge_batch([_fragment(ddl, f, segs)])
+    torch.cuda.synchronize()
+    for k, (segs, refs) in enumerate(runs):
+        for si, s in enumerate(segs):
+            check_segment(s, refs[si], f"run {k} seg {si}")
+
+
+@pytest.mark.parametrize("tile,bpc", [(8192, 0), (16384, 2), (65536, 0), (32768, 8)])
+def test_launch_shape_options(ddl, tile, bpc):
+    old = ddl.get_option("tile_elems"), ddl.get_option("blocks_per_cu")
+    try:
+        ddl.set_option("tile_elems", tile)
+        ddl.set_option("blocks_per_cu", bpc)
+        wl = ddl_synth.reduced("large_dense")
+        data, refs = _materialise(wl)
+        ddl.merge_batch([_fragment(ddl, f, segs) for f, segs in zip(wl.fragments, data)])
+        n = 3 * tile + 4097
+        th, v, ls, tok, mask = random_problem(tile + bpc, n, 3, torch.bfloat16, DEV)
+        ref = oracle.merge_fragment(ddl_synth.to_host_array(th), ddl_synth.to_host_array(v),
+                                    [ddl_synth.to_host_array(x) for x in ls], tok, mask, 0.7, 0.9)
+        ddl.merge_fragment(th, v, ls, tok, mask, 0.7, 0.9)
+        torch.cuda.synchronize()
+        _check_all(wl, data, refs)
+        check_segment(ddl_synth.SegmentData(th, v, ls), ref, "flat")
+    finally:
+        ddl.set_option("tile_elems", old[0])
+        ddl.set_option("blocks_per_cu", old[1])
+    with pytest.raises(ddl.DdlError):
+        ddl.set_option("tile_elems", 1000)
+    with pytest.raises(ddl.DdlError):
+        ddl.set_option("no_such_option", 1)
