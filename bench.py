@@ -1,0 +1,248 @@
+#!/usr/bin/env python3
+"""Benchmark of the synchronizer hot path on one MI355X.
+
+A "step" is one sync of the whole workload: per fragment, quorum weights from the token
+counters and the mask, compaction of the contributing learners, and the fused merge + outer
+Nesterov step over every tensor of the fragment (ddl_plan_merge on a resident plan; the
+streaming workload issues one call per arriving fragment, in its seeded arrival order).
+All inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line: merged params/s (``value``), the HBM roofline of the merge kernel
+(``roofline``) and the fp64 CPU oracle timed on this machine's host cores (``cpu_baseline``).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload dense_block]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
+
+# HBM bytes per merge launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE, each
+# scaled by what the same counter reads for ddl_copy_probe of known size); the runs are
+# summarised under profiles/.  None where no counter run exists for the workload.
+MEASURED_TRAFFIC_BYTES = {
+    "dense_block": None,
+}
+
+METRIC = "merged params/sec and achieved HBM GB/s (% of peak), merge+outer Nesterov"
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="dense_block",
+                    choices=["tiny", "dense_block", "large_dense", "moe", "streaming_model"])
+    ap.add_argument("--api", default="plan", choices=["plan", "batch"],
+                    help="resident plan (default) or the one-shot ddl_merge_batch per step")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tile-elems", type=int, default=None)
+    ap.add_argument("--blocks-per-cu", type=int, default=None)
+    return ap.parse_args()
+
+
+def time_copy_probe(ddl, torch, nbytes=1 << 30, reps=20):
+    """GB/s (read + write bytes) of the plain streaming copy kernel."""
+    src = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda:0").normal_()
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        ddl.copy_probe(dst, src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        ddl.copy_probe(dst, src)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    del src, dst
+    return 2 * nbytes / (ms * 1e-3) / 1e9
+
+
+def cpu_baseline(torch, ddl_synth, wl, data, budget_s=20.0):
+    """The oracle as it stands, timed on the host: the plain scalar fp64 loop on one core and
+    the same loop chunked over all cores.  Sample: whole tensors of the workload, in order,
+    until about ``budget_s`` seconds of single-core work have been spent."""
+    import oracle
+    cores = len(os.sched_getaffinity(0))
+    cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)) or cores)
+    done_params = 0
+    t_single = 0.0
+    t_multi = 0.0
+    tensors = 0
+    for fi in wl.arrival_order:
+        f = wl.fragments[fi]
+        for s in data[fi]:
+            n = s.theta.numel()
+            cap = 1 << 26               # at most 64 Mi elements of a tensor: bounds host memory
+            th = ddl_synth.to_host_array(s.theta[:cap])
+            v = ddl_synth.to_host_array(s.v[:cap])
+            ls = [ddl_synth.to_host_array(x[:cap]) if (x is not None and q and t > 0) else None
+                  for x, q, t in zip(s.learners, f.quorum_mask, f.token_counts)]
+            t0 = time.perf_counter()
+            oracle.merge_fragment(th, v, ls, f.token_counts, f.quorum_mask, f.lr, f.mu)
+            t1 = time.perf_counter()
+            oracle.merge_fragment(th, v, ls, f.token_counts, f.quorum_mask, f.lr, f.mu,
+                                  nthreads=cores)
+            t2 = time.perf_counter()
+            t_single += t1 - t0
+            t_multi += t2 - t1
+            done_params += min(n, cap)
+            tensors += 1
+            if t_single >= budget_s:
+                break
+        if t_single >= budget_s:
+            break
+    return {
+        "value": done_params / t_multi,
+        "unit": "params/s",
+        "cores": cores,
+        "kind": "oracle",
+        "sample": (f"{tensors} tensor(s), {done_params} params of workload {wl.name} "
+                   f"(of {wl.numel}); same fp64 scalar loop chunked over {cores} threads"),
+        "value_1core": done_params / t_single,
+        "seconds_1core": round(t_single, 3),
+        "seconds_allcores": round(t_multi, 3),
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        sys.stderr.write(
+            "bench.py: this build is single-GPU by design (the synchronizer path is element-wise "
+            "and has no collectives here); run with --gpus 1.\n")
+        sys.exit(2)
+
+    import torch
+
+    import ddl_synth
+    import paper_2604_21428_amd as ddl
+
+    if not torch.cuda.is_available():
+        sys.stderr.write("bench.py: no GPU visible; the HIP path has no CPU fallback.\n")
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    if args.tile_elems is not None:
+        ddl.set_option("tile_elems", args.tile_elems)
+    if args.blocks_per_cu is not None:
+        ddl.set_option("blocks_per_cu", args.blocks_per_cu)
+
+    wl = ddl_synth.WORKLOADS[args.workload]()
+    big = wl.numel > 2_000_000_000
+    steps = args.steps if args.steps is not None else (20 if big else 300)
+    warmup = args.warmup if args.warmup is not None else (2 if big else 20)
+
+    # ---- inputs, resident in HBM ----------------------------------------------------------
+    data = [ddl_synth.make_fragment(wl, f, "cuda:0", absent="valid") for f in wl.fragments]
+    dt = {"bf16": torch.bfloat16, "f32": torch.float32}
+    if args.api == "plan":
+        plan = ddl.Plan([ddl.Fragment([(s.theta, s.v, s.learners) for s in segs], M=f.M,
+                                      learner_dtype=dt[f.learner_dtype])
+                         for f, segs in zip(wl.fragments, data)])
+        calls = [plan.prepare([(fi, wl.fragments[fi].token_counts, wl.fragments[fi].quorum_mask,
+                                wl.fragments[fi].lr, wl.fragments[fi].mu)])
+                 for fi in wl.arrival_order]
+
+        def step():
+            for c in calls:
+                plan.merge(c)
+    else:
+        frs = [ddl.Fragment([(s.theta, s.v, s.learners) for s in segs], f.token_counts,
+                            f.quorum_mask, f.lr, f.mu, M=f.M, learner_dtype=dt[f.learner_dtype])
+               for f, segs in zip(wl.fragments, data)]
+
+        def step():
+            for fi in wl.arrival_order:
+                ddl.merge_batch([frs[fi]])
+
+    launches_per_step = len(wl.arrival_order)
+    torch.cuda.synchronize()
+
+    # ---- timed region ---------------------------------------------------------------------
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()          # on torch's current stream: the stream the kernels are launched on
+    for _ in range(steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    wall_ms = (t1 - t0) * 1e3 / steps
+    gpu_ms = ev0.elapsed_time(ev1) / steps
+
+    params_per_s = wl.numel / (wall_ms * 1e-3)
+    alg_bytes = wl.algorithmic_bytes
+    # The step consists of merge-kernel launches only (no copies, no other kernels), so the
+    # event time per step divided by the launches per step is the average launch duration,
+    # gaps between back-to-back launches included.
+    kernel_ms = gpu_ms / launches_per_step
+    achieved = alg_bytes / launches_per_step / (kernel_ms * 1e-3) / 1e9
+    copy_gbps = time_copy_probe(ddl, torch)
+    traffic = MEASURED_TRAFFIC_BYTES.get(wl.name)
+
+    out = {
+        "metric": METRIC,
+        "value": params_per_s,
+        "unit": "params/s",
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": warmup,
+        "ms_per_step": wall_ms,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": wl.name,
+            "params": wl.numel,
+            "tensors": wl.num_segments,
+            "fragments": len(wl.fragments),
+            "M": wl.fragments[0].M,
+            "Mq": sorted({f.Mq for f in wl.fragments}),
+            "learner_dtype": wl.fragments[0].learner_dtype,
+            "state_dtype": "f32",
+            "lr": wl.fragments[0].lr,
+            "mu": wl.fragments[0].mu,
+            "api": "ddl_plan_merge" if args.api == "plan" else "ddl_merge_batch",
+            "launches_per_step": launches_per_step,
+            "tile_elems": ddl.get_option("tile_elems"),
+            "blocks_per_cu": ddl.get_option("blocks_per_cu"),
+        },
+        "achieved_gbps": alg_bytes / (wall_ms * 1e-3) / 1e9,
+        "algorithmic_bytes_per_step": alg_bytes,
+        "roofline": {
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBPS,
+            "traffic": traffic,
+            "kernel": "ddl_merge_kernel",
+            "avg_launch_ms": kernel_ms,
+            "algorithmic_bytes_per_launch": alg_bytes / launches_per_step,
+            "copy_probe_gbps": copy_gbps,
+            "frac_of_copy_probe": achieved / copy_gbps,
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(torch, ddl_synth, wl, data)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

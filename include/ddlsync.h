@@ -194,6 +194,15 @@ DDL_API int ddl_plan_num_fragments(const ddl_plan* plan);
 DDL_API size_t ddl_plan_num_elements(const ddl_plan* plan);
 
 /*
+ * Measurement aid, not part of the method: a plain device-to-device streaming copy of `bytes`
+ * bytes (a multiple of 16; dst and src device, 16-byte aligned, not overlapping) with the
+ * merge kernel's access width and cache hints.  It reads `bytes` and writes `bytes`, which
+ * gives the HBM rate this GPU sustains for such a stream and a known-size reference for
+ * scaling profiler byte counters.
+ */
+DDL_API ddl_status ddl_copy_probe(void* dst, const void* src, size_t bytes, void* hip_stream);
+
+/*
  * Launch-shape knobs, for measurement.  Names: "tile_elems" (elements per work tile, a
  * multiple of 8192, default chosen by the library), "blocks_per_cu" (0: one workgroup per
  * tile; k > 0: a grid of k * #CU workgroups that stride over the tiles).  Affects later calls

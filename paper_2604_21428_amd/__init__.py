@@ -79,11 +79,14 @@ def _load() -> ctypes.CDLL:
     lib.ddl_plan_num_fragments.restype = ctypes.c_int
     lib.ddl_plan_num_elements.argtypes = [ctypes.c_void_p]
     lib.ddl_plan_num_elements.restype = ctypes.c_size_t
+    lib.ddl_copy_probe.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                   ctypes.c_void_p]
     lib.ddl_set_option.argtypes = [ctypes.c_char_p, ctypes.c_long]
     lib.ddl_get_option.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_long)]
     for name in ("ddl_compute_weights", "ddl_compute_weights_quality", "ddl_merge_fragment",
                  "ddl_merge_fragment_weighted", "ddl_merge_batch", "ddl_plan_create",
-                 "ddl_plan_merge", "ddl_plan_destroy", "ddl_set_option", "ddl_get_option"):
+                 "ddl_plan_merge", "ddl_plan_destroy", "ddl_set_option", "ddl_get_option",
+                 "ddl_copy_probe"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -312,6 +315,15 @@ class Plan:
             self.destroy()
         except Exception:
             pass
+
+
+def copy_probe(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    """ddl_copy_probe: plain streaming copy of src into dst (measurement aid)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes or not (dst.is_cuda and src.is_cuda):
+        raise ValueError("dst and src must be device tensors of the same byte size")
+    _check(_lib.ddl_copy_probe(dst.data_ptr(), src.data_ptr(), nbytes, _stream_handle(stream)),
+           "ddl_copy_probe")
 
 
 def set_option(name: str, value: int) -> None:

@@ -53,3 +53,6 @@ static_assert(sizeof(DdlLaunchArgs) <= 4096, "kernel argument block limit");
 // table).  dtype: 0 fp32, 1 bf16 (values of ddl_dtype).  Returns a hipError_t as int.
 int ddl_launch_merge(int dtype, int Mq, bool flat, uint32_t grid, void* stream,
                      const DdlLaunchArgs& args);
+
+// Launches the plain 16-byte-per-lane copy of n16 * 16 bytes.
+int ddl_launch_copy(void* dst, const void* src, uint64_t n16, uint32_t grid, void* stream);

@@ -603,6 +603,21 @@ int ddl_plan_num_fragments(const ddl_plan* plan) { return plan ? (int)plan->tabl
 
 size_t ddl_plan_num_elements(const ddl_plan* plan) { return plan ? (size_t)plan->table.elems : 0; }
 
+ddl_status ddl_copy_probe(void* dst, const void* src, size_t bytes, void* hip_stream)
+{
+    if (!dst || !src || bytes % 16 || !aligned(dst, 16) || !aligned(src, 16))
+        return DDL_ERR_INVALID_ARG;
+    if (bytes == 0) return DDL_OK;
+    const uintptr_t d = (uintptr_t)dst, s = (uintptr_t)src;
+    if (d < s + bytes && s < d + bytes) return DDL_ERR_ALIAS;
+    const uint64_t n16 = bytes / 16;
+    const uint64_t blocks = (n16 + DDL_BLOCK * 4 - 1) / (DDL_BLOCK * 4);
+    const uint32_t grid = (uint32_t)std::min<uint64_t>(blocks, 0x7fffffffull);
+    const int e = ddl_launch_copy(dst, src, n16, grid, hip_stream);
+    if (e != (int)hipSuccess) return runtime_error((hipError_t)e, "copy kernel launch");
+    return DDL_OK;
+}
+
 ddl_status ddl_set_option(const char* name, long value)
 {
     if (!name) return DDL_ERR_INVALID_ARG;

@@ -283,6 +283,29 @@ typedef LearnerBF16x8 LearnerBF16;
 typedef LearnerBF16x4 LearnerBF16;
 #endif
 
+// Plain streaming copy, 16 bytes per lane, same access pattern and cache hints as the merge
+// kernel: the yardstick for what this GPU's HBM sustains and for scaling profiler counters.
+__global__ void __launch_bounds__(DDL_BLOCK) ddl_copy_kernel(uint64_t dst, uint64_t src, uint64_t n16)
+{
+    constexpr uint32_t kPerBlock = DDL_BLOCK * 4;
+    for (uint64_t base = (uint64_t)blockIdx.x * kPerBlock; base < n16;
+         base += (uint64_t)gridDim.x * kPerBlock) {
+        const uint64_t s = src + base * 16, d = dst + base * 16;
+        const uint32_t left = n16 - base < kPerBlock ? (uint32_t)(n16 - base) : kPerBlock;
+        u32x4 r[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t i = threadIdx.x + u * DDL_BLOCK;
+            if (i < left) r[u] = ld<u32x4>(s, i);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t i = threadIdx.x + u * DDL_BLOCK;
+            if (i < left) st<u32x4>(d, i, r[u]);
+        }
+    }
+}
+
 typedef void (*kernel_fn)(const DdlLaunchArgs);
 
 template <typename L, bool FLAT>
@@ -310,5 +333,14 @@ int ddl_launch_merge(int dtype, int Mq, bool flat, uint32_t grid, void* stream,
         k = flat ? pick_mq<LearnerBF16, true>(Mq) : pick_mq<LearnerBF16, false>(Mq);
     if (!k || grid == 0) return (int)hipErrorInvalidValue;
     hipLaunchKernelGGL(k, dim3(grid), dim3(DDL_BLOCK), 0, static_cast<hipStream_t>(stream), args);
+    return (int)hipGetLastError();
+}
+
+int ddl_launch_copy(void* dst, const void* src, uint64_t n16, uint32_t grid, void* stream)
+{
+    if (grid == 0) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(ddl_copy_kernel, dim3(grid), dim3(DDL_BLOCK), 0,
+                       static_cast<hipStream_t>(stream), reinterpret_cast<uint64_t>(dst),
+                       reinterpret_cast<uint64_t>(src), n16);
     return (int)hipGetLastError();
 }
