@@ -30,7 +30,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # scaled by what the same counter reads for ddl_copy_probe of known size); the runs are
 # summarised under profiles/.  None where no counter run exists for the workload.
 MEASURED_TRAFFIC_BYTES = {
-    "dense_block": None,
+    "dense_block": 1107038826,  # profiles/ddl_merge_kernel_dense_block.txt
 }
 
 METRIC = "merged params/sec and achieved HBM GB/s (% of peak), merge+outer Nesterov"
@@ -45,9 +45,13 @@ def parse_args():
                     choices=["tiny", "dense_block", "large_dense", "moe", "streaming_model"])
     ap.add_argument("--api", default="plan", choices=["plan", "batch"],
                     help="resident plan (default) or the one-shot ddl_merge_batch per step")
+    ap.add_argument("--replicas", type=int, default=None,
+                    help="independent copies of the workload visited round-robin, one per step, "
+                         "so that no step finds its data in the 256 MB last-level cache "
+                         "(default: enough copies for a 3 GiB rotating footprint)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--tile-elems", type=int, default=None)
-    ap.add_argument("--blocks-per-cu", type=int, default=None)
+    ap.add_argument("--tiles-per-block", type=int, default=None)
+    ap.add_argument("--max-blocks-per-cu", type=int, default=None)
     return ap.parse_args()
 
 
@@ -133,10 +137,10 @@ def main():
         sys.stderr.write("bench.py: no GPU visible; the HIP path has no CPU fallback.\n")
         sys.exit(3)
     torch.cuda.set_device(0)
-    if args.tile_elems is not None:
-        ddl.set_option("tile_elems", args.tile_elems)
-    if args.blocks_per_cu is not None:
-        ddl.set_option("blocks_per_cu", args.blocks_per_cu)
+    if args.tiles_per_block is not None:
+        ddl.set_option("tiles_per_block", args.tiles_per_block)
+    if args.max_blocks_per_cu is not None:
+        ddl.set_option("max_blocks_per_cu", args.max_blocks_per_cu)
 
     wl = ddl_synth.WORKLOADS[args.workload]()
     big = wl.numel > 2_000_000_000
@@ -144,27 +148,43 @@ def main():
     warmup = args.warmup if args.warmup is not None else (2 if big else 20)
 
     # ---- inputs, resident in HBM ----------------------------------------------------------
-    data = [ddl_synth.make_fragment(wl, f, "cuda:0", absent="valid") for f in wl.fragments]
+    # Every step syncs ONE copy of the workload.  Small workloads are replicated and the
+    # copies visited round-robin: a real syncer touches a fragment once every H steps, so its
+    # data never sits in the last-level cache, and a loop over one 0.8 GB copy would.
+    footprint = sum(f.numel * ((2 if f.learner_dtype == "bf16" else 4) * f.M + 8)
+                    for f in wl.fragments)
+    replicas = args.replicas if args.replicas is not None else max(
+        1, min(8, -(-3 * (1 << 30) // footprint)))
     dt = {"bf16": torch.bfloat16, "f32": torch.float32}
-    if args.api == "plan":
-        plan = ddl.Plan([ddl.Fragment([(s.theta, s.v, s.learners) for s in segs], M=f.M,
-                                      learner_dtype=dt[f.learner_dtype])
-                         for f, segs in zip(wl.fragments, data)])
-        calls = [plan.prepare([(fi, wl.fragments[fi].token_counts, wl.fragments[fi].quorum_mask,
-                                wl.fragments[fi].lr, wl.fragments[fi].mu)])
-                 for fi in wl.arrival_order]
+    copies = []
+    for r in range(replicas):
+        data = [ddl_synth.make_fragment(wl, f, "cuda:0", absent="valid") for f in wl.fragments]
+        if args.api == "plan":
+            plan = ddl.Plan([ddl.Fragment([(s.theta, s.v, s.learners) for s in segs], M=f.M,
+                                          learner_dtype=dt[f.learner_dtype])
+                             for f, segs in zip(wl.fragments, data)])
+            calls = [plan.prepare([(fi, wl.fragments[fi].token_counts,
+                                    wl.fragments[fi].quorum_mask, wl.fragments[fi].lr,
+                                    wl.fragments[fi].mu)]) for fi in wl.arrival_order]
+            copies.append((data, plan, calls))
+        else:
+            frs = [ddl.Fragment([(s.theta, s.v, s.learners) for s in segs], f.token_counts,
+                                f.quorum_mask, f.lr, f.mu, M=f.M,
+                                learner_dtype=dt[f.learner_dtype])
+                   for f, segs in zip(wl.fragments, data)]
+            copies.append((data, None, frs))
+    data = copies[0][0]
+    counter = [0]
 
-        def step():
+    def step():
+        _, plan, calls = copies[counter[0] % replicas]
+        counter[0] += 1
+        if plan is not None:
             for c in calls:
                 plan.merge(c)
-    else:
-        frs = [ddl.Fragment([(s.theta, s.v, s.learners) for s in segs], f.token_counts,
-                            f.quorum_mask, f.lr, f.mu, M=f.M, learner_dtype=dt[f.learner_dtype])
-               for f, segs in zip(wl.fragments, data)]
-
-        def step():
+        else:
             for fi in wl.arrival_order:
-                ddl.merge_batch([frs[fi]])
+                ddl.merge_batch([calls[fi]])
 
     launches_per_step = len(wl.arrival_order)
     torch.cuda.synchronize()
@@ -220,8 +240,9 @@ def main():
             "mu": wl.fragments[0].mu,
             "api": "ddl_plan_merge" if args.api == "plan" else "ddl_merge_batch",
             "launches_per_step": launches_per_step,
-            "tile_elems": ddl.get_option("tile_elems"),
-            "blocks_per_cu": ddl.get_option("blocks_per_cu"),
+            "replicas": replicas,
+            "tiles_per_block": ddl.get_option("tiles_per_block"),
+            "max_blocks_per_cu": ddl.get_option("max_blocks_per_cu"),
         },
         "achieved_gbps": alg_bytes / (wall_ms * 1e-3) / 1e9,
         "algorithmic_bytes_per_step": alg_bytes,

@@ -203,11 +203,10 @@ DDL_API size_t ddl_plan_num_elements(const ddl_plan* plan);
 DDL_API ddl_status ddl_copy_probe(void* dst, const void* src, size_t bytes, void* hip_stream);
 
 /*
- * Launch-shape knobs, for measurement.  Names: "tile_elems" (elements per work tile, a
- * multiple of 8192, default chosen by the library), "blocks_per_cu" (0: one workgroup per
- * tile; k > 0: a grid of k * #CU workgroups that stride over the tiles).  Affects later calls
- * and plans created later.  Unknown name or bad value: INVALID_ARG.  ddl_get_option writes
- * the current value.
+ * Launch-shape knobs, for measurement.  Names: "tiles_per_block" (how many consecutive
+ * 1024-element tiles one workgroup walks, 1..1024), "max_blocks_per_cu" (0: no cap; k in
+ * 3..64: at most k workgroups resident per compute unit).  Affects later calls.  Unknown name
+ * or bad value: INVALID_ARG.  ddl_get_option writes the current value.
  */
 DDL_API ddl_status ddl_set_option(const char* name, long value);
 DDL_API ddl_status ddl_get_option(const char* name, long* value_out);

@@ -6,6 +6,7 @@ library lands next to this file so that it travels with the source tree.
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -26,11 +27,18 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextr
 
 def _compile(src: str, extra) -> str:
     obj = os.path.join(BUILD_DIR, os.path.splitext(src)[0] + ".o")
-    cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, "-Rpass-analysis=kernel-resource-usage", *extra, "-c",
+           os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         sys.stderr.write(r.stdout + r.stderr)
         raise RuntimeError(f"hipcc failed on {src}")
+    # No kernel may use private (scratch) memory: the kernels keep everything in registers,
+    # and a by-value argument that got copied to scratch must never be addressed as constant
+    # memory.
+    scratch = [int(m) for m in re.findall(r"ScratchSize \[bytes/lane\]: (\d+)", r.stderr)]
+    if any(scratch):
+        raise RuntimeError(f"{src}: a kernel uses {max(scratch)} bytes/lane of scratch memory")
     return obj
 
 

@@ -1,7 +1,8 @@
 // Structures shared by the host side of libddlsync and its gfx950 kernels.
 //
-// A launch works on "tiles": fixed-size element ranges of the tensors ("segments") of up to
-// DDL_MAX_ITEMS fragments that share learner dtype and number of contributing learners.
+// A launch works on "tiles": runs of DDL_TILE consecutive elements of the tensors ("segments")
+// of up to DDL_MAX_ITEMS fragments that share learner dtype and number of contributing
+// learners.  A workgroup handles `tiles_per_block` consecutive tiles of the launch.
 // Segment descriptors live in device memory (or, for the single flat fragment, inside the
 // kernel argument block); everything that changes per sync -- weights, which learners
 // contribute, lr, mu -- travels in the kernel argument block, i.e. in constant memory that
@@ -12,7 +13,8 @@
 #define DDL_MAXL 16         // learners per fragment, = DDL_MAX_LEARNERS of the public header
 #define DDL_MAX_ITEMS 8     // fragments per launch
 #define DDL_BLOCK 256       // threads per workgroup: 4 wavefronts of 64
-#define DDL_TILE_QUANTUM 8192  // tile sizes are multiples of this many elements
+#define DDL_TILE (DDL_BLOCK * 4)  // elements per tile: one group of four per lane
+#define DDL_LDS_PER_CU (160 * 1024)  // bytes of LDS per compute unit on gfx950
 
 struct DdlSegDesc {
     float* theta;                   // n fp32, read and written
@@ -34,14 +36,19 @@ struct DdlItem {
     float w[DDL_MAXL];      // normalised weights of the contributing learners, compacted
     uint8_t idx[DDL_MAXL];  // learner index of compacted entry j
     float lr, mu;
-    uint32_t pad[2];
+    uint32_t coarse_begin;  // first entry of the fragment's coarse index in DdlLaunchArgs::coarse
+    uint32_t coarse_shift;  // entry i covers tiles [i << shift, (i + 1) << shift)
 };
 static_assert(sizeof(DdlItem) == 112, "item layout");
 
 struct DdlLaunchArgs {
     const DdlSegDesc* segs;  // device table (unused by the flat variant)
+    // Coarse index into the table: entry i of a fragment is the descriptor that holds tile
+    // i << shift (clamped to the last descriptor past the end), so a tile's descriptor lies
+    // between entries i and i + 1 -- usually the same one, and no search is needed.
+    const uint32_t* coarse;
     uint32_t total_tiles;
-    uint32_t tile_elems;     // multiple of DDL_TILE_QUANTUM
+    uint32_t tiles_per_block;  // >= 1
     int32_t num_items;
     int32_t pad;
     DdlItem item[DDL_MAX_ITEMS];
@@ -51,8 +58,9 @@ static_assert(sizeof(DdlLaunchArgs) <= 4096, "kernel argument block limit");
 
 // Launches the merge kernel specialised for (learner dtype, contributing learners, flat or
 // table).  dtype: 0 fp32, 1 bf16 (values of ddl_dtype).  Returns a hipError_t as int.
-int ddl_launch_merge(int dtype, int Mq, bool flat, uint32_t grid, void* stream,
+// lds_bytes of (unused) dynamic LDS per workgroup cap how many workgroups a compute unit holds.
+int ddl_launch_merge(int dtype, int Mq, bool flat, uint32_t grid, uint32_t lds_bytes, void* stream,
                      const DdlLaunchArgs& args);
 
-// Launches the plain 16-byte-per-lane copy of n16 * 16 bytes.
+// Launches the plain 16-byte-per-lane copy of n16 * 16 bytes; grid = ceil(n16 / DDL_BLOCK).
 int ddl_launch_copy(void* dst, const void* src, uint64_t n16, uint32_t grid, void* stream);

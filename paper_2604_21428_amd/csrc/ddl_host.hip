@@ -36,8 +36,8 @@ ddl_status runtime_error(hipError_t e, const char* what)
 // options and per-device state
 // ------------------------------------------------------------------------------------------
 std::mutex g_mu;  // guards options, device state and the staging ring
-long g_tile_elems = 2 * DDL_TILE_QUANTUM;
-long g_blocks_per_cu = 0;
+long g_tiles_per_block = 1;    // consecutive tiles a workgroup walks
+long g_max_blocks_per_cu = 4;  // 0: no cap; k: at most k resident workgroups per compute unit
 
 constexpr int kMaxDevices = 16;
 constexpr int kSlots = 4;
@@ -51,8 +51,6 @@ struct Slot {
 };
 
 struct DeviceState {
-    bool init = false;
-    int cus = 0;
     Slot slot[kSlots];
     unsigned next = 0;
 };
@@ -66,22 +64,23 @@ ddl_status device_state(DeviceState** out)
         g_err = "device index out of range";
         return DDL_ERR_RUNTIME;
     }
-    DeviceState& s = g_dev[dev];
-    if (!s.init) {
-        int cus = 0;
-        DDL_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-        s.cus = cus > 0 ? cus : 256;
-        s.init = true;
-    }
-    *out = &s;
+    *out = &g_dev[dev];
     return DDL_OK;
 }
 
-uint32_t grid_for(uint32_t total_tiles, const DeviceState& ds)
+uint32_t grid_for(uint32_t total_tiles)
 {
-    if (g_blocks_per_cu <= 0) return total_tiles;
-    const uint64_t cap = (uint64_t)g_blocks_per_cu * (uint64_t)ds.cus;
-    return (uint32_t)std::min<uint64_t>(total_tiles, cap);
+    const uint64_t g = (uint64_t)g_tiles_per_block;
+    return (uint32_t)(((uint64_t)total_tiles + g - 1) / g);
+}
+
+// Dynamic LDS requested per workgroup purely to cap residency: floor(LDS per CU / k), kept
+// within the 64 KiB a kernel may ask for without opting in.
+uint32_t lds_cap_bytes()
+{
+    if (g_max_blocks_per_cu <= 0) return 0;
+    uint32_t b = (uint32_t)(DDL_LDS_PER_CU / g_max_blocks_per_cu) & ~511u;
+    return b > 64 * 1024 ? 64 * 1024 : b;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -223,7 +222,8 @@ void fill_desc(DdlSegDesc& d, float* theta, float* v, const void* const* learner
 }
 
 void fill_item(DdlItem& it, const Quorum& q, float lr, float mu, uint32_t seg_begin,
-               uint32_t num_segs, uint32_t tile_off)
+               uint32_t num_segs, uint32_t tile_off, uint32_t coarse_begin = 0,
+               uint32_t coarse_shift = 0)
 {
     std::memset(&it, 0, sizeof it);
     it.seg_begin = seg_begin;
@@ -234,6 +234,8 @@ void fill_item(DdlItem& it, const Quorum& q, float lr, float mu, uint32_t seg_be
     std::memcpy(it.idx, q.idx, sizeof it.idx);
     it.lr = lr;
     it.mu = mu;
+    it.coarse_begin = coarse_begin;
+    it.coarse_shift = coarse_shift;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -241,6 +243,7 @@ void fill_item(DdlItem& it, const Quorum& q, float lr, float mu, uint32_t seg_be
 // ------------------------------------------------------------------------------------------
 struct FragInfo {
     uint32_t seg_begin = 0, num_segs = 0, tiles = 0;
+    uint32_t coarse_begin = 0, coarse_shift = 0;
     int M = 0;
     ddl_dtype dt = DDL_F32;
     uint64_t elems = 0;
@@ -250,9 +253,39 @@ struct FragInfo {
 struct Table {
     std::vector<DdlSegDesc> segs;  // empty segments are left out
     std::vector<FragInfo> frags;
-    uint32_t tile_elems = 0;
+    std::vector<uint32_t> coarse;  // per fragment: descriptor (relative) holding tile i << shift
     uint64_t elems = 0;
+
+    size_t seg_bytes() const { return segs.size() * sizeof(DdlSegDesc); }
+    size_t bytes() const { return seg_bytes() + coarse.size() * sizeof(uint32_t); }
+    // Device image: the descriptors followed by the coarse index.
+    void copy_to(void* dst) const
+    {
+        std::memcpy(dst, segs.data(), seg_bytes());
+        std::memcpy(static_cast<char*>(dst) + seg_bytes(), coarse.data(),
+                    coarse.size() * sizeof(uint32_t));
+    }
 };
+
+// About four coarse entries per descriptor: a tile's two bracketing entries are then almost
+// always equal.  One extra entry past the end keeps entry i + 1 readable for every tile.
+void build_coarse(Table& T, FragInfo& fi)
+{
+    fi.coarse_begin = (uint32_t)T.coarse.size();
+    fi.coarse_shift = 0;
+    if (fi.num_segs == 0) return;
+    const uint64_t target = 4ull * fi.num_segs;
+    while (fi.coarse_shift < 31 && ((uint64_t)fi.tiles >> (fi.coarse_shift + 1)) >= target)
+        ++fi.coarse_shift;
+    const uint32_t entries = (fi.tiles >> fi.coarse_shift) + 2;
+    const DdlSegDesc* segs = T.segs.data() + fi.seg_begin;
+    uint32_t s = 0;
+    for (uint32_t i = 0; i < entries; ++i) {
+        const uint64_t tile = (uint64_t)i << fi.coarse_shift;
+        while (s + 1 < fi.num_segs && segs[s + 1].tile_begin <= tile) ++s;
+        T.coarse.push_back(tile < fi.tiles ? s : fi.num_segs - 1);
+    }
+}
 
 ddl_status check_fragment_shape(const ddl_fragment& f)
 {
@@ -267,11 +300,11 @@ ddl_status check_fragment_shape(const ddl_fragment& f)
 // Builds the descriptors.  learner_bits[i] says which learners of fragment i must be valid
 // and take part in the overlap check.
 ddl_status build_table(const ddl_fragment* frags, int num_frags, const uint32_t* learner_bits,
-                       uint32_t tile_elems, Table& T)
+                       Table& T)
 {
     T.segs.clear();
+    T.coarse.clear();
     T.frags.assign((size_t)num_frags, FragInfo());
-    T.tile_elems = tile_elems;
     T.elems = 0;
     std::vector<Range> ranges;
     for (int i = 0; i < num_frags; ++i) {
@@ -300,12 +333,13 @@ ddl_status build_table(const ddl_fragment* frags, int num_frags, const uint32_t*
             DdlSegDesc d;
             fill_desc(d, g.theta, g.v, g.learner_params, f.M, g.n, (uint32_t)tiles);
             T.segs.push_back(d);
-            tiles += (g.n + tile_elems - 1) / tile_elems;
+            tiles += (g.n + DDL_TILE - 1) / DDL_TILE;
             fi.elems += g.n;
         }
         if (tiles > 0x7fffffffull) return DDL_ERR_INVALID_ARG;
         fi.tiles = (uint32_t)tiles;
         fi.num_segs = (uint32_t)T.segs.size() - fi.seg_begin;
+        build_coarse(T, fi);
         T.elems += fi.elems;
     }
     if (ranges_alias(ranges)) return DDL_ERR_ALIAS;
@@ -321,8 +355,8 @@ struct Work {
 
 // Enqueue the fragments in `work`: one launch per group of up to DDL_MAX_ITEMS fragments with
 // the same learner dtype and number of contributing learners.
-ddl_status launch_work(const Table& T, const DdlSegDesc* d_segs, std::vector<Work>& work,
-                       const DeviceState& ds, void* stream)
+ddl_status launch_work(const Table& T, const void* d_table, std::vector<Work>& work,
+                       void* stream)
 {
     std::stable_sort(work.begin(), work.end(), [&](const Work& a, const Work& b) {
         const FragInfo& fa = T.frags[a.frag];
@@ -335,8 +369,10 @@ ddl_status launch_work(const Table& T, const DdlSegDesc* d_segs, std::vector<Wor
         const FragInfo& f0 = T.frags[work[i].frag];
         DdlLaunchArgs a;
         std::memset(&a, 0, sizeof a);
-        a.segs = d_segs;
-        a.tile_elems = T.tile_elems;
+        a.segs = static_cast<const DdlSegDesc*>(d_table);
+        a.coarse = reinterpret_cast<const uint32_t*>(static_cast<const char*>(d_table) +
+                                                     T.seg_bytes());
+        a.tiles_per_block = (uint32_t)g_tiles_per_block;
         uint64_t tiles = 0;
         int items = 0;
         size_t j = i;
@@ -346,7 +382,7 @@ ddl_status launch_work(const Table& T, const DdlSegDesc* d_segs, std::vector<Wor
             if (f.tiles == 0) continue;
             if (tiles + f.tiles > 0x7fffffffull) break;
             fill_item(a.item[items], work[j].q, work[j].lr, work[j].mu, f.seg_begin, f.num_segs,
-                      (uint32_t)tiles);
+                      (uint32_t)tiles, f.coarse_begin, f.coarse_shift);
             tiles += f.tiles;
             ++items;
         }
@@ -354,7 +390,7 @@ ddl_status launch_work(const Table& T, const DdlSegDesc* d_segs, std::vector<Wor
             a.num_items = items;
             a.total_tiles = (uint32_t)tiles;
             const int e = ddl_launch_merge((int)f0.dt, work[i].q.Mq, false,
-                                           grid_for(a.total_tiles, ds), stream, a);
+                                           grid_for(a.total_tiles), lds_cap_bytes(), stream, a);
             if (e != (int)hipSuccess) return runtime_error((hipError_t)e, "merge kernel launch");
         }
         if (j == i) return DDL_ERR_INVALID_ARG;  // cannot happen: a lone fragment always fits
@@ -379,20 +415,17 @@ ddl_status merge_flat(float* theta, float* v, const void* const* learner_params,
     if (ranges_alias(ranges)) return DDL_ERR_ALIAS;
 
     std::lock_guard<std::mutex> lock(g_mu);
-    DeviceState* ds = nullptr;
-    ddl_status st = device_state(&ds);
-    if (st != DDL_OK) return st;
-    const uint64_t tile = (uint64_t)g_tile_elems;
-    const uint64_t tiles = (n + tile - 1) / tile;
+    const uint64_t tiles = (n + DDL_TILE - 1) / DDL_TILE;
     if (tiles > 0x7fffffffull) return DDL_ERR_INVALID_ARG;
     DdlLaunchArgs a;
     std::memset(&a, 0, sizeof a);
-    a.tile_elems = (uint32_t)tile;
+    a.tiles_per_block = (uint32_t)g_tiles_per_block;
     a.total_tiles = (uint32_t)tiles;
     a.num_items = 1;
     fill_desc(a.flat, theta, v, lp, M, n, 0);
     fill_item(a.item[0], q, lr, mu, 0, 1, 0);
-    const int e = ddl_launch_merge((int)dt, q.Mq, true, grid_for(a.total_tiles, *ds), stream, a);
+    const int e = ddl_launch_merge((int)dt, q.Mq, true, grid_for(a.total_tiles), lds_cap_bytes(),
+                                   stream, a);
     if (e != (int)hipSuccess) return runtime_error((hipError_t)e, "merge kernel launch");
     return DDL_OK;
 }
@@ -402,7 +435,7 @@ ddl_status merge_flat(float* theta, float* v, const void* const* learner_params,
 struct ddl_plan {
     int device = 0;
     Table table;
-    DdlSegDesc* d_segs = nullptr;
+    void* d_table = nullptr;  // descriptors followed by the coarse index
 };
 
 extern "C" {
@@ -485,7 +518,7 @@ ddl_status ddl_merge_batch(const ddl_fragment* frags, int num_frags, void* hip_s
     ddl_status st = device_state(&ds);
     if (st != DDL_OK) return st;
     Table T;
-    st = build_table(frags, num_frags, bits.data(), (uint32_t)g_tile_elems, T);
+    st = build_table(frags, num_frags, bits.data(), T);
     if (st != DDL_OK) return st;
     if (T.segs.empty()) return DDL_OK;
 
@@ -496,7 +529,7 @@ ddl_status ddl_merge_batch(const ddl_fragment* frags, int num_frags, void* hip_s
         DDL_HIP(hipEventSynchronize(sl.done));
         sl.pending = false;
     }
-    const size_t bytes = T.segs.size() * sizeof(DdlSegDesc);
+    const size_t bytes = T.bytes();
     if (bytes > sl.cap) {
         if (sl.host) DDL_HIP(hipHostFree(sl.host));
         if (sl.dev) DDL_HIP(hipFree(sl.dev));
@@ -508,10 +541,10 @@ ddl_status ddl_merge_batch(const ddl_fragment* frags, int num_frags, void* hip_s
         sl.cap = cap;
     }
     if (!sl.done) DDL_HIP(hipEventCreateWithFlags(&sl.done, hipEventDisableTiming));
-    std::memcpy(sl.host, T.segs.data(), bytes);
+    T.copy_to(sl.host);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     DDL_HIP(hipMemcpyAsync(sl.dev, sl.host, bytes, hipMemcpyHostToDevice, stream));
-    st = launch_work(T, static_cast<const DdlSegDesc*>(sl.dev), work, *ds, hip_stream);
+    st = launch_work(T, sl.dev, work, hip_stream);
     // Record even after a failed launch: the copy above may still be in flight.
     if (hipEventRecord(sl.done, stream) == hipSuccess) sl.pending = true;
     return st;
@@ -532,7 +565,7 @@ ddl_status ddl_plan_create(const ddl_fragment* frags, int num_frags, ddl_plan** 
     ddl_status st;
     {
         std::lock_guard<std::mutex> lock(g_mu);
-        st = build_table(frags, num_frags, bits.data(), (uint32_t)g_tile_elems, p->table);
+        st = build_table(frags, num_frags, bits.data(), p->table);
     }
     if (st != DDL_OK) {
         delete p;
@@ -540,13 +573,14 @@ ddl_status ddl_plan_create(const ddl_fragment* frags, int num_frags, ddl_plan** 
     }
     hipError_t e = hipGetDevice(&p->device);
     if (e == hipSuccess && !p->table.segs.empty()) {
-        const size_t bytes = p->table.segs.size() * sizeof(DdlSegDesc);
-        e = hipMalloc(reinterpret_cast<void**>(&p->d_segs), bytes);
-        if (e == hipSuccess)
-            e = hipMemcpy(p->d_segs, p->table.segs.data(), bytes, hipMemcpyHostToDevice);
+        const size_t bytes = p->table.bytes();
+        std::vector<char> image(bytes);
+        p->table.copy_to(image.data());
+        e = hipMalloc(&p->d_table, bytes);
+        if (e == hipSuccess) e = hipMemcpy(p->d_table, image.data(), bytes, hipMemcpyHostToDevice);
     }
     if (e != hipSuccess) {
-        if (p->d_segs) (void)hipFree(p->d_segs);
+        if (p->d_table) (void)hipFree(p->d_table);
         delete p;
         return runtime_error(e, "plan upload");
     }
@@ -581,18 +615,15 @@ ddl_status ddl_plan_merge(ddl_plan* plan, const ddl_sync* syncs, int count, void
         work.push_back(wk);
     }
     std::lock_guard<std::mutex> lock(g_mu);
-    DeviceState* ds = nullptr;
-    const ddl_status st = device_state(&ds);
-    if (st != DDL_OK) return st;
-    return launch_work(T, plan->d_segs, work, *ds, hip_stream);
+    return launch_work(T, plan->d_table, work, hip_stream);
 }
 
 ddl_status ddl_plan_destroy(ddl_plan* plan)
 {
     if (!plan) return DDL_OK;
     ddl_status st = DDL_OK;
-    if (plan->d_segs) {
-        const hipError_t e = hipFree(plan->d_segs);
+    if (plan->d_table) {
+        const hipError_t e = hipFree(plan->d_table);
         if (e != hipSuccess) st = runtime_error(e, "hipFree");
     }
     delete plan;
@@ -611,8 +642,9 @@ ddl_status ddl_copy_probe(void* dst, const void* src, size_t bytes, void* hip_st
     const uintptr_t d = (uintptr_t)dst, s = (uintptr_t)src;
     if (d < s + bytes && s < d + bytes) return DDL_ERR_ALIAS;
     const uint64_t n16 = bytes / 16;
-    const uint64_t blocks = (n16 + DDL_BLOCK * 4 - 1) / (DDL_BLOCK * 4);
-    const uint32_t grid = (uint32_t)std::min<uint64_t>(blocks, 0x7fffffffull);
+    const uint64_t blocks = (n16 + DDL_BLOCK - 1) / DDL_BLOCK;
+    if (blocks > 0x7fffffffull) return DDL_ERR_INVALID_ARG;
+    const uint32_t grid = (uint32_t)blocks;
     const int e = ddl_launch_copy(dst, src, n16, grid, hip_stream);
     if (e != (int)hipSuccess) return runtime_error((hipError_t)e, "copy kernel launch");
     return DDL_OK;
@@ -622,15 +654,14 @@ ddl_status ddl_set_option(const char* name, long value)
 {
     if (!name) return DDL_ERR_INVALID_ARG;
     std::lock_guard<std::mutex> lock(g_mu);
-    if (!std::strcmp(name, "tile_elems")) {
-        if (value < DDL_TILE_QUANTUM || value % DDL_TILE_QUANTUM || value > (1L << 30))
-            return DDL_ERR_INVALID_ARG;
-        g_tile_elems = value;
+    if (!std::strcmp(name, "tiles_per_block")) {
+        if (value < 1 || value > 1024) return DDL_ERR_INVALID_ARG;
+        g_tiles_per_block = value;
         return DDL_OK;
     }
-    if (!std::strcmp(name, "blocks_per_cu")) {
-        if (value < 0 || value > 1024) return DDL_ERR_INVALID_ARG;
-        g_blocks_per_cu = value;
+    if (!std::strcmp(name, "max_blocks_per_cu")) {
+        if (value != 0 && (value < 3 || value > 64)) return DDL_ERR_INVALID_ARG;
+        g_max_blocks_per_cu = value;
         return DDL_OK;
     }
     return DDL_ERR_INVALID_ARG;
@@ -640,12 +671,12 @@ ddl_status ddl_get_option(const char* name, long* value_out)
 {
     if (!name || !value_out) return DDL_ERR_INVALID_ARG;
     std::lock_guard<std::mutex> lock(g_mu);
-    if (!std::strcmp(name, "tile_elems")) {
-        *value_out = g_tile_elems;
+    if (!std::strcmp(name, "tiles_per_block")) {
+        *value_out = g_tiles_per_block;
         return DDL_OK;
     }
-    if (!std::strcmp(name, "blocks_per_cu")) {
-        *value_out = g_blocks_per_cu;
+    if (!std::strcmp(name, "max_blocks_per_cu")) {
+        *value_out = g_max_blocks_per_cu;
         return DDL_OK;
     }
     return DDL_ERR_INVALID_ARG;

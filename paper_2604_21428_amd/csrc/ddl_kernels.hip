@@ -5,13 +5,19 @@
 // The work is a streaming reduction with no reuse: per element it reads Mq learner values
 // (2 or 4 bytes each) plus Theta and v, and writes Theta and v -- about 0.7 flop per byte --
 // so the kernel is organised around HBM, not around the ALUs:
-//   * every lane moves 16 bytes per access and the lanes of a wavefront cover consecutive
-//     addresses, so each wave-wide load or store is one contiguous run of 1 KiB (Theta / v /
-//     fp32 learners / 8-wide bf16) or 512 B (4-wide bf16);
-//   * all loads of DDL_UNROLL vector groups are issued before the first use, which keeps
-//     (16 Mq + 64) * UNROLL bytes per lane in flight;
+//   * the unit of work is a tile of DDL_TILE = 1024 consecutive elements, one group of four
+//     elements per lane: every wave-wide access is one contiguous run (1 KiB of Theta, v or
+//     an fp32 learner, 512 B of a bf16 learner), and the tiles in flight across the chip at
+//     any moment form one compact address window per array, which is what keeps DRAM pages
+//     open.  Measured on MI355X, this beats wider per-lane groups, deeper unrolling and
+//     persistent grids, all of which widen that window;
+//   * a workgroup walks `tiles_per_block` consecutive tiles, so the tile -> tensor lookup
+//     (scalar loads from the descriptor table, addressed as constant memory) is paid once
+//     per run of tiles, not once per tile;
 //   * weights, learner selection, lr and mu come from the kernel argument block (scalar
 //     loads into SGPRs); absent learners do not appear in it and are never addressed;
+//   * every access is non-temporal: each byte is touched once per sync, and mixing cached
+//     and streaming accesses to Theta and v costs 10-20 %;
 //   * Delta, the new v and the new Theta stay in registers; Theta and v are read once and
 //     written once.
 #include <hip/hip_runtime.h>
@@ -19,13 +25,16 @@
 #include "ddl_device.h"
 
 #ifndef DDL_NT_LOAD
-#define DDL_NT_LOAD 1   // learner / Theta / v loads bypass-hinted: every byte is used once
+#define DDL_NT_LOAD 1
+#endif
+#ifndef DDL_NT_STATE_LOAD
+#define DDL_NT_STATE_LOAD DDL_NT_LOAD
 #endif
 #ifndef DDL_NT_STORE
 #define DDL_NT_STORE 1
 #endif
-#ifndef DDL_BF16_VEC
-#define DDL_BF16_VEC 8  // bf16 elements per lane per group: 8 (16-byte loads) or 4 (8-byte)
+#ifndef DDL_PAIR
+#define DDL_PAIR 0  // 1: issue the loads of two consecutive tiles before the first use
 #endif
 
 namespace {
@@ -35,19 +44,16 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // All tensor accesses go through explicit global-address-space pointers built from a
-// 64-bit base held in scalar registers plus a 32-bit per-lane index, which is the form the
-// global_load / global_store "saddr" encoding takes directly.
+// 64-bit base held in scalar registers plus a 32-bit per-lane index.
 #define DDL_GLOBAL __attribute__((address_space(1)))
+#define DDL_CONST __attribute__((address_space(4)))
 
-template <typename T>
+template <typename T, bool NT>
 __device__ __forceinline__ T ld(uint64_t base, uint32_t index)
 {
     const DDL_GLOBAL T* p = reinterpret_cast<const DDL_GLOBAL T*>(base) + index;
-#if DDL_NT_LOAD
-    return __builtin_nontemporal_load(p);
-#else
+    if (NT) return __builtin_nontemporal_load(p);
     return *p;
-#endif
 }
 
 template <typename T>
@@ -62,9 +68,8 @@ __device__ __forceinline__ void st(uint64_t base, uint32_t index, T x)
 }
 
 // Values that are the same for every lane of a workgroup (tile geometry, base addresses) are
-// moved to scalar registers explicitly: descriptor fields read from the device table arrive
-// in vector registers, and sixteen 64-bit learner addresses held per lane would halve the
-// number of resident wavefronts.
+// moved to scalar registers explicitly, so that sixteen 64-bit learner addresses do not sit
+// in vector registers of every lane.
 __device__ __forceinline__ uint32_t uniform(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
 __device__ __forceinline__ uint64_t uniform(uint64_t x)
 {
@@ -77,12 +82,10 @@ __device__ __forceinline__ uint64_t uniform(uint64_t x)
 __device__ __forceinline__ float bf16_even(uint32_t pair) { return __uint_as_float(pair << 16); }
 __device__ __forceinline__ float bf16_odd(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }
 
-// Learner element types.  VEC = elements one lane handles per group, RAW = the register
-// image of those VEC elements as loaded.
+// Learner element types: `raw` is the register image of the four elements a lane loads.
 struct LearnerF32 {
     typedef float elem;
     typedef u32x4 raw;
-    static constexpr int VEC = 4;  // elements per lane per group
     static __device__ __forceinline__ void widen(const raw& r, float (&x)[4])
     {
         x[0] = __uint_as_float(r.x);
@@ -93,48 +96,20 @@ struct LearnerF32 {
     static __device__ __forceinline__ float widen1(float e) { return e; }
 };
 
-struct LearnerBF16x8 {
-    typedef uint16_t elem;
-    typedef u32x4 raw;
-    static constexpr int VEC = 8;
-    static __device__ __forceinline__ void widen(const raw& r, float (&x)[8])
-    {
-        x[0] = bf16_even(r.x); x[1] = bf16_odd(r.x);
-        x[2] = bf16_even(r.y); x[3] = bf16_odd(r.y);
-        x[4] = bf16_even(r.z); x[5] = bf16_odd(r.z);
-        x[6] = bf16_even(r.w); x[7] = bf16_odd(r.w);
-    }
-    static __device__ __forceinline__ float widen1(uint16_t e)
-    {
-        return __uint_as_float((uint32_t)e << 16);
-    }
-};
-
-struct LearnerBF16x4 {
+struct LearnerBF16 {
     typedef uint16_t elem;
     typedef u32x2 raw;
-    static constexpr int VEC = 4;
     static __device__ __forceinline__ void widen(const raw& r, float (&x)[4])
     {
-        x[0] = bf16_even(r.x); x[1] = bf16_odd(r.x);
-        x[2] = bf16_even(r.y); x[3] = bf16_odd(r.y);
+        x[0] = bf16_even(r.x);
+        x[1] = bf16_odd(r.x);
+        x[2] = bf16_even(r.y);
+        x[3] = bf16_odd(r.y);
     }
     static __device__ __forceinline__ float widen1(uint16_t e)
     {
         return __uint_as_float((uint32_t)e << 16);
     }
-};
-
-// How many vector groups a lane keeps in flight, by register budget: a group holds
-// 4 Mq (or 2 Mq) learner registers plus 2 VEC for Theta and v.
-template <typename L, int MQ>
-struct Unroll {
-#ifdef DDL_UNROLL
-    static constexpr int value = DDL_UNROLL;
-#else
-    static constexpr int regs = (int)(sizeof(typename L::raw) / 4) * MQ + 2 * L::VEC;
-    static constexpr int value = regs <= 24 ? 4 : (regs <= 48 ? 2 : 1);
-#endif
 };
 
 // One element: Delta = sum_j w_j (Theta - x_j); v' = mu v + Delta;
@@ -152,51 +127,42 @@ __device__ __forceinline__ void outer_step(float& theta, float& v, const float (
     v = v_new;
 }
 
-// U vector groups per lane: group u of this lane is `g + u * DDL_BLOCK`.  th / vv / lp are
-// the byte addresses of the tile's first element in each array.
-template <typename L, int MQ, int U>
-__device__ __forceinline__ void merge_groups(uint64_t th, uint64_t vv, const uint64_t (&lp)[MQ],
-                                             const float (&w)[MQ], float lr, float mu, uint32_t g)
+// NT full tiles starting at element 0 of the given bases: lane handles group `lane` of each.
+// All loads are issued before the first use.
+template <typename L, int MQ, int NT>
+__device__ __forceinline__ void merge_full_tiles(uint64_t th, uint64_t vv, const uint64_t (&lp)[MQ],
+                                                 const float (&w)[MQ], float lr, float mu)
 {
-    constexpr int VEC = L::VEC;
-    constexpr int Q = VEC / 4;  // float4 per group for Theta and for v
-    typename L::raw raw[U][MQ];
-    f32x4 T[U][Q], V[U][Q];
+    typename L::raw raw[NT][MQ];
+    f32x4 T[NT], V[NT];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const uint32_t gi = g + u * DDL_BLOCK;
+    for (int u = 0; u < NT; ++u) {
+        const uint32_t g = threadIdx.x + u * DDL_BLOCK;
 #pragma unroll
-        for (int j = 0; j < MQ; ++j) raw[u][j] = ld<typename L::raw>(lp[j], gi);
-#pragma unroll
-        for (int q = 0; q < Q; ++q) {
-            T[u][q] = ld<f32x4>(th, gi * Q + q);
-            V[u][q] = ld<f32x4>(vv, gi * Q + q);
-        }
+        for (int j = 0; j < MQ; ++j) raw[u][j] = ld<typename L::raw, DDL_NT_LOAD>(lp[j], g);
+        T[u] = ld<f32x4, DDL_NT_STATE_LOAD>(th, g);
+        V[u] = ld<f32x4, DDL_NT_STATE_LOAD>(vv, g);
     }
-    // Keep every load above ahead of the arithmetic: the bytes in flight are the point.
-    __builtin_amdgcn_sched_barrier(0);
+    if (NT > 1) __builtin_amdgcn_sched_barrier(0);  // keep the loads ahead of the arithmetic
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const uint32_t gi = g + u * DDL_BLOCK;
-        float x[MQ][VEC];
+    for (int u = 0; u < NT; ++u) {
+        const uint32_t g = threadIdx.x + u * DDL_BLOCK;
+        float x[MQ][4];
 #pragma unroll
         for (int j = 0; j < MQ; ++j) L::widen(raw[u][j], x[j]);
+        float t4[4] = {T[u].x, T[u].y, T[u].z, T[u].w};
+        float v4[4] = {V[u].x, V[u].y, V[u].z, V[u].w};
 #pragma unroll
-        for (int q = 0; q < Q; ++q) {
-            float t4[4] = {T[u][q].x, T[u][q].y, T[u][q].z, T[u][q].w};
-            float v4[4] = {V[u][q].x, V[u][q].y, V[u][q].z, V[u][q].w};
+        for (int k = 0; k < 4; ++k) {
+            float xe[MQ];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                float xe[MQ];
-#pragma unroll
-                for (int j = 0; j < MQ; ++j) xe[j] = x[j][q * 4 + k];
-                outer_step<MQ>(t4[k], v4[k], xe, w, lr, mu);
-            }
-            f32x4 tn = {t4[0], t4[1], t4[2], t4[3]};
-            f32x4 vn = {v4[0], v4[1], v4[2], v4[3]};
-            st<f32x4>(th, gi * Q + q, tn);
-            st<f32x4>(vv, gi * Q + q, vn);
+            for (int j = 0; j < MQ; ++j) xe[j] = x[j][k];
+            outer_step<MQ>(t4[k], v4[k], xe, w, lr, mu);
         }
+        const f32x4 tn = {t4[0], t4[1], t4[2], t4[3]};
+        const f32x4 vn = {v4[0], v4[1], v4[2], v4[3]};
+        st<f32x4>(th, g, tn);
+        st<f32x4>(vv, g, vn);
     }
 }
 
@@ -216,15 +182,27 @@ __device__ __forceinline__ void merge_scalar(uint64_t th, uint64_t vv, const uin
     *(reinterpret_cast<DDL_GLOBAL float*>(vv) + e) = v;
 }
 
+// A ragged tile (the last of a tensor): guarded groups, then fewer than four left-overs.
+template <typename L, int MQ>
+__device__ __forceinline__ void merge_ragged_tile(uint64_t th, uint64_t vv, const uint64_t (&lp)[MQ],
+                                                  const float (&w)[MQ], float lr, float mu,
+                                                  uint32_t cnt)
+{
+    const uint32_t nvec = cnt / 4;
+    if (threadIdx.x < nvec) merge_full_tiles<L, MQ, 1>(th, vv, lp, w, lr, mu);
+    const uint32_t e = nvec * 4 + threadIdx.x;
+    if (e < cnt) merge_scalar<L, MQ>(th, vv, lp, w, lr, mu, e);
+}
+
 template <typename L, int MQ, bool FLAT>
 __global__ void __launch_bounds__(DDL_BLOCK) ddl_merge_kernel(const DdlLaunchArgs a)
 {
-    constexpr int VEC = L::VEC;
-    constexpr int U = Unroll<L, MQ>::value;
     typedef typename L::elem elem;
+    uint32_t tile = blockIdx.x * a.tiles_per_block;
+    const uint32_t last = min(tile + a.tiles_per_block, a.total_tiles);
 
-    for (uint32_t tile = blockIdx.x; tile < a.total_tiles; tile += gridDim.x) {
-        // Which fragment of the launch, then which of its segments, holds this tile.
+    while (tile < last) {
+        // Which fragment of the launch, then which of its tensors, holds this tile.
         int it = 0;
         if (!FLAT) {
             for (int k = 1; k < a.num_items; ++k)
@@ -232,23 +210,37 @@ __global__ void __launch_bounds__(DDL_BLOCK) ddl_merge_kernel(const DdlLaunchArg
         }
         const DdlItem& I = a.item[it];
         const uint32_t t = tile - I.tile_off;
-        const DdlSegDesc* sp;
+        // The descriptor table is read-only for the whole launch: address it as constant
+        // memory, so that these block-uniform lookups are scalar loads through the scalar
+        // cache instead of vector loads queueing behind the streaming traffic.
+        const DDL_CONST DdlSegDesc* sp;
         if (FLAT) {
-            sp = &a.flat;
+            // The one descriptor sits in the kernel-argument block.  Reach it through the
+            // kernarg segment pointer: taking the address of the by-value argument would make
+            // the compiler copy it to private memory, which is not constant address space.
+            sp = &((const DDL_CONST DdlLaunchArgs*)__builtin_amdgcn_kernarg_segment_ptr())->flat;
         } else {
-            const DdlSegDesc* segs = a.segs + I.seg_begin;
-            uint32_t lo = 0, hi = I.num_segs - 1;  // last segment whose tile_begin <= t
+            const DDL_CONST DdlSegDesc* segs =
+                reinterpret_cast<const DDL_CONST DdlSegDesc*>(reinterpret_cast<uint64_t>(a.segs)) +
+                I.seg_begin;
+            const DDL_CONST uint32_t* coarse =
+                reinterpret_cast<const DDL_CONST uint32_t*>(reinterpret_cast<uint64_t>(a.coarse)) +
+                I.coarse_begin + (t >> I.coarse_shift);
+            uint32_t lo = coarse[0], hi = coarse[1];  // last tensor whose tile_begin <= t
             while (lo < hi) {
                 const uint32_t mid = (lo + hi + 1) >> 1;
                 if (segs[mid].tile_begin <= t) lo = mid; else hi = mid - 1;
             }
             sp = segs + lo;
         }
-        const uint64_t off = (uint64_t)(t - sp->tile_begin) * a.tile_elems;  // elements
-        const uint64_t rem = sp->n - off;
-        const uint32_t cnt = uniform(rem < a.tile_elems ? (uint32_t)rem : a.tile_elems);
-        const uint64_t th = uniform(reinterpret_cast<uint64_t>(sp->theta) + off * 4);
-        const uint64_t vv = uniform(reinterpret_cast<uint64_t>(sp->v) + off * 4);
+        const uint64_t n = sp->n;
+        const uint32_t seg_tiles = (uint32_t)((n + DDL_TILE - 1) / DDL_TILE);
+        const uint32_t first_in_seg = t - sp->tile_begin;
+        // tiles of this tensor that this workgroup handles: [first_in_seg, end_in_seg)
+        const uint32_t end_in_seg = uniform(min(seg_tiles, first_in_seg + (last - tile)));
+        const uint64_t off = (uint64_t)first_in_seg * DDL_TILE;  // elements
+        uint64_t th = uniform(reinterpret_cast<uint64_t>(sp->theta) + off * 4);
+        uint64_t vv = uniform(reinterpret_cast<uint64_t>(sp->v) + off * 4);
         uint64_t lp[MQ];
         float w[MQ];
 #pragma unroll
@@ -260,49 +252,40 @@ __global__ void __launch_bounds__(DDL_BLOCK) ddl_merge_kernel(const DdlLaunchArg
         const bool vec_ok = uniform((uint32_t)(
             sp->base_aligned && ((I.present_bits & ~(uint32_t)sp->learner_aligned) == 0))) != 0;
 
-        if (vec_ok) {
-            const uint32_t nvec = cnt / VEC;
-            uint32_t g = threadIdx.x;
-            if (U > 1) {
-                for (; g + (U - 1) * DDL_BLOCK < nvec; g += U * DDL_BLOCK)
-                    merge_groups<L, MQ, U>(th, vv, lp, w, lr, mu, g);
+        uint32_t s = first_in_seg;
+        while (s < end_in_seg) {
+            const uint64_t rem = n - (uint64_t)s * DDL_TILE;
+            uint32_t step = 1;
+            if (!vec_ok) {
+                const uint32_t cnt = rem < DDL_TILE ? (uint32_t)rem : DDL_TILE;
+                for (uint32_t e = threadIdx.x; e < cnt; e += DDL_BLOCK)
+                    merge_scalar<L, MQ>(th, vv, lp, w, lr, mu, e);
+            } else if (DDL_PAIR && s + 2 <= end_in_seg && rem >= 2 * DDL_TILE) {
+                merge_full_tiles<L, MQ, 2>(th, vv, lp, w, lr, mu);
+                step = 2;
+            } else if (rem >= DDL_TILE) {
+                merge_full_tiles<L, MQ, 1>(th, vv, lp, w, lr, mu);
+            } else {
+                merge_ragged_tile<L, MQ>(th, vv, lp, w, lr, mu, (uint32_t)rem);
             }
-            for (; g < nvec; g += DDL_BLOCK) merge_groups<L, MQ, 1>(th, vv, lp, w, lr, mu, g);
-            const uint32_t e = nvec * VEC + threadIdx.x;  // fewer than VEC leftover elements
-            if (e < cnt) merge_scalar<L, MQ>(th, vv, lp, w, lr, mu, e);
-        } else {
-            for (uint32_t e = threadIdx.x; e < cnt; e += DDL_BLOCK)
-                merge_scalar<L, MQ>(th, vv, lp, w, lr, mu, e);
+            s += step;
+            th += (uint64_t)step * DDL_TILE * 4;
+            vv += (uint64_t)step * DDL_TILE * 4;
+#pragma unroll
+            for (int j = 0; j < MQ; ++j) lp[j] += (uint64_t)step * DDL_TILE * sizeof(elem);
         }
+        tile += end_in_seg - first_in_seg;
     }
 }
 
-#if DDL_BF16_VEC == 8
-typedef LearnerBF16x8 LearnerBF16;
-#else
-typedef LearnerBF16x4 LearnerBF16;
-#endif
-
-// Plain streaming copy, 16 bytes per lane, same access pattern and cache hints as the merge
+// Plain streaming copy, 16 bytes per lane, one group per lane, same cache hints as the merge
 // kernel: the yardstick for what this GPU's HBM sustains and for scaling profiler counters.
 __global__ void __launch_bounds__(DDL_BLOCK) ddl_copy_kernel(uint64_t dst, uint64_t src, uint64_t n16)
 {
-    constexpr uint32_t kPerBlock = DDL_BLOCK * 4;
-    for (uint64_t base = (uint64_t)blockIdx.x * kPerBlock; base < n16;
-         base += (uint64_t)gridDim.x * kPerBlock) {
-        const uint64_t s = src + base * 16, d = dst + base * 16;
-        const uint32_t left = n16 - base < kPerBlock ? (uint32_t)(n16 - base) : kPerBlock;
-        u32x4 r[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const uint32_t i = threadIdx.x + u * DDL_BLOCK;
-            if (i < left) r[u] = ld<u32x4>(s, i);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const uint32_t i = threadIdx.x + u * DDL_BLOCK;
-            if (i < left) st<u32x4>(d, i, r[u]);
-        }
+    const uint64_t base = (uint64_t)blockIdx.x * DDL_BLOCK;
+    if (base + threadIdx.x < n16) {
+        const u32x4 r = ld<u32x4, true>(src + base * 16, threadIdx.x);
+        st<u32x4>(dst + base * 16, threadIdx.x, r);
     }
 }
 
@@ -323,7 +306,7 @@ kernel_fn pick_mq(int Mq)
 
 }  // namespace
 
-int ddl_launch_merge(int dtype, int Mq, bool flat, uint32_t grid, void* stream,
+int ddl_launch_merge(int dtype, int Mq, bool flat, uint32_t grid, uint32_t lds_bytes, void* stream,
                      const DdlLaunchArgs& args)
 {
     kernel_fn k = nullptr;
@@ -332,7 +315,8 @@ int ddl_launch_merge(int dtype, int Mq, bool flat, uint32_t grid, void* stream,
     else if (dtype == 1)
         k = flat ? pick_mq<LearnerBF16, true>(Mq) : pick_mq<LearnerBF16, false>(Mq);
     if (!k || grid == 0) return (int)hipErrorInvalidValue;
-    hipLaunchKernelGGL(k, dim3(grid), dim3(DDL_BLOCK), 0, static_cast<hipStream_t>(stream), args);
+    hipLaunchKernelGGL(k, dim3(grid), dim3(DDL_BLOCK), lds_bytes, static_cast<hipStream_t>(stream),
+                       args);
     return (int)hipGetLastError();
 }
 

@@ -136,8 +136,11 @@ def test_argument_errors_need_no_device(ddl):
 
 
 def test_options(ddl):
-    assert ddl.get_option("tile_elems") % 8192 == 0
+    assert ddl.get_option("tiles_per_block") >= 1
+    assert ddl.get_option("max_blocks_per_cu") >= 0
     with pytest.raises(ddl.DdlError):
-        ddl.set_option("tile_elems", 12345)
+        ddl.set_option("tiles_per_block", 0)
     with pytest.raises(ddl.DdlError):
-        ddl.set_option("blocks_per_cu", -1)
+        ddl.set_option("max_blocks_per_cu", 2)
+    with pytest.raises(ddl.DdlError):
+        ddl.set_option("max_blocks_per_cu", -1)

@@ -204,27 +204,31 @@ def test_many_batches_reuse_the_staging_ring(ddl):
             check_segment(s, refs[si], f"run {k} seg {si}")
 
 
-@pytest.mark.parametrize("tile,bpc", [(8192, 0), (16384, 2), (65536, 0), (32768, 8)])
-def test_launch_shape_options(ddl, tile, bpc):
-    old = ddl.get_option("tile_elems"), ddl.get_option("blocks_per_cu")
+@pytest.mark.parametrize("tpb,cap", [(1, 0), (2, 0), (3, 4), (7, 0), (64, 8), (1024, 3)])
+def test_launch_shape_options(ddl, tpb, cap):
+    """Workgroups that walk several tiles (across tensor and fragment boundaries) and capped
+    residency give the same results."""
+    old = ddl.get_option("tiles_per_block"), ddl.get_option("max_blocks_per_cu")
     try:
-        ddl.set_option("tile_elems", tile)
-        ddl.set_option("blocks_per_cu", bpc)
-        wl = ddl_synth.reduced("large_dense")
-        data, refs = _materialise(wl)
-        ddl.merge_batch([_fragment(ddl, f, segs) for f, segs in zip(wl.fragments, data)])
-        n = 3 * tile + 4097
-        th, v, ls, tok, mask = random_problem(tile + bpc, n, 3, torch.bfloat16, DEV)
+        ddl.set_option("tiles_per_block", tpb)
+        ddl.set_option("max_blocks_per_cu", cap)
+        for name in ("large_dense", "moe", "streaming_model"):
+            wl = ddl_synth.reduced(name)
+            data, refs = _materialise(wl)
+            ddl.merge_batch([_fragment(ddl, f, segs) for f, segs in zip(wl.fragments, data)])
+            torch.cuda.synchronize()
+            _check_all(wl, data, refs)
+        n = 3 * 1024 * tpb + 4097
+        th, v, ls, tok, mask = random_problem(tpb + cap, n, 3, torch.bfloat16, DEV)
         ref = oracle.merge_fragment(ddl_synth.to_host_array(th), ddl_synth.to_host_array(v),
                                     [ddl_synth.to_host_array(x) for x in ls], tok, mask, 0.7, 0.9)
         ddl.merge_fragment(th, v, ls, tok, mask, 0.7, 0.9)
         torch.cuda.synchronize()
-        _check_all(wl, data, refs)
         check_segment(ddl_synth.SegmentData(th, v, ls), ref, "flat")
     finally:
-        ddl.set_option("tile_elems", old[0])
-        ddl.set_option("blocks_per_cu", old[1])
+        ddl.set_option("tiles_per_block", old[0])
+        ddl.set_option("max_blocks_per_cu", old[1])
     with pytest.raises(ddl.DdlError):
-        ddl.set_option("tile_elems", 1000)
+        ddl.set_option("tiles_per_block", 0)
     with pytest.raises(ddl.DdlError):
         ddl.set_option("no_such_option", 1)

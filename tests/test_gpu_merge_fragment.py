@@ -34,8 +34,8 @@ def _run_and_check(ddl, theta, v, learners, tokens, mask, lr, mu, what):
 
 # sizes: below / at / above a vector group, a workgroup pass, an unrolled pass and a tile,
 # each with and without a ragged tail
-SIZES = [1, 3, 7, 8, 9, 1023, 1024, 1025, 2048 * 4 + 5, 16384, 16384 + 1, 3 * 16384 + 8191,
-         5 * 16384 + 12345]
+SIZES = [1, 3, 4, 5, 7, 8, 9, 255, 1021, 1023, 1024, 1025, 1027, 2048, 2048 * 4 + 5, 16384,
+         16384 + 1, 3 * 16384 + 8191, 5 * 16384 + 12345]
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
