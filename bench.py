@@ -49,6 +49,9 @@ def parse_args():
                     help="independent copies of the workload visited round-robin, one per step, "
                          "so that no step finds its data in the 256 MB last-level cache "
                          "(default: enough copies for a 3 GiB rotating footprint)")
+    ap.add_argument("--balanced", type=int, default=0, metavar="P",
+                    help="regroup the workload's tensors into P balanced fragments with "
+                         "ddl_balanced_fragments (the paper uses P = 24)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tiles-per-block", type=int, default=None)
     ap.add_argument("--max-blocks-per-cu", type=int, default=None)
@@ -143,6 +146,9 @@ def main():
         ddl.set_option("max_blocks_per_cu", args.max_blocks_per_cu)
 
     wl = ddl_synth.WORKLOADS[args.workload]()
+    if args.balanced:
+        sizes = [t.numel for f in wl.fragments for t in f.tensors]
+        wl = ddl_synth.regroup(wl, ddl.balanced_fragments(sizes, args.balanced), args.balanced)
     big = wl.numel > 2_000_000_000
     steps = args.steps if args.steps is not None else (20 if big else 300)
     warmup = args.warmup if args.warmup is not None else (2 if big else 20)

@@ -191,6 +191,30 @@ def streaming_model(d_model: int = 4096, d_ff: int = 14336, blocks: int = 32,
     return Workload("streaming_model", frags, order)
 
 
+def regroup(wl: Workload, fragment_of: Sequence[int], num_fragments: int) -> Workload:
+    """The same tensors regrouped into ``num_fragments`` fragments: tensor i (numbered across
+    the fragments of ``wl`` in order) goes to fragment ``fragment_of[i]``.  The partition is an
+    input (it comes from the fragmentation routine under test); each new fragment draws its
+    own quorum (at least 2/3 of the learners) and token counters, and the arrival order is a
+    seeded permutation."""
+    tensors = [t for f in wl.fragments for t in f.tensors]
+    assert len(fragment_of) == len(tensors)
+    base = wl.fragments[0]
+    name = f"{wl.name}/regrouped{num_fragments}"
+    frags: List[FragmentSpec] = []
+    for p in range(num_fragments):
+        rng = np.random.default_rng(seed_for(name, p, "meta"))
+        mine = [t for t, q in zip(tensors, fragment_of) if q == p]
+        k = int(rng.integers(-(-2 * base.M // 3), base.M + 1))
+        frags.append(FragmentSpec(p, mine, M=base.M, learner_dtype=base.learner_dtype,
+                                  token_counts=_uniform_tokens(rng, base.M, 1 << 22),
+                                  quorum_mask=_choose_quorum(rng, base.M, k),
+                                  drift=list(base.drift), lr=base.lr, mu=base.mu,
+                                  v_sigma=base.v_sigma))
+    order = np.random.default_rng(seed_for(name, "arrival")).permutation(num_fragments).tolist()
+    return Workload(name, frags, order)
+
+
 WORKLOADS = {
     "tiny": tiny,
     "dense_block": dense_block,

@@ -194,6 +194,20 @@ DDL_API int ddl_plan_num_fragments(const ddl_plan* plan);
 DDL_API size_t ddl_plan_num_elements(const ddl_plan* plan);
 
 /*
+ * Balanced tensor fragmentation (Section 5.1; Appendix C, "Balanced tensor fragmentation"):
+ * greedy number partitioning of the model's tensors into num_fragments fragments -- tensors are
+ * taken in descending order of size and each goes to the fragment whose total is the smallest
+ * so far (largest fragment at most 4/3 of the optimum).  Ties, on which the paper is silent:
+ * equal sizes keep their input order; the lowest-numbered of equally light fragments wins.
+ *   sizes        host, num_tensors entries, any unit (elements, bytes, bits)
+ *   fragment_of  host, num_tensors entries, receives the fragment index of each tensor
+ * Host-only; produces the tensor lists that ddl_plan_create / ddl_merge_batch take.
+ * Errors: INVALID_ARG (num_tensors < 0, num_fragments < 1, NULL with num_tensors > 0).
+ */
+DDL_API ddl_status ddl_balanced_fragments(const uint64_t* sizes, int num_tensors,
+                                          int num_fragments, int* fragment_of);
+
+/*
  * Measurement aid, not part of the method: a plain device-to-device streaming copy of `bytes`
  * bytes (a multiple of 16; dst and src device, 16-byte aligned, not overlapping) with the
  * merge kernel's access width and cache hints.  It reads `bytes` and writes `bytes`, which

@@ -79,6 +79,8 @@ def _load() -> ctypes.CDLL:
     lib.ddl_plan_num_fragments.restype = ctypes.c_int
     lib.ddl_plan_num_elements.argtypes = [ctypes.c_void_p]
     lib.ddl_plan_num_elements.restype = ctypes.c_size_t
+    lib.ddl_balanced_fragments.argtypes = [u64p, ctypes.c_int, ctypes.c_int,
+                                           ctypes.POINTER(ctypes.c_int)]
     lib.ddl_copy_probe.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                                    ctypes.c_void_p]
     lib.ddl_set_option.argtypes = [ctypes.c_char_p, ctypes.c_long]
@@ -86,7 +88,7 @@ def _load() -> ctypes.CDLL:
     for name in ("ddl_compute_weights", "ddl_compute_weights_quality", "ddl_merge_fragment",
                  "ddl_merge_fragment_weighted", "ddl_merge_batch", "ddl_plan_create",
                  "ddl_plan_merge", "ddl_plan_destroy", "ddl_set_option", "ddl_get_option",
-                 "ddl_copy_probe"):
+                 "ddl_copy_probe", "ddl_balanced_fragments"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -315,6 +317,15 @@ class Plan:
             self.destroy()
         except Exception:
             pass
+
+
+def balanced_fragments(sizes, num_fragments: int) -> List[int]:
+    """ddl_balanced_fragments: greedy number partitioning of tensor sizes into fragments."""
+    n = len(sizes)
+    out = (ctypes.c_int * max(1, n))()
+    _check(_lib.ddl_balanced_fragments(_u64(sizes), n, num_fragments, out),
+           "ddl_balanced_fragments")
+    return list(out)[:n]
 
 
 def copy_probe(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
