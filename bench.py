@@ -52,6 +52,8 @@ def parse_args():
     ap.add_argument("--balanced", type=int, default=0, metavar="P",
                     help="regroup the workload's tensors into P balanced fragments with "
                          "ddl_balanced_fragments (the paper uses P = 24)")
+    ap.add_argument("--bcast", action="store_true",
+                    help="also write the new Theta as bf16 in the same pass (+2 B/param)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tiles-per-block", type=int, default=None)
     ap.add_argument("--max-blocks-per-cu", type=int, default=None)
@@ -165,8 +167,12 @@ def main():
     copies = []
     for r in range(replicas):
         data = [ddl_synth.make_fragment(wl, f, "cuda:0", absent="valid") for f in wl.fragments]
+        for segs in data:
+            for s in segs:
+                s.bcast = (torch.empty(s.theta.numel(), dtype=torch.bfloat16, device="cuda:0")
+                           if args.bcast else None)
         if args.api == "plan":
-            plan = ddl.Plan([ddl.Fragment([(s.theta, s.v, s.learners) for s in segs], M=f.M,
+            plan = ddl.Plan([ddl.Fragment([(s.theta, s.v, s.learners, s.bcast) for s in segs], M=f.M,
                                           learner_dtype=dt[f.learner_dtype])
                              for f, segs in zip(wl.fragments, data)])
             calls = [plan.prepare([(fi, wl.fragments[fi].token_counts,
@@ -174,7 +180,7 @@ def main():
                                     wl.fragments[fi].mu)]) for fi in wl.arrival_order]
             copies.append((data, plan, calls))
         else:
-            frs = [ddl.Fragment([(s.theta, s.v, s.learners) for s in segs], f.token_counts,
+            frs = [ddl.Fragment([(s.theta, s.v, s.learners, s.bcast) for s in segs], f.token_counts,
                                 f.quorum_mask, f.lr, f.mu, M=f.M,
                                 learner_dtype=dt[f.learner_dtype])
                    for f, segs in zip(wl.fragments, data)]
@@ -211,14 +217,14 @@ def main():
     gpu_ms = ev0.elapsed_time(ev1) / steps
 
     params_per_s = wl.numel / (wall_ms * 1e-3)
-    alg_bytes = wl.algorithmic_bytes
+    alg_bytes = wl.algorithmic_bytes + (2 * wl.numel if args.bcast else 0)
     # The step consists of merge-kernel launches only (no copies, no other kernels), so the
     # event time per step divided by the launches per step is the average launch duration,
     # gaps between back-to-back launches included.
     kernel_ms = gpu_ms / launches_per_step
     achieved = alg_bytes / launches_per_step / (kernel_ms * 1e-3) / 1e9
     copy_gbps = time_copy_probe(ddl, torch)
-    traffic = MEASURED_TRAFFIC_BYTES.get(wl.name)
+    traffic = None if args.bcast else MEASURED_TRAFFIC_BYTES.get(wl.name)
 
     out = {
         "metric": METRIC,
@@ -247,6 +253,7 @@ def main():
             "api": "ddl_plan_merge" if args.api == "plan" else "ddl_merge_batch",
             "launches_per_step": launches_per_step,
             "replicas": replicas,
+            "bf16_broadcast_copy": bool(args.bcast),
             "tiles_per_block": ddl.get_option("tiles_per_block"),
             "max_blocks_per_cu": ddl.get_option("max_blocks_per_cu"),
         },

@@ -121,6 +121,18 @@ DDL_API ddl_status ddl_merge_fragment_weighted(float* theta, float* v, const voi
                                        size_t n, float lr, float mu, void* hip_stream);
 
 /*
+ * As ddl_merge_fragment, and in the same pass also writes the new Theta, rounded to
+ * nearest-even bf16, into theta_bf16 (device, n bf16 elements, not NULL): the fragment as it
+ * is broadcast back to the learners (Algorithm 2, "Send(Learners, Theta_p, t)"), without a
+ * second sweep over Theta.  Costs 2 more bytes of HBM traffic per parameter.
+ */
+DDL_API ddl_status ddl_merge_fragment_bcast(float* theta, float* v, void* theta_bf16,
+                                            const void* const* learner_params,
+                                            ddl_dtype learner_dtype, const uint64_t* token_counts,
+                                            const uint8_t* quorum_mask, int M, size_t n, float lr,
+                                            float mu, void* hip_stream);
+
+/*
  * A fragment as the paper forms it: a set of whole tensors (Section 5.1 and Appendix C,
  * balanced tensor fragmentation), each tensor its own flat array ("segment").  All segments of
  * a fragment share the fragment's counters, mask, lr and mu (per-fragment counters c_{m,p},
@@ -131,6 +143,11 @@ typedef struct ddl_segment {
     float* v;                          /* device, n fp32 elements, updated in place            */
     const void* const* learner_params; /* HOST array of M DEVICE pointers (M of the fragment)  */
     size_t n;                          /* elements in this tensor; 0 is allowed                */
+    void* theta_bf16;                  /* device, optional (NULL: none): n bf16 elements that
+                                          receive the new Theta rounded to nearest-even, the
+                                          copy the syncer sends back to the learners
+                                          (Algorithm 2, "Send(Learners, Theta_p)"), written by
+                                          the same pass; 2-byte aligned, must overlap nothing  */
 } ddl_segment;
 
 typedef struct ddl_fragment {

@@ -71,6 +71,8 @@ def load(path: str | None = None) -> ctypes.CDLL:
                                                                 ctypes.c_size_t, ctypes.c_float,
                                                                 ctypes.c_float]
     lib.ddl_oracle_merge_fragment_weighted.restype = ctypes.c_int
+    lib.ddl_oracle_round_bf16.argtypes = [f32p, ctypes.POINTER(ctypes.c_uint16), ctypes.c_size_t]
+    lib.ddl_oracle_round_bf16.restype = None
     if path is None:
         _lib = lib
     return lib
@@ -193,6 +195,15 @@ def merge_fragment_weighted(theta: np.ndarray, v: np.ndarray,
     if rc != OK:
         raise OracleError(rc)
     return theta_out, v_out
+
+
+def round_bf16(x: np.ndarray, lib=None) -> np.ndarray:
+    """fp32 -> bf16 bit patterns (uint16), round to nearest, ties to even."""
+    lib = lib or load()
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape, dtype=np.uint16)
+    lib.ddl_oracle_round_bf16(_ptr(x, ctypes.c_float), _ptr(out, ctypes.c_uint16), x.size)
+    return out
 
 
 def merge_batch(fragments) -> list:

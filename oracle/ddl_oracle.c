@@ -216,6 +216,48 @@ int ddl_oracle_merge_fragment_weighted(double* theta_out, double* v_out, const f
 }
 
 /*
+ * fp32 -> bf16 for the broadcast copy of the new global fragment (Algorithm 2, the Send back
+ * to the learners; bf16 being the paper's wire format, Appendix D.3): round to nearest, ties
+ * to even, written from the definition -- the two bf16 neighbours of x are found by clearing
+ * the low 16 bits and by stepping one bf16 unit away from zero, the nearer one in exact
+ * (double) arithmetic wins, a tie goes to the one whose last kept bit is 0.  NaN stays NaN
+ * (sign and top payload bits kept, quiet bit set); overflow rounds to infinity.
+ */
+static uint16_t round_bf16(float x)
+{
+    uint32_t bits;
+    memcpy(&bits, &x, sizeof bits);
+    if ((bits & 0x7fffffffu) > 0x7f800000u)
+        return (uint16_t)((bits >> 16) | 0x40u);
+    uint32_t lo_bits = bits & 0xffff0000u;      /* neighbour towards zero */
+    uint32_t hi_bits = lo_bits + 0x10000u;      /* neighbour away from zero (may be inf) */
+    float lo, hi;
+    memcpy(&lo, &lo_bits, sizeof lo);
+    memcpy(&hi, &hi_bits, sizeof hi);
+    if ((hi_bits & 0x7f800000u) == 0x7f800000u) {
+        /* away-from-zero neighbour is infinity: its place on the real line, for the distance
+         * test, is one bf16 step beyond the largest finite value */
+        double step = ldexp(1.0, 127 - 7);
+        double dlo = fabs((double)x - (double)lo);
+        double dhi = step - dlo;
+        if (dlo < dhi) return (uint16_t)(lo_bits >> 16);
+        if (dhi < dlo) return (uint16_t)(hi_bits >> 16);
+        return (uint16_t)((((lo_bits >> 16) & 1u) == 0 ? lo_bits : hi_bits) >> 16);
+    }
+    double dlo = fabs((double)x - (double)lo);
+    double dhi = fabs((double)hi - (double)x);
+    if (dlo < dhi) return (uint16_t)(lo_bits >> 16);
+    if (dhi < dlo) return (uint16_t)(hi_bits >> 16);
+    return (uint16_t)((((lo_bits >> 16) & 1u) == 0 ? lo_bits : hi_bits) >> 16);
+}
+
+void ddl_oracle_round_bf16(const float* x, uint16_t* out, size_t n)
+{
+    for (size_t i = 0; i < n; ++i)
+        out[i] = round_bf16(x[i]);
+}
+
+/*
  * The identical scalar loop, with the element range cut into `nthreads`
  * contiguous chunks that run on their own threads.  Elements are independent,
  * so the result is bit-identical to ddl_oracle_merge_fragment.  Used only to

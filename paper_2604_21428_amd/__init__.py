@@ -32,7 +32,8 @@ class DdlError(RuntimeError):
 
 class _Segment(ctypes.Structure):
     _fields_ = [("theta", ctypes.c_void_p), ("v", ctypes.c_void_p),
-                ("learner_params", ctypes.POINTER(ctypes.c_void_p)), ("n", ctypes.c_size_t)]
+                ("learner_params", ctypes.POINTER(ctypes.c_void_p)), ("n", ctypes.c_size_t),
+                ("theta_bf16", ctypes.c_void_p)]
 
 
 class _Fragment(ctypes.Structure):
@@ -66,6 +67,9 @@ def _load() -> ctypes.CDLL:
     lib.ddl_merge_fragment.argtypes = [ctypes.c_void_p, ctypes.c_void_p, vpp, ctypes.c_int, u64p,
                                        u8p, ctypes.c_int, ctypes.c_size_t, ctypes.c_float,
                                        ctypes.c_float, ctypes.c_void_p]
+    lib.ddl_merge_fragment_bcast.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, vpp,
+                                             ctypes.c_int, u64p, u8p, ctypes.c_int, ctypes.c_size_t,
+                                             ctypes.c_float, ctypes.c_float, ctypes.c_void_p]
     lib.ddl_merge_fragment_weighted.argtypes = [ctypes.c_void_p, ctypes.c_void_p, vpp,
                                                 ctypes.c_int, f64p, ctypes.c_int, ctypes.c_size_t,
                                                 ctypes.c_float, ctypes.c_float, ctypes.c_void_p]
@@ -88,7 +92,7 @@ def _load() -> ctypes.CDLL:
     for name in ("ddl_compute_weights", "ddl_compute_weights_quality", "ddl_merge_fragment",
                  "ddl_merge_fragment_weighted", "ddl_merge_batch", "ddl_plan_create",
                  "ddl_plan_merge", "ddl_plan_destroy", "ddl_set_option", "ddl_get_option",
-                 "ddl_copy_probe", "ddl_balanced_fragments"):
+                 "ddl_copy_probe", "ddl_balanced_fragments", "ddl_merge_fragment_bcast"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -192,6 +196,28 @@ def merge_fragment(theta: torch.Tensor, v: torch.Tensor,
                                    _stream_handle(stream)), "ddl_merge_fragment")
 
 
+def _bf16_ptr(t: torch.Tensor, n: int) -> int:
+    if t.dtype != torch.bfloat16 or not t.is_cuda or not t.is_contiguous() or t.numel() != n:
+        raise TypeError(f"theta_bf16 must be a contiguous bfloat16 device tensor of {n} elements")
+    return t.data_ptr()
+
+
+def merge_fragment_bcast(theta: torch.Tensor, v: torch.Tensor, theta_bf16: torch.Tensor,
+                         learner_params: Sequence[Optional[torch.Tensor]], token_counts,
+                         quorum_mask, lr: float, mu: float, stream=None, learner_dtype=None) -> None:
+    """ddl_merge_fragment_bcast: merge_fragment that also writes the new theta as bf16."""
+    n = theta.numel()
+    if v.numel() != n:
+        raise ValueError("theta and v differ in size")
+    M = len(learner_params)
+    table, code = _learner_table(learner_params, n,
+                                 None if learner_dtype is None else _dtype_code(learner_dtype))
+    _check(_lib.ddl_merge_fragment_bcast(_state_ptr(theta, "theta"), _state_ptr(v, "v"),
+                                         _bf16_ptr(theta_bf16, n), table, code,
+                                         _u64(token_counts, M), _u8(quorum_mask, M), M, n, lr, mu,
+                                         _stream_handle(stream)), "ddl_merge_fragment_bcast")
+
+
 def merge_fragment_weighted(theta: torch.Tensor, v: torch.Tensor,
                             learner_params: Sequence[Optional[torch.Tensor]], weights,
                             lr: float, mu: float, stream=None, learner_dtype=None) -> None:
@@ -211,8 +237,8 @@ def merge_fragment_weighted(theta: torch.Tensor, v: torch.Tensor,
 
 
 class Fragment:
-    """Marshalled ddl_fragment: a list of (theta, v, learners) tensor triples that share one
-    quorum.  Keeps the ctypes arrays (and the tensors) alive."""
+    """Marshalled ddl_fragment: a list of (theta, v, learners[, theta_bf16]) tensor tuples that
+    share one quorum.  Keeps the ctypes arrays (and the tensors) alive."""
 
     def __init__(self, segments, token_counts=None, quorum_mask=None, lr: float = 0.0,
                  mu: float = 0.0, M: Optional[int] = None, learner_dtype=None):
@@ -225,7 +251,9 @@ class Fragment:
         code = None if learner_dtype is None else _dtype_code(learner_dtype)
         self._tables = []
         self._segs = (_Segment * max(1, len(self.tensors)))()
-        for i, (theta, v, learners) in enumerate(self.tensors):
+        for i, seg in enumerate(self.tensors):
+            theta, v, learners = seg[0], seg[1], seg[2]
+            bcast = seg[3] if len(seg) > 3 else None
             if len(learners) != M:
                 raise ValueError("every segment of a fragment has M learner entries")
             n = theta.numel()
@@ -237,6 +265,7 @@ class Fragment:
             self._segs[i].v = _state_ptr(v, "v")
             self._segs[i].learner_params = ctypes.cast(table, ctypes.POINTER(ctypes.c_void_p))
             self._segs[i].n = n
+            self._segs[i].theta_bf16 = None if bcast is None else _bf16_ptr(bcast, n)
         self.dtype_code = DDL_F32 if code is None else code
         self._tok = _u64(token_counts, M) if token_counts is not None else None
         self._mask = _u8(quorum_mask, M) if quorum_mask is not None else None

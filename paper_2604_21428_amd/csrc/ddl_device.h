@@ -20,13 +20,14 @@ struct DdlSegDesc {
     float* theta;                   // n fp32, read and written
     float* v;                       // n fp32, read and written
     const void* learner[DDL_MAXL];  // learner m's copy (bf16 or fp32), read if it contributes
+    void* theta_bf16;               // optional: receives the new Theta as bf16 (n elements)
     uint64_t n;                     // elements (> 0)
     uint32_t tile_begin;            // first tile of this segment within its fragment
     uint16_t learner_aligned;       // bit m: learner[m] is 16-byte aligned
-    uint8_t base_aligned;           // theta and v are 16-byte aligned
+    uint8_t base_aligned;           // theta, v 16-byte and theta_bf16 (if any) 8-byte aligned
     uint8_t pad;
 };
-static_assert(sizeof(DdlSegDesc) == 160, "descriptor layout");
+static_assert(sizeof(DdlSegDesc) == 168, "descriptor layout");
 
 struct DdlItem {
     uint32_t seg_begin;     // first descriptor of the fragment in the table

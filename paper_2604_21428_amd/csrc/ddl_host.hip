@@ -190,12 +190,15 @@ inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) =
 
 // Appends the ranges of one segment; false if a needed pointer is NULL or misaligned for its
 // element type.  `learner_bits` selects which learners' ranges count.
-bool add_segment_ranges(const float* theta, const float* v, const void* const* learners,
-                        uint32_t learner_bits, ddl_dtype dt, size_t n, std::vector<Range>& r)
+bool add_segment_ranges(const float* theta, const float* v, const void* theta_bf16,
+                        const void* const* learners, uint32_t learner_bits, ddl_dtype dt, size_t n,
+                        std::vector<Range>& r)
 {
-    if (!theta || !v || !aligned(theta, 4) || !aligned(v, 4)) return false;
+    if (!theta || !v || !aligned(theta, 4) || !aligned(v, 4) || !aligned(theta_bf16, 2))
+        return false;
     r.push_back({(uintptr_t)theta, (uintptr_t)theta + 4 * n, true});
     r.push_back({(uintptr_t)v, (uintptr_t)v + 4 * n, true});
+    if (theta_bf16) r.push_back({(uintptr_t)theta_bf16, (uintptr_t)theta_bf16 + 2 * n, true});
     const size_t b = elem_size(dt);
     for (int m = 0; m < DDL_MAXL; ++m) {
         if (!(learner_bits >> m & 1)) continue;
@@ -206,15 +209,16 @@ bool add_segment_ranges(const float* theta, const float* v, const void* const* l
     return true;
 }
 
-void fill_desc(DdlSegDesc& d, float* theta, float* v, const void* const* learners, int M, size_t n,
-               uint32_t tile_begin)
+void fill_desc(DdlSegDesc& d, float* theta, float* v, void* theta_bf16,
+               const void* const* learners, int M, size_t n, uint32_t tile_begin)
 {
     std::memset(&d, 0, sizeof d);
     d.theta = theta;
     d.v = v;
+    d.theta_bf16 = theta_bf16;
     d.n = n;
     d.tile_begin = tile_begin;
-    d.base_aligned = aligned(theta, 16) && aligned(v, 16);
+    d.base_aligned = aligned(theta, 16) && aligned(v, 16) && aligned(theta_bf16, 8);
     for (int m = 0; m < M; ++m) {
         d.learner[m] = learners[m];
         if (aligned(learners[m], 16)) d.learner_aligned |= (uint16_t)(1u << m);
@@ -326,12 +330,12 @@ ddl_status build_table(const ddl_fragment* frags, int num_frags, const uint32_t*
             }
             for (int m = 0; m < f.M; ++m)
                 if (!g.learner_params[m]) fi.nonnull_bits &= ~(1u << m);
-            if (!add_segment_ranges(g.theta, g.v, g.learner_params, bits, f.learner_dtype, g.n,
-                                    ranges))
+            if (!add_segment_ranges(g.theta, g.v, g.theta_bf16, g.learner_params, bits,
+                                    f.learner_dtype, g.n, ranges))
                 return DDL_ERR_INVALID_ARG;
             if (tiles > 0xffffffffull) return DDL_ERR_INVALID_ARG;
             DdlSegDesc d;
-            fill_desc(d, g.theta, g.v, g.learner_params, f.M, g.n, (uint32_t)tiles);
+            fill_desc(d, g.theta, g.v, g.theta_bf16, g.learner_params, f.M, g.n, (uint32_t)tiles);
             T.segs.push_back(d);
             tiles += (g.n + DDL_TILE - 1) / DDL_TILE;
             fi.elems += g.n;
@@ -399,8 +403,9 @@ ddl_status launch_work(const Table& T, const void* d_table, std::vector<Work>& w
     return DDL_OK;
 }
 
-ddl_status merge_flat(float* theta, float* v, const void* const* learner_params, ddl_dtype dt,
-                      const double* w, int M, size_t n, float lr, float mu, void* stream)
+ddl_status merge_flat(float* theta, float* v, void* theta_bf16, const void* const* learner_params,
+                      ddl_dtype dt, const double* w, int M, size_t n, float lr, float mu,
+                      void* stream)
 {
     if (dt != DDL_F32 && dt != DDL_BF16) return DDL_ERR_INVALID_ARG;
     if (!finite_nonneg(lr) || !finite_nonneg(mu)) return DDL_ERR_INVALID_ARG;
@@ -411,7 +416,8 @@ ddl_status merge_flat(float* theta, float* v, const void* const* learner_params,
     std::vector<Range> ranges;
     const void* lp[DDL_MAXL] = {};
     for (int m = 0; m < M; ++m) lp[m] = (q.present_bits >> m & 1) ? learner_params[m] : nullptr;
-    if (!add_segment_ranges(theta, v, lp, q.present_bits, dt, n, ranges)) return DDL_ERR_INVALID_ARG;
+    if (!add_segment_ranges(theta, v, theta_bf16, lp, q.present_bits, dt, n, ranges))
+        return DDL_ERR_INVALID_ARG;
     if (ranges_alias(ranges)) return DDL_ERR_ALIAS;
 
     std::lock_guard<std::mutex> lock(g_mu);
@@ -422,7 +428,7 @@ ddl_status merge_flat(float* theta, float* v, const void* const* learner_params,
     a.tiles_per_block = (uint32_t)g_tiles_per_block;
     a.total_tiles = (uint32_t)tiles;
     a.num_items = 1;
-    fill_desc(a.flat, theta, v, lp, M, n, 0);
+    fill_desc(a.flat, theta, v, theta_bf16, lp, M, n, 0);
     fill_item(a.item[0], q, lr, mu, 0, 1, 0);
     const int e = ddl_launch_merge((int)dt, q.Mq, true, grid_for(a.total_tiles), lds_cap_bytes(),
                                    stream, a);
@@ -476,7 +482,21 @@ ddl_status ddl_merge_fragment(float* theta, float* v, const void* const* learner
     double w[DDL_MAXL];
     const ddl_status st = weights_tokens(token_counts, quorum_mask, M, w);
     if (st != DDL_OK) return st;
-    return merge_flat(theta, v, learner_params, learner_dtype, w, M, n, lr, mu, hip_stream);
+    return merge_flat(theta, v, nullptr, learner_params, learner_dtype, w, M, n, lr, mu,
+                      hip_stream);
+}
+
+ddl_status ddl_merge_fragment_bcast(float* theta, float* v, void* theta_bf16,
+                                    const void* const* learner_params, ddl_dtype learner_dtype,
+                                    const uint64_t* token_counts, const uint8_t* quorum_mask,
+                                    int M, size_t n, float lr, float mu, void* hip_stream)
+{
+    double w[DDL_MAXL];
+    const ddl_status st = weights_tokens(token_counts, quorum_mask, M, w);
+    if (st != DDL_OK) return st;
+    if (n > 0 && !theta_bf16) return DDL_ERR_INVALID_ARG;
+    return merge_flat(theta, v, theta_bf16, learner_params, learner_dtype, w, M, n, lr, mu,
+                      hip_stream);
 }
 
 ddl_status ddl_merge_fragment_weighted(float* theta, float* v, const void* const* learner_params,
@@ -486,7 +506,8 @@ ddl_status ddl_merge_fragment_weighted(float* theta, float* v, const void* const
     double w[DDL_MAXL];
     const ddl_status st = weights_given(weights, M, w);
     if (st != DDL_OK) return st;
-    return merge_flat(theta, v, learner_params, learner_dtype, w, M, n, lr, mu, hip_stream);
+    return merge_flat(theta, v, nullptr, learner_params, learner_dtype, w, M, n, lr, mu,
+                      hip_stream);
 }
 
 ddl_status ddl_merge_batch(const ddl_fragment* frags, int num_frags, void* hip_stream)

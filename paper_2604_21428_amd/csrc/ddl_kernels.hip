@@ -112,6 +112,14 @@ struct LearnerBF16 {
     }
 };
 
+// fp32 -> bf16, round to nearest, ties to even; NaN stays a (quiet) NaN.
+__device__ __forceinline__ uint32_t bf16_rne(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
 // One element: Delta = sum_j w_j (Theta - x_j); v' = mu v + Delta;
 // Theta' = Theta - lr (Delta + mu v').  The difference form keeps the fp32 rounding of the
 // weights (their sum is 1 only to ~1e-7) away from |Theta|.
@@ -130,8 +138,9 @@ __device__ __forceinline__ void outer_step(float& theta, float& v, const float (
 // NT full tiles starting at element 0 of the given bases: lane handles group `lane` of each.
 // All loads are issued before the first use.
 template <typename L, int MQ, int NT>
-__device__ __forceinline__ void merge_full_tiles(uint64_t th, uint64_t vv, const uint64_t (&lp)[MQ],
-                                                 const float (&w)[MQ], float lr, float mu)
+__device__ __forceinline__ void merge_full_tiles(uint64_t th, uint64_t vv, uint64_t tb,
+                                                 const uint64_t (&lp)[MQ], const float (&w)[MQ],
+                                                 float lr, float mu)
 {
     typename L::raw raw[NT][MQ];
     f32x4 T[NT], V[NT];
@@ -163,12 +172,18 @@ __device__ __forceinline__ void merge_full_tiles(uint64_t th, uint64_t vv, const
         const f32x4 vn = {v4[0], v4[1], v4[2], v4[3]};
         st<f32x4>(th, g, tn);
         st<f32x4>(vv, g, vn);
+        if (tb) {  // block-uniform: the broadcast copy of the new Theta
+            const u32x2 packed = {bf16_rne(t4[0]) | (bf16_rne(t4[1]) << 16),
+                                  bf16_rne(t4[2]) | (bf16_rne(t4[3]) << 16)};
+            st<u32x2>(tb, g, packed);
+        }
     }
 }
 
 template <typename L, int MQ>
-__device__ __forceinline__ void merge_scalar(uint64_t th, uint64_t vv, const uint64_t (&lp)[MQ],
-                                             const float (&w)[MQ], float lr, float mu, uint32_t e)
+__device__ __forceinline__ void merge_scalar(uint64_t th, uint64_t vv, uint64_t tb,
+                                             const uint64_t (&lp)[MQ], const float (&w)[MQ],
+                                             float lr, float mu, uint32_t e)
 {
     typedef typename L::elem elem;
     float t = *(reinterpret_cast<const DDL_GLOBAL float*>(th) + e);
@@ -180,18 +195,19 @@ __device__ __forceinline__ void merge_scalar(uint64_t th, uint64_t vv, const uin
     outer_step<MQ>(t, v, xe, w, lr, mu);
     *(reinterpret_cast<DDL_GLOBAL float*>(th) + e) = t;
     *(reinterpret_cast<DDL_GLOBAL float*>(vv) + e) = v;
+    if (tb) *(reinterpret_cast<DDL_GLOBAL uint16_t*>(tb) + e) = (uint16_t)bf16_rne(t);
 }
 
 // A ragged tile (the last of a tensor): guarded groups, then fewer than four left-overs.
 template <typename L, int MQ>
-__device__ __forceinline__ void merge_ragged_tile(uint64_t th, uint64_t vv, const uint64_t (&lp)[MQ],
-                                                  const float (&w)[MQ], float lr, float mu,
-                                                  uint32_t cnt)
+__device__ __forceinline__ void merge_ragged_tile(uint64_t th, uint64_t vv, uint64_t tb,
+                                                  const uint64_t (&lp)[MQ], const float (&w)[MQ],
+                                                  float lr, float mu, uint32_t cnt)
 {
     const uint32_t nvec = cnt / 4;
-    if (threadIdx.x < nvec) merge_full_tiles<L, MQ, 1>(th, vv, lp, w, lr, mu);
+    if (threadIdx.x < nvec) merge_full_tiles<L, MQ, 1>(th, vv, tb, lp, w, lr, mu);
     const uint32_t e = nvec * 4 + threadIdx.x;
-    if (e < cnt) merge_scalar<L, MQ>(th, vv, lp, w, lr, mu, e);
+    if (e < cnt) merge_scalar<L, MQ>(th, vv, tb, lp, w, lr, mu, e);
 }
 
 template <typename L, int MQ, bool FLAT>
@@ -241,6 +257,8 @@ __global__ void __launch_bounds__(DDL_BLOCK) ddl_merge_kernel(const DdlLaunchArg
         const uint64_t off = (uint64_t)first_in_seg * DDL_TILE;  // elements
         uint64_t th = uniform(reinterpret_cast<uint64_t>(sp->theta) + off * 4);
         uint64_t vv = uniform(reinterpret_cast<uint64_t>(sp->v) + off * 4);
+        const uint64_t tb0 = reinterpret_cast<uint64_t>(sp->theta_bf16);
+        uint64_t tb = uniform(tb0 ? tb0 + off * 2 : 0);  // 0: no broadcast copy asked for
         uint64_t lp[MQ];
         float w[MQ];
 #pragma unroll
@@ -259,18 +277,19 @@ __global__ void __launch_bounds__(DDL_BLOCK) ddl_merge_kernel(const DdlLaunchArg
             if (!vec_ok) {
                 const uint32_t cnt = rem < DDL_TILE ? (uint32_t)rem : DDL_TILE;
                 for (uint32_t e = threadIdx.x; e < cnt; e += DDL_BLOCK)
-                    merge_scalar<L, MQ>(th, vv, lp, w, lr, mu, e);
+                    merge_scalar<L, MQ>(th, vv, tb, lp, w, lr, mu, e);
             } else if (DDL_PAIR && s + 2 <= end_in_seg && rem >= 2 * DDL_TILE) {
-                merge_full_tiles<L, MQ, 2>(th, vv, lp, w, lr, mu);
+                merge_full_tiles<L, MQ, 2>(th, vv, tb, lp, w, lr, mu);
                 step = 2;
             } else if (rem >= DDL_TILE) {
-                merge_full_tiles<L, MQ, 1>(th, vv, lp, w, lr, mu);
+                merge_full_tiles<L, MQ, 1>(th, vv, tb, lp, w, lr, mu);
             } else {
-                merge_ragged_tile<L, MQ>(th, vv, lp, w, lr, mu, (uint32_t)rem);
+                merge_ragged_tile<L, MQ>(th, vv, tb, lp, w, lr, mu, (uint32_t)rem);
             }
             s += step;
             th += (uint64_t)step * DDL_TILE * 4;
             vv += (uint64_t)step * DDL_TILE * 4;
+            if (tb) tb += (uint64_t)step * DDL_TILE * 2;
 #pragma unroll
             for (int j = 0; j < MQ; ++j) lp[j] += (uint64_t)step * DDL_TILE * sizeof(elem);
         }

@@ -40,6 +40,9 @@ class OracleApi:
         return oracle.merge_fragment(theta, v, learners, t, q, lr, mu, nthreads=nthreads,
                                      lib=self.lib)
 
+    def round_bf16(self, x):
+        return oracle.round_bf16(x, lib=self.lib)
+
     def merge_weighted(self, theta, v, learners, w, lr, mu):
         return oracle.merge_fragment_weighted(theta, v, learners, w, lr, mu, lib=self.lib)
 
@@ -354,6 +357,33 @@ def pin_bf16_widening(o: OracleApi):
     a = o.merge(theta, v, learners, t, q, 0.7, 0.9)
     b = o.merge(theta, v, [bf16_to_f64(x).astype(np.float32) for x in learners], t, q, 0.7, 0.9)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def pin_round_bf16_matches_torch_cast(o: OracleApi):
+    """Round-to-nearest-even against torch's fp32 -> bf16 cast: every bf16 value, every exact
+    tie between two neighbours, values just off the ties, the overflow edge, random floats."""
+    hi = np.arange(65536, dtype=np.uint32) << 16
+    patterns = [hi, hi | 0x8000, hi | 0x7fff, hi | 0x8001, hi | 0x0001, hi | 0xffff, hi | 0x4000,
+                hi | 0xc000]
+    rng = np.random.default_rng(19)
+    patterns.append(rng.integers(0, 1 << 32, size=200000, dtype=np.uint64).astype(np.uint32))
+    bits = np.concatenate(patterns).astype(np.uint32)
+    x = bits.view(np.float32)
+    finite_or_inf = ~np.isnan(x)
+    got = o.round_bf16(x)
+    ref = bf16_bits(x)
+    assert np.array_equal(got[finite_or_inf], ref[finite_or_inf])
+    # NaN in, NaN out
+    back = bf16_to_f64(got[~finite_or_inf])
+    assert np.all(np.isnan(back))
+    # spot values worked by hand: 1 + 2^-8 is a tie between 1 and 1 + 2^-7 -> even (1.0);
+    # 1 + 3 * 2^-8 is a tie between 1 + 2^-7 and 1 + 2^-6 -> even (1 + 2^-6)
+    spot = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20,
+                     -(1.0 + 2.0 ** -8), 3.3895313892515355e38, 3.4028234663852886e38],
+                    np.float32)
+    # the last two: the largest bf16 value stays; the largest fp32 value overflows to +inf
+    want = np.array([0x3f80, 0x3f82, 0x3f81, 0xbf80, 0x7f7f, 0x7f80], np.uint16)
+    assert np.array_equal(o.round_bf16(spot), want)
 
 
 def pin_linearity_shift(o: OracleApi):

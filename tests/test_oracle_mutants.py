@@ -38,6 +38,10 @@ MUTANTS = [
     ("quality_tokens_only", "raw[m] = c_tok * (c_tok / (double)step_counts[m]);", "raw[m] = c_tok;"),
     ("quality_inverted", "raw[m] = c_tok * (c_tok / (double)step_counts[m]);",
      "raw[m] = c_tok * ((double)step_counts[m] / c_tok);"),
+    ("bf16_round_truncates", "if (dlo < dhi) return (uint16_t)(lo_bits >> 16);\n    if (dhi < dlo) return (uint16_t)(hi_bits >> 16);\n    return (uint16_t)((((lo_bits >> 16) & 1u) == 0 ? lo_bits : hi_bits) >> 16);\n}",
+     "return (uint16_t)(lo_bits >> 16);\n}"),
+    ("bf16_round_ties_away", "    double dhi = fabs((double)hi - (double)x);\n    if (dlo < dhi) return (uint16_t)(lo_bits >> 16);\n    if (dhi < dlo) return (uint16_t)(hi_bits >> 16);\n    return (uint16_t)((((lo_bits >> 16) & 1u) == 0 ? lo_bits : hi_bits) >> 16);",
+     "    double dhi = fabs((double)hi - (double)x);\n    if (dlo < dhi) return (uint16_t)(lo_bits >> 16);\n    return (uint16_t)(hi_bits >> 16);"),
     ("chunk_overlap", "size_t lo = per * (size_t)t;", "size_t lo = per * (size_t)t + (t ? 1 : 0);"),
 ]
 
