@@ -71,6 +71,10 @@ def load(path: str | None = None) -> ctypes.CDLL:
                                                                 ctypes.c_size_t, ctypes.c_float,
                                                                 ctypes.c_float]
     lib.ddl_oracle_merge_fragment_weighted.restype = ctypes.c_int
+    lib.ddl_oracle_rda_merge_fragment.argtypes = common + [u64p, u8p, ctypes.c_int,
+                                                           ctypes.c_size_t, ctypes.c_size_t,
+                                                           ctypes.c_float, ctypes.c_float]
+    lib.ddl_oracle_rda_merge_fragment.restype = ctypes.c_int
     lib.ddl_oracle_round_bf16.argtypes = [f32p, ctypes.POINTER(ctypes.c_uint16), ctypes.c_size_t]
     lib.ddl_oracle_round_bf16.restype = None
     if path is None:
@@ -191,6 +195,31 @@ def merge_fragment_weighted(theta: np.ndarray, v: np.ndarray,
         _ptr(theta_out, ctypes.c_double), _ptr(v_out, ctypes.c_double),
         _ptr(theta, ctypes.c_float), _ptr(v, ctypes.c_float), table, dtype,
         _ptr(w, ctypes.c_double), M, n, lr, mu)
+    del keep
+    if rc != OK:
+        raise OracleError(rc)
+    return theta_out, v_out
+
+
+def rda_merge_fragment(theta: np.ndarray, v: np.ndarray, learners: Sequence[np.ndarray | None],
+                       token_counts, quorum_mask, group_len: int, lr: float, mu: float, lib=None):
+    """One fragment sync with radial-directional averaging as the merge, one norm per
+    ``group_len`` consecutive elements.  Returns (theta_new, v_new) as float64 arrays."""
+    lib = lib or load()
+    theta = np.ascontiguousarray(theta, dtype=np.float32)
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    n = theta.shape[0]
+    assert theta.ndim == 1 and v.shape == (n,)
+    M = len(learners)
+    t = _counts(token_counts, M)
+    q = _mask(quorum_mask, M)
+    table, dtype, keep = _learner_table(learners, n)
+    theta_out = np.empty(n, dtype=np.float64)
+    v_out = np.empty(n, dtype=np.float64)
+    rc = lib.ddl_oracle_rda_merge_fragment(
+        _ptr(theta_out, ctypes.c_double), _ptr(v_out, ctypes.c_double),
+        _ptr(theta, ctypes.c_float), _ptr(v, ctypes.c_float), table, dtype,
+        _ptr(t, ctypes.c_uint64), _ptr(q, ctypes.c_uint8), M, n, group_len, lr, mu)
     del keep
     if rc != OK:
         raise OracleError(rc)

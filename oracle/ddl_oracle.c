@@ -216,6 +216,84 @@ int ddl_oracle_merge_fragment_weighted(double* theta_out, double* v_out, const f
 }
 
 /*
+ * Radial-directional averaging (Appendix D.2, "Radial-directional averaging"), weighted
+ * form, followed by the same OuterOpt.  For a set of outer gradients d_m = Theta - theta_m
+ * (m in the quorum, normalised weights w_m):
+ *
+ *     RDA = ( sum_m w_m ||d_m|| ) * phi( sum_m w_m phi(d_m) ),      phi(x) = x / ||x||_2
+ *
+ * i.e. norms and directions are averaged separately and the mean direction is projected
+ * back to unit length.  The printed weighted formula has sum_m w_m d_m (a vector) where the
+ * unweighted one has the mean of the norms; it is read as the weighted mean of the norms,
+ * "completely analogously" as the text says.
+ *
+ * The paper does not say over which elements a norm is taken (it only says the magnitude
+ * tensors are tiny next to the direction tensors).  Here a tensor is cut into consecutive
+ * groups of `group_len` elements (the last one may be shorter) and RDA is applied to each
+ * group on its own: group_len = row length gives one magnitude per row, group_len >= n one
+ * per tensor.  phi is undefined at 0: a learner whose outer gradient is zero on a group adds
+ * nothing to that group's mean direction (its zero norm still enters the mean norm), and a
+ * group whose mean direction is zero gets Delta = 0.
+ */
+int ddl_oracle_rda_merge_fragment(double* theta_out, double* v_out, const float* theta,
+                                  const float* v, const void* const* learner_params,
+                                  int learner_dtype, const uint64_t* token_counts,
+                                  const uint8_t* quorum_mask, int M, size_t n, size_t group_len,
+                                  float lr, float mu)
+{
+    double w[ORACLE_MAX_LEARNERS];
+    int rc = ddl_oracle_weights(token_counts, quorum_mask, M, w);
+    if (rc != ORACLE_OK)
+        return rc;
+    rc = check_merge_args(theta_out, v_out, theta, v, learner_params, learner_dtype, w, M, n, lr,
+                          mu);
+    if (rc != ORACLE_OK)
+        return rc;
+    if (group_len == 0)
+        return ORACLE_BAD_ARG;
+    for (size_t lo = 0; lo < n; lo += group_len) {
+        size_t hi = n - lo < group_len ? n : lo + group_len;
+        /* norms of the outer gradients on this group, and their weighted mean */
+        double norm[ORACLE_MAX_LEARNERS];
+        double mean_norm = 0.0;
+        for (int m = 0; m < M; ++m) {
+            norm[m] = 0.0;
+            if (w[m] == 0.0)
+                continue;
+            double ss = 0.0;
+            for (size_t i = lo; i < hi; ++i) {
+                double d = (double)theta[i] - learner_value(learner_params[m], learner_dtype, i);
+                ss += d * d;
+            }
+            norm[m] = sqrt(ss);
+            mean_norm += w[m] * norm[m];
+        }
+        /* weighted mean of the unit directions, kept in v_out as scratch, and its norm */
+        double dir_ss = 0.0;
+        for (size_t i = lo; i < hi; ++i) {
+            double u = 0.0;
+            for (int m = 0; m < M; ++m) {
+                if (w[m] == 0.0 || norm[m] == 0.0)
+                    continue;
+                double d = (double)theta[i] - learner_value(learner_params[m], learner_dtype, i);
+                u += w[m] * (d / norm[m]);
+            }
+            v_out[i] = u;
+            dir_ss += u * u;
+        }
+        double dir_norm = sqrt(dir_ss);
+        for (size_t i = lo; i < hi; ++i) {
+            double Delta = dir_norm > 0.0 ? mean_norm * (v_out[i] / dir_norm) : 0.0;
+            double Theta = (double)theta[i];
+            double v_new = (double)mu * (double)v[i] + Delta;
+            theta_out[i] = Theta - (double)lr * (Delta + (double)mu * v_new);
+            v_out[i] = v_new;
+        }
+    }
+    return ORACLE_OK;
+}
+
+/*
  * fp32 -> bf16 for the broadcast copy of the new global fragment (Algorithm 2, the Send back
  * to the learners; bf16 being the paper's wire format, Appendix D.3): round to nearest, ties
  * to even, written from the definition -- the two bf16 neighbours of x are found by clearing

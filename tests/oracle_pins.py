@@ -40,6 +40,9 @@ class OracleApi:
         return oracle.merge_fragment(theta, v, learners, t, q, lr, mu, nthreads=nthreads,
                                      lib=self.lib)
 
+    def rda(self, theta, v, learners, t, q, group_len, lr, mu):
+        return oracle.rda_merge_fragment(theta, v, learners, t, q, group_len, lr, mu, lib=self.lib)
+
     def round_bf16(self, x):
         return oracle.round_bf16(x, lib=self.lib)
 
@@ -484,6 +487,142 @@ def pin_merge_errors(o: OracleApi):
     e = np.zeros(0, np.float32)
     th, vn = o.merge(e, e, [e, e], t, q, 0.7, 0.9)
     assert th.shape == (0,) and vn.shape == (0,)
+
+
+# --------------------------------------------------------------------------------------
+# radial-directional averaging
+# --------------------------------------------------------------------------------------
+
+def pin_rda_golden(o: OracleApi):
+    for c in json.load(open(GOLDEN))["rda_cases"]:
+        th, v = o.rda(f32(c["theta"]), f32(c["v"]), [f32(x) for x in c["learners"]],
+                      c["token_counts"], c["quorum_mask"], c["group_len"], c["lr"], c["mu"])
+        d = np.asarray(c["delta"])
+        assert np.allclose(v, d, rtol=0, atol=c["tolerance"] * (1 + np.abs(d).max())), (c["name"], v)
+        assert np.allclose(th, np.asarray(c["theta"]) - d, rtol=0, atol=1e-13), c["name"]
+
+
+def _rda_delta(o, theta, learners, t, q, g):
+    return o.rda(theta, np.zeros_like(theta), learners, t, q, g, 1.0, 0.0)[1]
+
+
+def pin_rda_norm_invariance(o: OracleApi):
+    """All outer gradients of norm R on a group => the merged one has norm R (the property the
+    paper states), whatever the directions and weights."""
+    rng = np.random.default_rng(21)
+    n, g, M, R = 96, 32, 5, 0.75
+    theta = f32(rng.normal(0, 1, n))
+    learners = []
+    for m in range(M):
+        d = rng.normal(0, 1, n)
+        for lo in range(0, n, g):
+            d[lo:lo + g] *= R / np.linalg.norm(d[lo:lo + g])
+        learners.append((theta.astype(np.float64) - d).astype(np.float32))
+    t = rng.integers(1, 1000, M).astype(np.uint64)
+    delta = _rda_delta(o, theta, learners, t, np.ones(M, np.uint8), g)
+    for lo in range(0, n, g):
+        assert abs(np.linalg.norm(delta[lo:lo + g]) - R) < 1e-5   # fp32 learners: R only to ~1e-7
+
+
+def pin_rda_single_learner_is_identity(o: OracleApi):
+    theta, v, learners, t, _ = _problem(22, n=100, M=3)
+    q = np.array([0, 1, 0], np.uint8)
+    a = o.rda(theta, v, learners, t, q, 7, 0.7, 0.9)
+    b = o.merge(theta, v, learners, t, q, 0.7, 0.9)
+    assert np.allclose(a[0], b[0], rtol=0, atol=1e-17) and np.allclose(a[1], b[1], rtol=0, atol=1e-17)
+
+
+def pin_rda_parallel_gradients_reduce_to_direct_average(o: OracleApi):
+    """Outer gradients that are positive multiples of one vector: averaging norms and
+    directions separately is then the plain weighted average."""
+    rng = np.random.default_rng(23)
+    n = 64
+    e = rng.integers(-8, 9, n) / 8.0
+    theta = f32(rng.integers(-16, 17, n) / 4.0)
+    scales = [0.5, 2.0, 1.25]
+    learners = [f32(theta - s * e) for s in scales]      # exact in fp32
+    t = np.array([2, 5, 1], np.uint64)
+    q = np.ones(3, np.uint8)
+    a = o.rda(theta, np.zeros(n, np.float32), learners, t, q, n, 0.5, 0.25)
+    b = o.merge(theta, np.zeros(n, np.float32), learners, t, q, 0.5, 0.25)
+    assert np.allclose(a[0], b[0], rtol=0, atol=1e-14) and np.allclose(a[1], b[1], rtol=0, atol=1e-14)
+
+
+def pin_rda_orthogonal_keeps_norm_where_average_shrinks(o: OracleApi):
+    """Orthogonal outer gradients of norm R: direct averaging gives R/sqrt(M), RDA gives R."""
+    M, R = 4, 2.0
+    n = 16 * M
+    theta = f32(np.linspace(-1, 1, n))
+    learners = []
+    for m in range(M):
+        d = np.zeros(n)
+        d[16 * m:16 * (m + 1)] = R / 4.0
+        learners.append(f32(theta.astype(np.float64) - d))
+    t, q = [3] * M, [1] * M
+    z = np.zeros(n, np.float32)
+    assert abs(np.linalg.norm(o.rda(theta, z, learners, t, q, n, 1.0, 0.0)[1]) - R) < 1e-6
+    assert abs(np.linalg.norm(o.merge(theta, z, learners, t, q, 1.0, 0.0)[1]) - R / 2.0) < 1e-6
+
+
+def pin_rda_scale_and_permutation(o: OracleApi):
+    rng = np.random.default_rng(24)
+    n, g, M = 60, 20, 4
+    theta = f32(rng.integers(-64, 64, n) / 8.0)
+    ds = [rng.integers(-32, 32, n) / 16.0 for _ in range(M)]
+    t = rng.integers(1, 50, M).astype(np.uint64)
+    q = np.array([1, 1, 0, 1], np.uint8)
+    L1 = [f32(theta - d) for d in ds]
+    L2 = [f32(theta - 4.0 * d) for d in ds]            # exact: power-of-two scale
+    d1 = _rda_delta(o, theta, L1, t, q, g)
+    d2 = _rda_delta(o, theta, L2, t, q, g)
+    assert np.allclose(d2, 4.0 * d1, rtol=0, atol=1e-13)
+    p = np.array([3, 0, 2, 1])
+    d3 = _rda_delta(o, theta, [L1[i] for i in p], t[p], q[p], g)
+    assert np.allclose(d3, d1, rtol=0, atol=1e-14)
+    # groups are independent: a group's result needs only that group's elements
+    d4 = _rda_delta(o, theta[g:2 * g], [x[g:2 * g].copy() for x in L1], t, q, g)
+    assert np.array_equal(d4, d1[g:2 * g])
+    # a group length that does not divide n: the last group is simply shorter
+    d5 = _rda_delta(o, theta, L1, t, q, 25)
+    d6 = _rda_delta(o, theta[50:], [x[50:].copy() for x in L1], t, q, 25)
+    assert np.array_equal(d5[50:], d6)
+
+
+def pin_rda_matches_numpy_formula(o: OracleApi):
+    """The printed formula evaluated with numpy's norm on random data (whole-tensor group)."""
+    theta, v, learners, t, q = _problem(25, n=200, M=4, quorum=[1, 1, 0, 1])
+    w = (t * q).astype(np.float64)
+    w /= w.sum()
+    D = [theta.astype(np.float64) - x.astype(np.float64) for x in learners]
+    mean_norm = sum(w[m] * np.linalg.norm(D[m]) for m in range(4) if q[m])
+    u = sum(w[m] * D[m] / np.linalg.norm(D[m]) for m in range(4) if q[m])
+    delta = mean_norm * u / np.linalg.norm(u)
+    got = _rda_delta(o, theta, learners, t, q, 200)
+    assert np.allclose(got, delta, rtol=0, atol=1e-15)
+    # and through the outer step: same as feeding that Delta to torch's Nesterov SGD
+    th, vn = o.rda(theta, v, learners, t, q, 200, 0.7, 0.9)
+    lr, mu = float(np.float32(0.7)), float(np.float32(0.9))
+    v_ref = mu * v.astype(np.float64) + delta
+    assert np.allclose(vn, v_ref, rtol=0, atol=1e-15)
+    assert np.allclose(th, theta - lr * (delta + mu * v_ref), rtol=0, atol=1e-15)
+
+
+def pin_rda_zero_gradient_cases(o: OracleApi):
+    """A learner equal to Theta on a group adds no direction (phi(0) is undefined) but its
+    zero norm enters the mean norm; all learners equal to Theta give Delta = 0."""
+    theta = f32([1.0, 2.0, 3.0, 4.0])
+    same = theta.copy()
+    other = f32([1.0 - 3.0, 2.0 - 4.0, 3.0, 4.0])        # d = (3,4) on group 0, zero on group 1
+    d = _rda_delta(o, theta, [same, other], [1, 1], [1, 1], 2)
+    assert np.allclose(d, [0.5 * 5 * 0.6, 0.5 * 5 * 0.8, 0.0, 0.0], rtol=0, atol=1e-15)
+    d = _rda_delta(o, theta, [same, same], [1, 1], [1, 1], 2)
+    assert np.all(d == 0.0)
+    # absent learners are never read
+    nan = np.full(4, np.nan, np.float32)
+    d2 = _rda_delta(o, theta, [same, other, nan], [1, 1, 7], [1, 1, 0], 2)
+    assert np.allclose(d2, [1.5, 2.0, 0.0, 0.0], rtol=0, atol=1e-15)
+    d3 = _rda_delta(o, theta, [same, other, None], [1, 1, 7], [1, 1, 0], 2)
+    assert np.array_equal(d2, d3)
 
 
 ALL_PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_") and callable(v)]

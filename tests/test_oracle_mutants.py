@@ -16,7 +16,11 @@ MUTANTS = [
     ("delta_sign", "w[m] * (Theta - learner_value(", "w[m] * (-Theta + learner_value("),
     ("delta_drops_theta", "w[m] * (Theta - learner_value(", "w[m] * (0.0 - learner_value("),
     ("delta_unweighted", "Delta += w[m] * (Theta", "Delta += (Theta"),
-    ("absent_multiplied_not_skipped", "if (w[m] == 0.0)\n                continue;", ""),
+    ("absent_multiplied_not_skipped",
+     "if (w[m] == 0.0)\n                continue;\n            Delta += w[m] * (Theta",
+     "Delta += w[m] * (Theta"),
+    ("rda_absent_multiplied_not_skipped",
+     "if (w[m] == 0.0 || norm[m] == 0.0)\n                    continue;", ""),
     ("momentum_dropped", "double v_new = mu * (double)v[i] + Delta;", "double v_new = Delta;"),
     ("momentum_dampened", "double v_new = mu * (double)v[i] + Delta;",
      "double v_new = mu * (double)v[i] + (1.0 - mu) * Delta;"),
@@ -42,6 +46,15 @@ MUTANTS = [
      "return (uint16_t)(lo_bits >> 16);\n}"),
     ("bf16_round_ties_away", "    double dhi = fabs((double)hi - (double)x);\n    if (dlo < dhi) return (uint16_t)(lo_bits >> 16);\n    if (dhi < dlo) return (uint16_t)(hi_bits >> 16);\n    return (uint16_t)((((lo_bits >> 16) & 1u) == 0 ? lo_bits : hi_bits) >> 16);",
      "    double dhi = fabs((double)hi - (double)x);\n    if (dlo < dhi) return (uint16_t)(lo_bits >> 16);\n    return (uint16_t)(hi_bits >> 16);"),
+    ("rda_norm_not_sqrt", "norm[m] = sqrt(ss);", "norm[m] = ss;"),
+    ("rda_mean_norm_unweighted", "mean_norm += w[m] * norm[m];", "mean_norm += norm[m] / M;"),
+    ("rda_direction_not_normalised", "u += w[m] * (d / norm[m]);", "u += w[m] * d;"),
+    ("rda_direction_unweighted", "u += w[m] * (d / norm[m]);", "u += (d / norm[m]);"),
+    ("rda_mean_direction_not_projected", "mean_norm * (v_out[i] / dir_norm)", "mean_norm * v_out[i]"),
+    ("rda_sign", "double d = (double)theta[i] - learner_value(learner_params[m], learner_dtype, i);\n                u +=",
+     "double d = learner_value(learner_params[m], learner_dtype, i) - (double)theta[i];\n                u +="),
+    ("rda_groups_merged", "size_t hi = n - lo < group_len ? n : lo + group_len;", "size_t hi = n; group_len = n;"),
+    ("rda_momentum_dropped", "double v_new = (double)mu * (double)v[i] + Delta;", "double v_new = Delta;"),
     ("chunk_overlap", "size_t lo = per * (size_t)t;", "size_t lo = per * (size_t)t + (t ? 1 : 0);"),
 ]
 
