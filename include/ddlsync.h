@@ -133,6 +133,40 @@ DDL_API ddl_status ddl_merge_fragment_bcast(float* theta, float* v, void* theta_
                                             float mu, void* hip_stream);
 
 /*
+ * Radial-directional averaging (Appendix D.2, "Radial-directional averaging", weighted form)
+ * as the merge, fused with the same outer Nesterov step, for one flat tensor.  With
+ * d_m = Theta - theta_m over a group of elements and normalised weights w_m,
+ *
+ *     Delta = ( sum_m w_m ||d_m|| ) * phi( sum_m w_m phi(d_m) ),     phi(x) = x / ||x||_2
+ *
+ * so norms and directions are averaged separately (the paper merges the non-embedding
+ * parameters this way, Section 5.1).  Readings where the paper is silent or garbled: the first
+ * factor of the printed weighted formula is the weighted mean of the norms; one norm is taken
+ * per group of `group_len` consecutive elements (group_len = row length: one magnitude per
+ * row; group_len >= n: one per tensor; the last group may be shorter); a learner whose outer
+ * gradient is zero on a group adds no direction there; a zero mean direction gives Delta = 0.
+ *
+ *   workspace        device scratch of at least ddl_rda_workspace_bytes(n, group_len, M) bytes,
+ *                    256-byte aligned, owned by the caller, overwritten; it must stay valid
+ *                    until the stream has run the call and must not be shared by calls that
+ *                    may overlap in time
+ *   other arguments  as ddl_merge_fragment
+ *
+ * Enqueues five kernels (three sweeps over the data, two per-group reductions); allocates
+ * nothing.  Results are reproducible (no atomics).  HBM traffic is up to three reads of the
+ * learners and of Theta; groups that fit the caches are re-read from there.
+ * Errors as ddl_merge_fragment, plus INVALID_ARG for group_len == 0 or a workspace that is
+ * NULL, misaligned or too small, and ALIAS if the workspace overlaps any array of the call.
+ */
+DDL_API size_t ddl_rda_workspace_bytes(size_t n, size_t group_len, int M);
+DDL_API ddl_status ddl_rda_merge_fragment(float* theta, float* v,
+                                          const void* const* learner_params,
+                                          ddl_dtype learner_dtype, const uint64_t* token_counts,
+                                          const uint8_t* quorum_mask, int M, size_t n,
+                                          size_t group_len, float lr, float mu, void* workspace,
+                                          size_t workspace_bytes, void* hip_stream);
+
+/*
  * A fragment as the paper forms it: a set of whole tensors (Section 5.1 and Appendix C,
  * balanced tensor fragmentation), each tensor its own flat array ("segment").  All segments of
  * a fragment share the fragment's counters, mask, lr and mu (per-fragment counters c_{m,p},

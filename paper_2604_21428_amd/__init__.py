@@ -83,6 +83,12 @@ def _load() -> ctypes.CDLL:
     lib.ddl_plan_num_fragments.restype = ctypes.c_int
     lib.ddl_plan_num_elements.argtypes = [ctypes.c_void_p]
     lib.ddl_plan_num_elements.restype = ctypes.c_size_t
+    lib.ddl_rda_workspace_bytes.argtypes = [ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int]
+    lib.ddl_rda_workspace_bytes.restype = ctypes.c_size_t
+    lib.ddl_rda_merge_fragment.argtypes = [ctypes.c_void_p, ctypes.c_void_p, vpp, ctypes.c_int, u64p,
+                                           u8p, ctypes.c_int, ctypes.c_size_t, ctypes.c_size_t,
+                                           ctypes.c_float, ctypes.c_float, ctypes.c_void_p,
+                                           ctypes.c_size_t, ctypes.c_void_p]
     lib.ddl_balanced_fragments.argtypes = [u64p, ctypes.c_int, ctypes.c_int,
                                            ctypes.POINTER(ctypes.c_int)]
     lib.ddl_copy_probe.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
@@ -92,7 +98,8 @@ def _load() -> ctypes.CDLL:
     for name in ("ddl_compute_weights", "ddl_compute_weights_quality", "ddl_merge_fragment",
                  "ddl_merge_fragment_weighted", "ddl_merge_batch", "ddl_plan_create",
                  "ddl_plan_merge", "ddl_plan_destroy", "ddl_set_option", "ddl_get_option",
-                 "ddl_copy_probe", "ddl_balanced_fragments", "ddl_merge_fragment_bcast"):
+                 "ddl_copy_probe", "ddl_balanced_fragments", "ddl_merge_fragment_bcast",
+                 "ddl_rda_merge_fragment"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -216,6 +223,32 @@ def merge_fragment_bcast(theta: torch.Tensor, v: torch.Tensor, theta_bf16: torch
                                          _bf16_ptr(theta_bf16, n), table, code,
                                          _u64(token_counts, M), _u8(quorum_mask, M), M, n, lr, mu,
                                          _stream_handle(stream)), "ddl_merge_fragment_bcast")
+
+
+def rda_workspace_bytes(n: int, group_len: int, M: int) -> int:
+    """ddl_rda_workspace_bytes: device scratch the RDA merge of n elements needs."""
+    return _lib.ddl_rda_workspace_bytes(n, group_len, M)
+
+
+def rda_merge_fragment(theta: torch.Tensor, v: torch.Tensor,
+                       learner_params: Sequence[Optional[torch.Tensor]], token_counts,
+                       quorum_mask, group_len: int, lr: float, mu: float,
+                       workspace: torch.Tensor, stream=None, learner_dtype=None) -> None:
+    """ddl_rda_merge_fragment: in-place sync of one flat tensor with radial-directional
+    averaging; ``workspace`` is a device byte tensor of at least rda_workspace_bytes()."""
+    n = theta.numel()
+    if v.numel() != n:
+        raise ValueError("theta and v differ in size")
+    M = len(learner_params)
+    table, code = _learner_table(learner_params, n,
+                                 None if learner_dtype is None else _dtype_code(learner_dtype))
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise TypeError("workspace must be a contiguous device tensor")
+    _check(_lib.ddl_rda_merge_fragment(_state_ptr(theta, "theta"), _state_ptr(v, "v"), table, code,
+                                       _u64(token_counts, M), _u8(quorum_mask, M), M, n,
+                                       group_len, lr, mu, workspace.data_ptr(),
+                                       workspace.numel() * workspace.element_size(),
+                                       _stream_handle(stream)), "ddl_rda_merge_fragment")
 
 
 def merge_fragment_weighted(theta: torch.Tensor, v: torch.Tensor,

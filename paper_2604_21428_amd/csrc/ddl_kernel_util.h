@@ -1,0 +1,117 @@
+// Device-side helpers shared by the gfx950 kernels of libddlsync: explicit address-space
+// accesses with cache hints, scalar-register broadcast, bf16 widening and rounding, and the
+// per-element outer step.  Everything is in an unnamed namespace: each kernel file gets its
+// own inlined copy.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#ifndef DDL_NT_LOAD
+#define DDL_NT_LOAD 1
+#endif
+#ifndef DDL_NT_STATE_LOAD
+#define DDL_NT_STATE_LOAD DDL_NT_LOAD
+#endif
+#ifndef DDL_NT_STORE
+#define DDL_NT_STORE 1
+#endif
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// All tensor accesses go through explicit global-address-space pointers built from a
+// 64-bit base held in scalar registers plus a 32-bit per-lane index.
+#define DDL_GLOBAL __attribute__((address_space(1)))
+#define DDL_CONST __attribute__((address_space(4)))
+
+template <typename T, bool NT>
+__device__ __forceinline__ T ld(uint64_t base, uint32_t index)
+{
+    const DDL_GLOBAL T* p = reinterpret_cast<const DDL_GLOBAL T*>(base) + index;
+    if (NT) return __builtin_nontemporal_load(p);
+    return *p;
+}
+
+template <typename T>
+__device__ __forceinline__ void st(uint64_t base, uint32_t index, T x)
+{
+    DDL_GLOBAL T* p = reinterpret_cast<DDL_GLOBAL T*>(base) + index;
+#if DDL_NT_STORE
+    __builtin_nontemporal_store(x, p);
+#else
+    *p = x;
+#endif
+}
+
+// Values that are the same for every lane of a workgroup (tile geometry, base addresses) are
+// moved to scalar registers explicitly, so that sixteen 64-bit learner addresses do not sit
+// in vector registers of every lane.
+__device__ __forceinline__ uint32_t uniform(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
+__device__ __forceinline__ uint64_t uniform(uint64_t x)
+{
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// bf16 is the upper half of an fp32 word, so widening is a shift or a mask.
+__device__ __forceinline__ float bf16_even(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float bf16_odd(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }
+
+// Learner element types: `raw` is the register image of the four elements a lane loads.
+struct LearnerF32 {
+    typedef float elem;
+    typedef u32x4 raw;
+    static __device__ __forceinline__ void widen(const raw& r, float (&x)[4])
+    {
+        x[0] = __uint_as_float(r.x);
+        x[1] = __uint_as_float(r.y);
+        x[2] = __uint_as_float(r.z);
+        x[3] = __uint_as_float(r.w);
+    }
+    static __device__ __forceinline__ float widen1(float e) { return e; }
+};
+
+struct LearnerBF16 {
+    typedef uint16_t elem;
+    typedef u32x2 raw;
+    static __device__ __forceinline__ void widen(const raw& r, float (&x)[4])
+    {
+        x[0] = bf16_even(r.x);
+        x[1] = bf16_odd(r.x);
+        x[2] = bf16_even(r.y);
+        x[3] = bf16_odd(r.y);
+    }
+    static __device__ __forceinline__ float widen1(uint16_t e)
+    {
+        return __uint_as_float((uint32_t)e << 16);
+    }
+};
+
+// fp32 -> bf16, round to nearest, ties to even; NaN stays a (quiet) NaN.
+__device__ __forceinline__ uint32_t bf16_rne(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// One element: Delta = sum_j w_j (Theta - x_j); v' = mu v + Delta;
+// Theta' = Theta - lr (Delta + mu v').  The difference form keeps the fp32 rounding of the
+// weights (their sum is 1 only to ~1e-7) away from |Theta|.
+template <int MQ>
+__device__ __forceinline__ void outer_step(float& theta, float& v, const float (&x)[MQ],
+                                           const float (&w)[MQ], float lr, float mu)
+{
+    float delta = 0.0f;
+#pragma unroll
+    for (int j = 0; j < MQ; ++j) delta = fmaf(w[j], theta - x[j], delta);
+    const float v_new = fmaf(mu, v, delta);
+    theta = fmaf(-lr, fmaf(mu, v_new, delta), theta);
+    v = v_new;
+}
+
+}  // namespace

@@ -1,0 +1,167 @@
+"""Radial-directional averaging on the GPU (ddl_rda_merge_fragment) against the fp64 oracle."""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import ddl_synth
+import oracle
+from ddl_testutil import assert_parity, host_learners, random_problem
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def ddl():
+    import paper_2604_21428_amd as ddl
+    assert torch.cuda.is_available()
+    return ddl
+
+
+def _workspace(ddl, n, g, M):
+    nbytes = ddl.rda_workspace_bytes(n, g, M)
+    assert nbytes > 0
+    return torch.full((nbytes,), 0xA5, dtype=torch.uint8, device=DEV)   # garbage on purpose
+
+
+def _run(ddl, theta, v, learners, tokens, mask, g, lr, mu, what):
+    n = theta.numel()
+    ref = oracle.rda_merge_fragment(ddl_synth.to_host_array(theta), ddl_synth.to_host_array(v),
+                                    host_learners(learners), tokens, mask, g, lr, mu)
+    ws = _workspace(ddl, n, g, len(learners))
+    print(f"case {what}", flush=True)
+    ddl.rda_merge_fragment(theta, v, learners, tokens, mask, g, lr, mu, ws)
+    torch.cuda.synchronize()
+    assert_parity(ddl_synth.to_host_array(theta), ref[0], what + " theta")
+    assert_parity(ddl_synth.to_host_array(v), ref[1], what + " v")
+
+
+def test_golden_cases(ddl):
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "merge_worked.json")
+    for c in json.load(open(path))["rda_cases"]:
+        theta = torch.tensor(c["theta"], dtype=torch.float32, device=DEV)
+        v = torch.tensor(c["v"], dtype=torch.float32, device=DEV)
+        learners = [torch.tensor(x, dtype=torch.float32, device=DEV) for x in c["learners"]]
+        ws = _workspace(ddl, theta.numel(), c["group_len"], len(learners))
+        ddl.rda_merge_fragment(theta, v, learners, c["token_counts"], c["quorum_mask"],
+                               c["group_len"], c["lr"], c["mu"], ws)
+        torch.cuda.synchronize()
+        d = np.asarray(c["delta"])
+        assert np.allclose(v.cpu().numpy(), d, rtol=0, atol=2e-6 * (1 + np.abs(d).max())), c["name"]
+        assert np.allclose(theta.cpu().numpy(), np.asarray(c["theta"]) - d, rtol=0, atol=2e-5)
+
+
+CASES = [(1, 1), (3, 2), (4, 4), (64, 8), (1000, 100), (1001, 7), (4096, 1024), (10000, 2048),
+         (8192 * 3, 8192), (8192 * 3 + 12, 8196), (50000, 20000), (50003, 50003), (70001, 10 ** 9),
+         (3 * 16384 + 5, 4)]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("n,g", CASES)
+def test_sizes_and_group_lengths(ddl, dtype, n, g):
+    theta, v, learners, tokens, mask = random_problem(500 + n, n, 3, dtype, DEV)
+    _run(ddl, theta, v, learners, tokens, mask, g, 0.7, 0.9, f"n={n} g={g} {dtype}")
+
+
+@pytest.mark.parametrize("Mq", [1, 2, 5, 8, 11, 16])
+def test_quorum_sizes(ddl, Mq):
+    M, n = 16, 30000
+    rng = np.random.default_rng(Mq)
+    mask = np.zeros(M, dtype=np.int64)
+    mask[rng.choice(M, size=Mq, replace=False)] = 1
+    theta, v, learners, tokens, _ = random_problem(600 + Mq, n, M, torch.bfloat16, DEV)
+    for m in range(M):
+        if not mask[m]:
+            learners[m] = None if m % 2 else learners[m].fill_(float("nan"))
+    _run(ddl, theta, v, learners, tokens, mask.tolist(), 1500, 0.7, 0.9, f"Mq={Mq}")
+
+
+@pytest.mark.parametrize("offset", [1, 2, 3])
+def test_misaligned(ddl, offset):
+    theta, v, learners, tokens, mask = random_problem(700 + offset, 20001, 3, torch.bfloat16, DEV,
+                                                      offset=offset)
+    _run(ddl, theta, v, learners, tokens, mask, 2000, 0.7, 0.9, f"offset={offset}")
+
+
+def test_zero_outer_gradient_on_some_groups(ddl):
+    n, g = 4096, 512
+    theta, v, learners, tokens, mask = random_problem(800, n, 3, torch.float32, DEV)
+    learners[0][512:1024] = theta[512:1024]          # learner 0 has no outer gradient on group 1
+    for x in learners:
+        x[2048:2560] = theta[2048:2560]              # nobody has one on group 4
+    _run(ddl, theta, v, learners, tokens, mask, g, 0.7, 0.9, "zero gradients")
+
+
+def test_row_norms_of_a_full_size_matrix(ddl):
+    """A 2048 x 8192 matrix (the dense block's W_up), one norm per row, checked on whole rows."""
+    rows, cols = 2048, 8192
+    n = rows * cols
+    theta, v, learners, tokens, mask = random_problem(900, n, 4, torch.bfloat16, DEV,
+                                                      mask=[1, 1, 0, 1])
+    picks = [0, 1, 777, rows - 1]
+    refs = []
+    for r in picks:
+        sl = slice(r * cols, (r + 1) * cols)
+        refs.append(oracle.rda_merge_fragment(
+            ddl_synth.to_host_array(theta[sl]), ddl_synth.to_host_array(v[sl]),
+            host_learners(learners, r * cols, (r + 1) * cols), tokens, mask, cols, 0.7, 0.9))
+    ws = _workspace(ddl, n, cols, 4)
+    ddl.rda_merge_fragment(theta, v, learners, tokens, mask, cols, 0.7, 0.9, ws)
+    torch.cuda.synchronize()
+    for r, ref in zip(picks, refs):
+        sl = slice(r * cols, (r + 1) * cols)
+        assert_parity(ddl_synth.to_host_array(theta[sl]), ref[0], f"row {r} theta")
+        assert_parity(ddl_synth.to_host_array(v[sl]), ref[1], f"row {r} v")
+
+
+def test_whole_tensor_norm_of_a_full_size_matrix(ddl):
+    n = 2048 * 2048
+    theta, v, learners, tokens, mask = random_problem(901, n, 3, torch.bfloat16, DEV)
+    _run(ddl, theta, v, learners, tokens, mask, n, 0.7, 0.9, "whole tensor 2048x2048")
+
+
+def test_single_learner_equals_direct_merge(ddl):
+    n = 12345
+    theta, v, learners, tokens, _ = random_problem(902, n, 3, torch.bfloat16, DEV)
+    th2, v2 = theta.clone(), v.clone()
+    ws = _workspace(ddl, n, 500, 3)
+    ddl.rda_merge_fragment(theta, v, learners, tokens, [0, 0, 1], 500, 0.7, 0.9, ws)
+    ddl.merge_fragment(th2, v2, learners, tokens, [0, 0, 1], 0.7, 0.9)
+    torch.cuda.synchronize()
+    assert torch.allclose(theta, th2, rtol=0, atol=1e-8) and torch.allclose(v, v2, rtol=0, atol=1e-8)
+
+
+def test_reproducible(ddl):
+    n = 100003
+    a = random_problem(903, n, 4, torch.bfloat16, DEV)
+    b = random_problem(903, n, 4, torch.bfloat16, DEV)
+    for th, v, ls, tok, mask in (a, b):
+        ddl.rda_merge_fragment(th, v, ls, tok, mask, 3000, 0.7, 0.9, _workspace(ddl, n, 3000, 4))
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+def test_errors(ddl):
+    n = 5000
+    theta, v, learners, tokens, mask = random_problem(904, n, 3, torch.bfloat16, DEV)
+    th0, v0 = theta.clone(), v.clone()
+    ws = _workspace(ddl, n, 100, 3)
+    with pytest.raises(ddl.DdlError) as e:
+        ddl.rda_merge_fragment(theta, v, learners, tokens, mask, 0, 0.7, 0.9, ws)
+    assert e.value.status == ddl.DDL_ERR_INVALID_ARG
+    with pytest.raises(ddl.DdlError) as e:
+        ddl.rda_merge_fragment(theta, v, learners, tokens, mask, 100, 0.7, 0.9, ws[:256])
+    assert e.value.status == ddl.DDL_ERR_INVALID_ARG
+    with pytest.raises(ddl.DdlError) as e:
+        ddl.rda_merge_fragment(theta, v, learners, tokens, [0, 0, 0], 100, 0.7, 0.9, ws)
+    assert e.value.status == ddl.DDL_ERR_EMPTY_QUORUM
+    with pytest.raises(ddl.DdlError) as e:
+        ddl.rda_merge_fragment(theta, v, learners, tokens, mask, 100, 0.7, 0.9,
+                               theta.view(torch.uint8))
+    assert e.value.status == ddl.DDL_ERR_ALIAS
+    torch.cuda.synchronize()
+    assert torch.equal(theta, th0) and torch.equal(v, v0)
+    assert ddl.rda_workspace_bytes(0, 10, 3) == 0 and ddl.rda_workspace_bytes(10, 0, 3) == 0
