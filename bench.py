@@ -52,11 +52,17 @@ def parse_args():
     ap.add_argument("--balanced", type=int, default=0, metavar="P",
                     help="regroup the workload's tensors into P balanced fragments with "
                          "ddl_balanced_fragments (the paper uses P = 24)")
+    ap.add_argument("--merge", default="avg", choices=["avg", "rda"],
+                    help="avg: weighted direct averaging (the metric's path); rda: "
+                         "radial-directional averaging, one ddl_rda_merge_fragment per tensor")
+    ap.add_argument("--rda-group", default="row", choices=["row", "tensor"],
+                    help="one norm per row of the last dimension, or one per tensor")
     ap.add_argument("--bcast", action="store_true",
                     help="also write the new Theta as bf16 in the same pass (+2 B/param)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tiles-per-block", type=int, default=None)
     ap.add_argument("--max-blocks-per-cu", type=int, default=None)
+    ap.add_argument("--rda-blocks-per-cu", type=int, default=None)
     return ap.parse_args()
 
 
@@ -146,6 +152,8 @@ def main():
         ddl.set_option("tiles_per_block", args.tiles_per_block)
     if args.max_blocks_per_cu is not None:
         ddl.set_option("max_blocks_per_cu", args.max_blocks_per_cu)
+    if args.rda_blocks_per_cu is not None:
+        ddl.set_option("rda_blocks_per_cu", args.rda_blocks_per_cu)
 
     wl = ddl_synth.WORKLOADS[args.workload]()
     if args.balanced:
@@ -171,7 +179,17 @@ def main():
             for s in segs:
                 s.bcast = (torch.empty(s.theta.numel(), dtype=torch.bfloat16, device="cuda:0")
                            if args.bcast else None)
-        if args.api == "plan":
+        if args.merge == "rda":
+            calls = []
+            for fi in wl.arrival_order:
+                f = wl.fragments[fi]
+                for s, t in zip(data[fi], f.tensors):
+                    g = t.shape[-1] if args.rda_group == "row" else t.numel
+                    ws = torch.empty(ddl.rda_workspace_bytes(t.numel, g, f.M), dtype=torch.uint8,
+                                     device="cuda:0")
+                    calls.append((s, f, g, ws))
+            copies.append((data, "rda", calls))
+        elif args.api == "plan":
             plan = ddl.Plan([ddl.Fragment([(s.theta, s.v, s.learners, s.bcast) for s in segs], M=f.M,
                                           learner_dtype=dt[f.learner_dtype])
                              for f, segs in zip(wl.fragments, data)])
@@ -191,14 +209,18 @@ def main():
     def step():
         _, plan, calls = copies[counter[0] % replicas]
         counter[0] += 1
-        if plan is not None:
+        if plan == "rda":
+            for s, f, g, ws in calls:
+                ddl.rda_merge_fragment(s.theta, s.v, s.learners, f.token_counts, f.quorum_mask, g,
+                                       f.lr, f.mu, ws)
+        elif plan is not None:
             for c in calls:
                 plan.merge(c)
         else:
             for fi in wl.arrival_order:
                 ddl.merge_batch([calls[fi]])
 
-    launches_per_step = len(wl.arrival_order)
+    launches_per_step = len(wl.arrival_order) if args.merge == "avg" else wl.num_segments
     torch.cuda.synchronize()
 
     # ---- timed region ---------------------------------------------------------------------
@@ -224,7 +246,8 @@ def main():
     kernel_ms = gpu_ms / launches_per_step
     achieved = alg_bytes / launches_per_step / (kernel_ms * 1e-3) / 1e9
     copy_gbps = time_copy_probe(ddl, torch)
-    traffic = None if args.bcast else MEASURED_TRAFFIC_BYTES.get(wl.name)
+    traffic = (None if args.bcast or args.merge != "avg"
+               else MEASURED_TRAFFIC_BYTES.get(wl.name))
 
     out = {
         "metric": METRIC,
@@ -250,7 +273,9 @@ def main():
             "state_dtype": "f32",
             "lr": wl.fragments[0].lr,
             "mu": wl.fragments[0].mu,
-            "api": "ddl_plan_merge" if args.api == "plan" else "ddl_merge_batch",
+            "api": ("ddl_rda_merge_fragment" if args.merge == "rda" else
+                    "ddl_plan_merge" if args.api == "plan" else "ddl_merge_batch"),
+            "merge": args.merge if args.merge == "avg" else f"rda/{args.rda_group}",
             "launches_per_step": launches_per_step,
             "replicas": replicas,
             "bf16_broadcast_copy": bool(args.bcast),
@@ -266,7 +291,7 @@ def main():
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBPS,
             "traffic": traffic,
-            "kernel": "ddl_merge_kernel",
+            "kernel": "ddl_merge_kernel" if args.merge == "avg" else "rda sweeps (5 kernels)",
             "avg_launch_ms": kernel_ms,
             "algorithmic_bytes_per_launch": alg_bytes / launches_per_step,
             "copy_probe_gbps": copy_gbps,

@@ -65,3 +65,7 @@ int ddl_launch_merge(int dtype, int Mq, bool flat, uint32_t grid, uint32_t lds_b
 
 // Launches the plain 16-byte-per-lane copy of n16 * 16 bytes; grid = ceil(n16 / DDL_BLOCK).
 int ddl_launch_copy(void* dst, const void* src, uint64_t n16, uint32_t grid, void* stream);
+
+// Launch-shape knob of the one-kernel RDA shape (set through ddl_set_option): at most this
+// many workgroups resident per compute unit (0: no cap), enforced with unused dynamic LDS.
+extern long ddl_opt_rda_blocks_per_cu;

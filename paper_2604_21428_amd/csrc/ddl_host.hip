@@ -16,6 +16,8 @@
 
 static_assert(DDL_MAXL == DDL_MAX_LEARNERS, "device and public learner limits differ");
 
+long ddl_opt_rda_blocks_per_cu = 0;
+
 namespace {
 
 thread_local std::string g_err;
@@ -685,6 +687,11 @@ ddl_status ddl_set_option(const char* name, long value)
         g_max_blocks_per_cu = value;
         return DDL_OK;
     }
+    if (!std::strcmp(name, "rda_blocks_per_cu")) {
+        if (value != 0 && (value < 3 || value > 64)) return DDL_ERR_INVALID_ARG;
+        ddl_opt_rda_blocks_per_cu = value;
+        return DDL_OK;
+    }
     return DDL_ERR_INVALID_ARG;
 }
 
@@ -698,6 +705,10 @@ ddl_status ddl_get_option(const char* name, long* value_out)
     }
     if (!std::strcmp(name, "max_blocks_per_cu")) {
         *value_out = g_max_blocks_per_cu;
+        return DDL_OK;
+    }
+    if (!std::strcmp(name, "rda_blocks_per_cu")) {
+        *value_out = ddl_opt_rda_blocks_per_cu;
         return DDL_OK;
     }
     return DDL_ERR_INVALID_ARG;

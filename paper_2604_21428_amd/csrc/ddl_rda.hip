@@ -7,8 +7,14 @@
 //     u     = sum_j (w_j / N_j) d_j       mean unit direction (learners with N_j = 0 left out)
 //     Delta = R * u / ||u||               (0 if u = 0)
 //
-// Three sweeps over the data, each a grid of one workgroup per "chunk" (at most DDL_RDA_CHUNK
-// consecutive elements of one group), with two tiny per-group kernels in between:
+// Two launch shapes.
+// (a) Groups of moderate length (a row of a weight matrix) and many of them: ONE kernel, one
+//     workgroup per group, which makes the three sweeps below over its own group back to back
+//     and keeps the two reductions in LDS.  The second and third sweep find the group in L2 or
+//     in the last-level cache, so HBM sees every byte about once, and no workspace is used.
+// (b) Long or few groups (one norm per tensor): three sweeps over the data, each a grid of one
+//     workgroup per "chunk" (at most DDL_RDA_CHUNK consecutive elements of one group), with
+//     two small per-group kernels in between:
 //   sweep 1  partial sums of d_j^2 per chunk        -> reduce: coefficients c_j = w_j / N_j, R
 //   sweep 2  partial sums of u^2 per chunk           -> reduce: scale = R / ||u||
 //   sweep 3  Delta = scale * u, outer step, write Theta and v
@@ -73,6 +79,32 @@ __device__ __forceinline__ float block_sum(float x, float* lds /* DDL_BLOCK / 64
     if (threadIdx.x == 0)
         for (int k = 0; k < DDL_BLOCK / 64; ++k) s += lds[k];
     return s;
+}
+
+// The same sum, delivered to every thread.
+__device__ __forceinline__ float block_sum_all(float x, float* lds /* DDL_BLOCK / 64 + 1 floats */)
+{
+    const float s = block_sum(x, lds);
+    if (threadIdx.x == 0) lds[DDL_BLOCK / 64] = s;
+    __syncthreads();
+    return lds[DDL_BLOCK / 64];
+}
+
+// Sum of count floats at p[k * stride], k < count, by the whole workgroup, in double and in a
+// fixed order; valid in thread 0.
+__device__ __forceinline__ double block_sum_strided(const float* p, uint32_t count, uint32_t stride,
+                                                    double* lds /* DDL_BLOCK doubles */)
+{
+    double s = 0.0;
+    for (uint32_t k = threadIdx.x; k < count; k += DDL_BLOCK) s += (double)p[(size_t)k * stride];
+    __syncthreads();
+    lds[threadIdx.x] = s;
+    __syncthreads();
+    for (int half = DDL_BLOCK / 2; half > 0; half >>= 1) {
+        if ((int)threadIdx.x < half) lds[threadIdx.x] += lds[threadIdx.x + half];
+        __syncthreads();
+    }
+    return lds[0];
 }
 
 // Walks the chunk: F(d[MQ], theta, v, element index within the chunk, is the first argument
@@ -152,24 +184,22 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_sumsq_kernel(const DdlRdaArgs a
     }
 }
 
-// One thread per group: norms from the chunk partials (in double, fixed order), then the
+// One workgroup per group: norms from the chunk partials (in double, fixed order), then the
 // direction coefficients w_j / N_j and the mean norm.
-__global__ void rda_norms_kernel(const DdlRdaArgs a, int Mq, uint32_t groups)
+__global__ void __launch_bounds__(DDL_BLOCK) rda_norms_kernel(const DdlRdaArgs a, int Mq)
 {
-    const uint32_t r = blockIdx.x * blockDim.x + threadIdx.x;
-    if (r >= groups) return;
-    const float* p1 = reinterpret_cast<const float*>(a.partial1);
+    __shared__ double lds[DDL_BLOCK];
+    const uint32_t r = blockIdx.x;
+    const float* p1 = reinterpret_cast<const float*>(a.partial1) + (size_t)r * a.chunks_per_group * Mq;
     float* coef = reinterpret_cast<float*>(a.coef) + (size_t)r * Mq;
     double R = 0.0;
     for (int j = 0; j < Mq; ++j) {
-        double ss = 0.0;
-        for (uint32_t k = 0; k < a.chunks_per_group; ++k)
-            ss += (double)p1[((size_t)r * a.chunks_per_group + k) * Mq + j];
+        const double ss = block_sum_strided(p1 + j, a.chunks_per_group, (uint32_t)Mq, lds);
         const double N = sqrt(ss);
         R += (double)a.w[j] * N;
-        coef[j] = N > 0.0 ? (float)((double)a.w[j] / N) : 0.0f;
+        if (threadIdx.x == 0) coef[j] = N > 0.0 ? (float)((double)a.w[j] / N) : 0.0f;
     }
-    reinterpret_cast<float*>(a.mean_norm)[r] = (float)R;
+    if (threadIdx.x == 0) reinterpret_cast<float*>(a.mean_norm)[r] = (float)R;
 }
 
 template <int MQ>
@@ -209,17 +239,14 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_dirsq_kernel(const DdlRdaArgs a
     if (threadIdx.x == 0) reinterpret_cast<float*>(a.partial2)[blockIdx.x] = s;
 }
 
-__global__ void rda_scale_kernel(const DdlRdaArgs a, uint32_t groups)
+__global__ void __launch_bounds__(DDL_BLOCK) rda_scale_kernel(const DdlRdaArgs a)
 {
-    const uint32_t r = blockIdx.x * blockDim.x + threadIdx.x;
-    if (r >= groups) return;
-    const float* p2 = reinterpret_cast<const float*>(a.partial2);
-    double ss = 0.0;
-    for (uint32_t k = 0; k < a.chunks_per_group; ++k)
-        ss += (double)p2[(size_t)r * a.chunks_per_group + k];
-    const double U = sqrt(ss);
+    __shared__ double lds[DDL_BLOCK];
+    const uint32_t r = blockIdx.x;
+    const float* p2 = reinterpret_cast<const float*>(a.partial2) + (size_t)r * a.chunks_per_group;
+    const double U = sqrt(block_sum_strided(p2, a.chunks_per_group, 1, lds));
     const double R = (double)reinterpret_cast<const float*>(a.mean_norm)[r];
-    reinterpret_cast<float*>(a.scale)[r] = U > 0.0 ? (float)(R / U) : 0.0f;
+    if (threadIdx.x == 0) reinterpret_cast<float*>(a.scale)[r] = U > 0.0 ? (float)(R / U) : 0.0f;
 }
 
 template <typename L, int MQ>
@@ -259,10 +286,99 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_apply_kernel(const DdlRdaArgs a
         });
 }
 
+// Launch shape (a): one workgroup makes all three sweeps over its own group.
+template <typename L, int MQ>
+__global__ void __launch_bounds__(DDL_BLOCK) rda_group_kernel(const DdlRdaArgs a)
+{
+    __shared__ float lds[DDL_BLOCK / 64 + 1];
+    const uint64_t g0 = (uint64_t)blockIdx.x * a.group_len;
+    const uint64_t g1 = a.n - g0 < a.group_len ? a.n : g0 + a.group_len;
+
+    // sweep 1: norms of the outer gradients
+    float ss[MQ];
+#pragma unroll
+    for (int j = 0; j < MQ; ++j) ss[j] = 0.0f;
+    for (uint64_t begin = g0; begin < g1; begin += DDL_RDA_CHUNK) {
+        const uint64_t end = begin + DDL_RDA_CHUNK < g1 ? begin + DDL_RDA_CHUNK : g1;
+        sweep_chunk<L, MQ, false>(
+            a, begin, end, false,
+            [&](const float (&d)[4][MQ], const f32x4&, const f32x4&, uint32_t) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+#pragma unroll
+                    for (int j = 0; j < MQ; ++j) ss[j] = fmaf(d[k][j], d[k][j], ss[j]);
+            },
+            [&](const float (&d)[MQ], float, float, uint32_t) {
+#pragma unroll
+                for (int j = 0; j < MQ; ++j) ss[j] = fmaf(d[j], d[j], ss[j]);
+            });
+    }
+    float c[MQ];
+    float R = 0.0f;
+#pragma unroll
+    for (int j = 0; j < MQ; ++j) {
+        const float N = sqrtf(block_sum_all(ss[j], lds));
+        R = fmaf(a.w[j], N, R);
+        c[j] = N > 0.0f ? a.w[j] / N : 0.0f;
+    }
+
+    // sweep 2: norm of the mean direction
+    float uu = 0.0f;
+    for (uint64_t begin = g0; begin < g1; begin += DDL_RDA_CHUNK) {
+        const uint64_t end = begin + DDL_RDA_CHUNK < g1 ? begin + DDL_RDA_CHUNK : g1;
+        sweep_chunk<L, MQ, false>(
+            a, begin, end, false,
+            [&](const float (&d)[4][MQ], const f32x4&, const f32x4&, uint32_t) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const float u = direction<MQ>(d[k], c);
+                    uu = fmaf(u, u, uu);
+                }
+            },
+            [&](const float (&d)[MQ], float, float, uint32_t) {
+                const float u = direction<MQ>(d, c);
+                uu = fmaf(u, u, uu);
+            });
+    }
+    const float U = sqrtf(block_sum_all(uu, lds));
+    const float scale = U > 0.0f ? R / U : 0.0f;
+#pragma unroll
+    for (int j = 0; j < MQ; ++j) c[j] *= scale;
+
+    // sweep 3: Delta = scale * u, outer step
+    const float lr = a.lr, mu = a.mu;
+    for (uint64_t begin = g0; begin < g1; begin += DDL_RDA_CHUNK) {
+        const uint64_t end = begin + DDL_RDA_CHUNK < g1 ? begin + DDL_RDA_CHUNK : g1;
+        const uint64_t th = a.theta + begin * 4, vv = a.v + begin * 4;
+        sweep_chunk<L, MQ, false>(
+            a, begin, end, true,
+            [&](const float (&d)[4][MQ], const f32x4& T, const f32x4& V, uint32_t g) {
+                float t4[4] = {T.x, T.y, T.z, T.w};
+                float v4[4] = {V.x, V.y, V.z, V.w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const float delta = direction<MQ>(d[k], c);
+                    v4[k] = fmaf(mu, v4[k], delta);
+                    t4[k] = fmaf(-lr, fmaf(mu, v4[k], delta), t4[k]);
+                }
+                const f32x4 tn = {t4[0], t4[1], t4[2], t4[3]};
+                const f32x4 vn = {v4[0], v4[1], v4[2], v4[3]};
+                st<f32x4>(th, g, tn);
+                st<f32x4>(vv, g, vn);
+            },
+            [&](const float (&d)[MQ], float t, float v, uint32_t e) {
+                const float delta = direction<MQ>(d, c);
+                const float v_new = fmaf(mu, v, delta);
+                *(reinterpret_cast<DDL_GLOBAL float*>(th) + e) = fmaf(-lr, fmaf(mu, v_new, delta), t);
+                *(reinterpret_cast<DDL_GLOBAL float*>(vv) + e) = v_new;
+            });
+    }
+}
+
 typedef void (*rda_fn)(const DdlRdaArgs);
 
 template <typename L>
-void pick(int Mq, rda_fn& k1, rda_fn& k2, rda_fn& k3)
+void pick(int Mq, rda_fn& k1, rda_fn& k2, rda_fn& k3, rda_fn& kg)
 {
     switch (Mq) {
 #define DDL_CASE(k)                        \
@@ -270,6 +386,7 @@ void pick(int Mq, rda_fn& k1, rda_fn& k2, rda_fn& k3)
         k1 = rda_sumsq_kernel<L, k>;       \
         k2 = rda_dirsq_kernel<L, k>;       \
         k3 = rda_apply_kernel<L, k>;       \
+        kg = rda_group_kernel<L, k>;       \
         break;
         DDL_CASE(1) DDL_CASE(2) DDL_CASE(3) DDL_CASE(4) DDL_CASE(5) DDL_CASE(6) DDL_CASE(7)
         DDL_CASE(8) DDL_CASE(9) DDL_CASE(10) DDL_CASE(11) DDL_CASE(12) DDL_CASE(13)
@@ -307,6 +424,11 @@ bool geometry(size_t n, size_t group_len, int Mq, Geometry& g)
     g.bytes = off;
     return true;
 }
+
+// Launch shape (a) is taken for groups no longer than this, if there are enough of them to
+// fill the GPU (one workgroup each).
+constexpr uint64_t kGroupKernelMaxLen = 65536;
+constexpr uint32_t kGroupKernelMinGroups = 512;
 
 inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
@@ -383,17 +505,27 @@ extern "C" ddl_status ddl_rda_merge_fragment(float* theta, float* v,
     a.partial2 = ws + g.off_partial2;
     a.scale = ws + g.off_scale;
 
-    rda_fn k1 = nullptr, k2 = nullptr, k3 = nullptr;
-    if (learner_dtype == DDL_F32) pick<LearnerF32>(Mq, k1, k2, k3); else pick<LearnerBF16>(Mq, k1, k2, k3);
+    rda_fn k1 = nullptr, k2 = nullptr, k3 = nullptr, kg = nullptr;
+    if (learner_dtype == DDL_F32)
+        pick<LearnerF32>(Mq, k1, k2, k3, kg);
+    else
+        pick<LearnerBF16>(Mq, k1, k2, k3, kg);
     if (!k1) return DDL_ERR_INVALID_ARG;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const dim3 grid((uint32_t)g.chunks), block(DDL_BLOCK);
+    const dim3 block(DDL_BLOCK);
     const uint32_t groups = (uint32_t)g.groups;
-    const dim3 rgrid((groups + 255) / 256), rblock(256);
-    hipLaunchKernelGGL(k1, grid, block, 0, stream, a);
-    hipLaunchKernelGGL(rda_norms_kernel, rgrid, rblock, 0, stream, a, Mq, groups);
-    hipLaunchKernelGGL(k2, grid, block, 0, stream, a);
-    hipLaunchKernelGGL(rda_scale_kernel, rgrid, rblock, 0, stream, a, groups);
-    hipLaunchKernelGGL(k3, grid, block, 0, stream, a);
+    if (a.group_len <= kGroupKernelMaxLen && groups >= kGroupKernelMinGroups) {
+        const long cap = ddl_opt_rda_blocks_per_cu;
+        uint32_t lds = cap > 0 ? (uint32_t)(DDL_LDS_PER_CU / cap) & ~511u : 0u;
+        if (lds > 60 * 1024) lds = 60 * 1024;  // static LDS of the kernel comes on top
+        hipLaunchKernelGGL(kg, dim3(groups), block, lds, stream, a);
+    } else {
+        const dim3 grid((uint32_t)g.chunks), rgrid(groups);
+        hipLaunchKernelGGL(k1, grid, block, 0, stream, a);
+        hipLaunchKernelGGL(rda_norms_kernel, rgrid, block, 0, stream, a, Mq);
+        hipLaunchKernelGGL(k2, grid, block, 0, stream, a);
+        hipLaunchKernelGGL(rda_scale_kernel, rgrid, block, 0, stream, a);
+        hipLaunchKernelGGL(k3, grid, block, 0, stream, a);
+    }
     return hipGetLastError() == hipSuccess ? DDL_OK : DDL_ERR_RUNTIME;
 }

@@ -56,7 +56,10 @@ def test_golden_cases(ddl):
 
 CASES = [(1, 1), (3, 2), (4, 4), (64, 8), (1000, 100), (1001, 7), (4096, 1024), (10000, 2048),
          (8192 * 3, 8192), (8192 * 3 + 12, 8196), (50000, 20000), (50003, 50003), (70001, 10 ** 9),
-         (3 * 16384 + 5, 4)]
+         (3 * 16384 + 5, 4),
+         # 512 groups or more: the one-kernel shape, one workgroup per group
+         (600 * 100, 100), (513 * 7, 7), (700 * 2048 + 5, 2048), (512 * 9000, 9000), (1024, 1),
+         (520 * 65536 // 64, 1024)]
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
@@ -66,8 +69,9 @@ def test_sizes_and_group_lengths(ddl, dtype, n, g):
     _run(ddl, theta, v, learners, tokens, mask, g, 0.7, 0.9, f"n={n} g={g} {dtype}")
 
 
+@pytest.mark.parametrize("g", [1500, 40])
 @pytest.mark.parametrize("Mq", [1, 2, 5, 8, 11, 16])
-def test_quorum_sizes(ddl, Mq):
+def test_quorum_sizes(ddl, Mq, g):
     M, n = 16, 30000
     rng = np.random.default_rng(Mq)
     mask = np.zeros(M, dtype=np.int64)
@@ -76,18 +80,19 @@ def test_quorum_sizes(ddl, Mq):
     for m in range(M):
         if not mask[m]:
             learners[m] = None if m % 2 else learners[m].fill_(float("nan"))
-    _run(ddl, theta, v, learners, tokens, mask.tolist(), 1500, 0.7, 0.9, f"Mq={Mq}")
+    _run(ddl, theta, v, learners, tokens, mask.tolist(), g, 0.7, 0.9, f"Mq={Mq} g={g}")
 
 
+@pytest.mark.parametrize("g", [2000, 20])
 @pytest.mark.parametrize("offset", [1, 2, 3])
-def test_misaligned(ddl, offset):
+def test_misaligned(ddl, offset, g):
     theta, v, learners, tokens, mask = random_problem(700 + offset, 20001, 3, torch.bfloat16, DEV,
                                                       offset=offset)
-    _run(ddl, theta, v, learners, tokens, mask, 2000, 0.7, 0.9, f"offset={offset}")
+    _run(ddl, theta, v, learners, tokens, mask, g, 0.7, 0.9, f"offset={offset} g={g}")
 
 
-def test_zero_outer_gradient_on_some_groups(ddl):
-    n, g = 4096, 512
+@pytest.mark.parametrize("n,g", [(4096, 512), (600 * 512, 512)])
+def test_zero_outer_gradient_on_some_groups(ddl, n, g):
     theta, v, learners, tokens, mask = random_problem(800, n, 3, torch.float32, DEV)
     learners[0][512:1024] = theta[512:1024]          # learner 0 has no outer gradient on group 1
     for x in learners:
