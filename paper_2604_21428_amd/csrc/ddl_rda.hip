@@ -12,6 +12,9 @@
 //     workgroup per group, which makes the three sweeps below over its own group back to back
 //     and keeps the two reductions in LDS.  The second and third sweep find the group in L2 or
 //     in the last-level cache, so HBM sees every byte about once, and no workspace is used.
+//     Groups of at most 16384 elements whose data fits the register file take a variant that
+//     loads the group once into registers and sweeps those: one pass over HBM, like direct
+//     averaging.
 // (b) Long or few groups (one norm per tensor): three sweeps over the data, each a grid of one
 //     workgroup per "chunk" (at most DDL_RDA_CHUNK consecutive elements of one group), with
 //     two small per-group kernels in between:
@@ -67,7 +70,8 @@ __device__ __forceinline__ void chunk_range(const DdlRdaArgs& a, uint32_t c, uin
 
 // Sum over the workgroup; the result is valid in thread 0.  Fixed order: lanes by butterfly,
 // then the four waves in sequence.
-__device__ __forceinline__ float block_sum(float x, float* lds /* DDL_BLOCK / 64 floats */)
+template <int NTH = DDL_BLOCK>
+__device__ __forceinline__ float block_sum(float x, float* lds /* NTH / 64 floats */)
 {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
@@ -77,17 +81,18 @@ __device__ __forceinline__ float block_sum(float x, float* lds /* DDL_BLOCK / 64
     __syncthreads();
     float s = 0.0f;
     if (threadIdx.x == 0)
-        for (int k = 0; k < DDL_BLOCK / 64; ++k) s += lds[k];
+        for (int k = 0; k < NTH / 64; ++k) s += lds[k];
     return s;
 }
 
 // The same sum, delivered to every thread.
-__device__ __forceinline__ float block_sum_all(float x, float* lds /* DDL_BLOCK / 64 + 1 floats */)
+template <int NTH = DDL_BLOCK>
+__device__ __forceinline__ float block_sum_all(float x, float* lds /* NTH / 64 + 1 floats */)
 {
-    const float s = block_sum(x, lds);
-    if (threadIdx.x == 0) lds[DDL_BLOCK / 64] = s;
+    const float s = block_sum<NTH>(x, lds);
+    if (threadIdx.x == 0) lds[NTH / 64] = s;
     __syncthreads();
-    return lds[DDL_BLOCK / 64];
+    return lds[NTH / 64];
 }
 
 // Sum of count floats at p[k * stride], k < count, by the whole workgroup, in double and in a
@@ -375,10 +380,169 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_group_kernel(const DdlRdaArgs a
     }
 }
 
+// Tells the compiler that a register's value may have changed.  Used between the sweeps of
+// the row kernel so that only the packed learner values stay live across them, not their
+// widened fp32 images and differences (which it would otherwise keep: 2-4x the registers).
+__device__ __forceinline__ void launder(u32x2& r) { asm volatile("" : "+v"(r.x), "+v"(r.y)); }
+__device__ __forceinline__ void launder(u32x4& r)
+{
+    asm volatile("" : "+v"(r.x), "+v"(r.y), "+v"(r.z), "+v"(r.w));
+}
+
+// Launch shape (a'), for groups of at most K * 4 * NTH elements on the aligned path: the
+// workgroup loads its whole group ONCE into registers (learner values stay packed as loaded)
+// and makes the three sweeps over the registers.  HBM traffic equals that of direct averaging.
+template <typename L, int MQ, int K, int NTH>
+__global__ void __launch_bounds__(NTH) rda_row_kernel(const DdlRdaArgs a)
+{
+    __shared__ float lds[NTH / 64 + 1];
+    typedef typename L::elem elem;
+    const uint64_t g0 = (uint64_t)blockIdx.x * a.group_len;
+    const uint64_t g1 = a.n - g0 < a.group_len ? a.n : g0 + a.group_len;
+    const uint32_t nvec = (uint32_t)(g1 - g0) / 4;  // the host sends only multiples of four here
+    const uint64_t th = a.theta + g0 * 4, vv = a.v + g0 * 4;
+    uint64_t lp[MQ];
+#pragma unroll
+    for (int j = 0; j < MQ; ++j) lp[j] = a.learner[j] + g0 * sizeof(elem);
+
+    typename L::raw raw[K][MQ];
+    f32x4 T[K];
+#pragma unroll
+    for (int u = 0; u < K; ++u) {
+        const uint32_t g = threadIdx.x + u * NTH;
+        if (g < nvec) {
+#pragma unroll
+            for (int j = 0; j < MQ; ++j) raw[u][j] = ld<typename L::raw, true>(lp[j], g);
+            T[u] = ld<f32x4, true>(th, g);
+        } else {  // lanes past the end of the group hold a zero outer gradient
+#pragma unroll
+            for (int j = 0; j < MQ; ++j) raw[u][j] = typename L::raw(0);
+            T[u] = f32x4(0.0f);
+        }
+    }
+
+    // outer gradients of group u, element k, recomputed from the packed registers on demand
+    auto diffs = [&](int u, float (&d)[4][MQ]) {
+        float x[MQ][4];
+#pragma unroll
+        for (int j = 0; j < MQ; ++j) L::widen(raw[u][j], x[j]);
+        const float t4[4] = {T[u].x, T[u].y, T[u].z, T[u].w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int j = 0; j < MQ; ++j) d[k][j] = t4[k] - x[j][k];
+    };
+
+    float ss[MQ];
+#pragma unroll
+    for (int j = 0; j < MQ; ++j) ss[j] = 0.0f;
+#pragma unroll
+    for (int u = 0; u < K; ++u) {
+        float d[4][MQ];
+        diffs(u, d);
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int j = 0; j < MQ; ++j) ss[j] = fmaf(d[k][j], d[k][j], ss[j]);
+    }
+    float c[MQ];
+    float R = 0.0f;
+#pragma unroll
+    for (int j = 0; j < MQ; ++j) {
+        const float N = sqrtf(block_sum_all<NTH>(ss[j], lds));
+        R = fmaf(a.w[j], N, R);
+        c[j] = N > 0.0f ? a.w[j] / N : 0.0f;
+    }
+
+#pragma unroll
+    for (int u = 0; u < K; ++u)
+#pragma unroll
+        for (int j = 0; j < MQ; ++j) launder(raw[u][j]);
+    float uu = 0.0f;
+#pragma unroll
+    for (int u = 0; u < K; ++u) {
+        float d[4][MQ];
+        diffs(u, d);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float x = direction<MQ>(d[k], c);
+            uu = fmaf(x, x, uu);
+        }
+    }
+    const float U = sqrtf(block_sum_all<NTH>(uu, lds));
+    const float scale = U > 0.0f ? R / U : 0.0f;
+#pragma unroll
+    for (int j = 0; j < MQ; ++j) c[j] *= scale;
+
+#pragma unroll
+    for (int u = 0; u < K; ++u)
+#pragma unroll
+        for (int j = 0; j < MQ; ++j) launder(raw[u][j]);
+    const float lr = a.lr, mu = a.mu;
+    f32x4 V[K];
+#pragma unroll
+    for (int u = 0; u < K; ++u) {
+        const uint32_t g = threadIdx.x + u * NTH;
+        V[u] = g < nvec ? ld<f32x4, true>(vv, g) : f32x4(0.0f);
+    }
+#pragma unroll
+    for (int u = 0; u < K; ++u) {
+        const uint32_t g = threadIdx.x + u * NTH;
+        float d[4][MQ];
+        diffs(u, d);
+        float t4[4] = {T[u].x, T[u].y, T[u].z, T[u].w};
+        float v4[4] = {V[u].x, V[u].y, V[u].z, V[u].w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float delta = direction<MQ>(d[k], c);
+            v4[k] = fmaf(mu, v4[k], delta);
+            t4[k] = fmaf(-lr, fmaf(mu, v4[k], delta), t4[k]);
+        }
+        if (g < nvec) {
+            const f32x4 tn = {t4[0], t4[1], t4[2], t4[3]};
+            const f32x4 vn = {v4[0], v4[1], v4[2], v4[3]};
+            st<f32x4>(th, g, tn);
+            st<f32x4>(vv, g, vn);
+        }
+    }
+}
+
+// Registers the row kernel keeps per lane: K groups of (packed learners + Theta + v); a
+// 1024-thread workgroup leaves each lane 128 registers, a 256-thread one 512.
+template <typename L, int MQ, int K, int NTH>
+constexpr bool row_kernel_fits()
+{
+    return K * ((int)(sizeof(typename L::raw) / 4) * MQ + 8) <= (NTH > 256 ? 80 : 192);
+}
+
 typedef void (*rda_fn)(const DdlRdaArgs);
 
+template <typename L, int MQ, int K, int NTH>
+rda_fn row_kernel_or_null()
+{
+    if constexpr (row_kernel_fits<L, MQ, K, NTH>())
+        return rda_row_kernel<L, MQ, K, NTH>;
+    else
+        return nullptr;
+}
+
+// The row kernel with the smallest footprint that holds `len` elements, if its registers fit.
+template <typename L, int MQ>
+rda_fn pick_row(uint64_t len, uint32_t& threads)
+{
+    threads = 256;
+    if (len <= 1 * 1024) return row_kernel_or_null<L, MQ, 1, 256>();
+    if (len <= 2 * 1024) return row_kernel_or_null<L, MQ, 2, 256>();
+    if (len <= 4 * 1024) return row_kernel_or_null<L, MQ, 4, 256>();
+    if (len <= 8 * 1024) return row_kernel_or_null<L, MQ, 8, 256>();
+    threads = 1024;
+    if (len <= 16 * 1024) return row_kernel_or_null<L, MQ, 4, 1024>();
+    return nullptr;
+}
+
 template <typename L>
-void pick(int Mq, rda_fn& k1, rda_fn& k2, rda_fn& k3, rda_fn& kg)
+void pick(int Mq, uint64_t group_len, rda_fn& k1, rda_fn& k2, rda_fn& k3, rda_fn& kg, rda_fn& kr,
+          uint32_t& kr_threads)
 {
     switch (Mq) {
 #define DDL_CASE(k)                        \
@@ -387,6 +551,7 @@ void pick(int Mq, rda_fn& k1, rda_fn& k2, rda_fn& k3, rda_fn& kg)
         k2 = rda_dirsq_kernel<L, k>;       \
         k3 = rda_apply_kernel<L, k>;       \
         kg = rda_group_kernel<L, k>;       \
+        kr = pick_row<L, k>(group_len, kr_threads); \
         break;
         DDL_CASE(1) DDL_CASE(2) DDL_CASE(3) DDL_CASE(4) DDL_CASE(5) DDL_CASE(6) DDL_CASE(7)
         DDL_CASE(8) DDL_CASE(9) DDL_CASE(10) DDL_CASE(11) DDL_CASE(12) DDL_CASE(13)
@@ -505,16 +670,19 @@ extern "C" ddl_status ddl_rda_merge_fragment(float* theta, float* v,
     a.partial2 = ws + g.off_partial2;
     a.scale = ws + g.off_scale;
 
-    rda_fn k1 = nullptr, k2 = nullptr, k3 = nullptr, kg = nullptr;
+    rda_fn k1 = nullptr, k2 = nullptr, k3 = nullptr, kg = nullptr, kr = nullptr;
+    uint32_t kr_threads = DDL_BLOCK;
     if (learner_dtype == DDL_F32)
-        pick<LearnerF32>(Mq, k1, k2, k3, kg);
+        pick<LearnerF32>(Mq, a.group_len, k1, k2, k3, kg, kr, kr_threads);
     else
-        pick<LearnerBF16>(Mq, k1, k2, k3, kg);
+        pick<LearnerBF16>(Mq, a.group_len, k1, k2, k3, kg, kr, kr_threads);
     if (!k1) return DDL_ERR_INVALID_ARG;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const dim3 block(DDL_BLOCK);
     const uint32_t groups = (uint32_t)g.groups;
-    if (a.group_len <= kGroupKernelMaxLen && groups >= kGroupKernelMinGroups) {
+    if (kr && vec_ok && n % 4 == 0 && groups >= kGroupKernelMinGroups) {
+        hipLaunchKernelGGL(kr, dim3(groups), dim3(kr_threads), 0, stream, a);
+    } else if (a.group_len <= kGroupKernelMaxLen && groups >= kGroupKernelMinGroups) {
         const long cap = ddl_opt_rda_blocks_per_cu;
         uint32_t lds = cap > 0 ? (uint32_t)(DDL_LDS_PER_CU / cap) & ~511u : 0u;
         if (lds > 60 * 1024) lds = 60 * 1024;  // static LDS of the kernel comes on top

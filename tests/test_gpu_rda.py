@@ -59,7 +59,10 @@ CASES = [(1, 1), (3, 2), (4, 4), (64, 8), (1000, 100), (1001, 7), (4096, 1024), 
          (3 * 16384 + 5, 4),
          # 512 groups or more: the one-kernel shape, one workgroup per group
          (600 * 100, 100), (513 * 7, 7), (700 * 2048 + 5, 2048), (512 * 9000, 9000), (1024, 1),
-         (520 * 65536 // 64, 1024)]
+         (520 * 65536 // 64, 1024),
+         # multiples of four on aligned bases: the register-resident variant, every footprint
+         (600 * 2048, 2048), (512 * 4096, 4096), (512 * 8192, 8192), (520 * 14336, 14336),
+         (512 * 16384 + 16, 16384), (513 * 3000, 3000)]
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
