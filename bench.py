@@ -30,7 +30,8 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # scaled by what the same counter reads for ddl_copy_probe of known size); the runs are
 # summarised under profiles/.  None where no counter run exists for the workload.
 MEASURED_TRAFFIC_BYTES = {
-    "dense_block": 1107038826,  # profiles/ddl_merge_kernel_dense_block.txt
+    "dense_block": 1107038826,   # profiles/ddl_merge_kernel_dense_block.txt
+    "large_dense": 27240225002,  # profiles/ddl_merge_kernel_large_workloads.txt
 }
 
 METRIC = "merged params/sec and achieved HBM GB/s (% of peak), merge+outer Nesterov"
