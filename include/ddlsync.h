@@ -78,8 +78,8 @@ DDL_API const char* ddl_last_error_message(void);
  * token_counts, quorum_mask, w_out: host arrays of M entries.  quorum_mask entries are 0 or 1.
  * Errors: INVALID_ARG (NULL, M < 1, M > DDL_MAX_LEARNERS, mask entry > 1), EMPTY_QUORUM.
  */
-DDL_API ddl_status ddl_compute_weights(const uint64_t* token_counts, const uint8_t* quorum_mask, int M,
-                               double* w_out);
+DDL_API ddl_status ddl_compute_weights(const uint64_t* token_counts, const uint8_t* quorum_mask,
+                                       int M, double* w_out);
 
 /*
  * The paper's own Weight function (Section 3.2): raw weight c_tokens * (c_tokens / c_steps),
@@ -87,8 +87,9 @@ DDL_API ddl_status ddl_compute_weights(const uint64_t* token_counts, const uint8
  * A quorum member with c_steps = 0 and c_tokens = 0 gets weight 0; c_steps = 0 with
  * c_tokens > 0 is INVALID_ARG.  All arrays: host, M entries.
  */
-DDL_API ddl_status ddl_compute_weights_quality(const uint64_t* token_counts, const uint64_t* step_counts,
-                                       const uint8_t* quorum_mask, int M, double* w_out);
+DDL_API ddl_status ddl_compute_weights_quality(const uint64_t* token_counts,
+                                               const uint64_t* step_counts,
+                                               const uint8_t* quorum_mask, int M, double* w_out);
 
 /*
  * One fragment held as ONE flat array: Weight, Merge and OuterOpt as defined at the top of
@@ -106,9 +107,9 @@ DDL_API ddl_status ddl_compute_weights_quality(const uint64_t* token_counts, con
  * Everything the kernel needs travels in its argument block: no device allocation, no copy.
  */
 DDL_API ddl_status ddl_merge_fragment(float* theta, float* v, const void* const* learner_params,
-                              ddl_dtype learner_dtype, const uint64_t* token_counts,
-                              const uint8_t* quorum_mask, int M, size_t n, float lr, float mu,
-                              void* hip_stream);
+                                      ddl_dtype learner_dtype, const uint64_t* token_counts,
+                                      const uint8_t* quorum_mask, int M, size_t n, float lr,
+                                      float mu, void* hip_stream);
 
 /*
  * As ddl_merge_fragment, with normalised weights supplied by the caller instead of token
@@ -116,9 +117,11 @@ DDL_API ddl_status ddl_merge_fragment(float* theta, float* v, const void* const*
  * weights is a host array of M non-negative finite fp64 values with a positive sum; they are
  * divided by their sum in fp64 before use.  w_m == 0 marks a non-contributing learner.
  */
-DDL_API ddl_status ddl_merge_fragment_weighted(float* theta, float* v, const void* const* learner_params,
-                                       ddl_dtype learner_dtype, const double* weights, int M,
-                                       size_t n, float lr, float mu, void* hip_stream);
+DDL_API ddl_status ddl_merge_fragment_weighted(float* theta, float* v,
+                                               const void* const* learner_params,
+                                               ddl_dtype learner_dtype, const double* weights,
+                                               int M, size_t n, float lr, float mu,
+                                               void* hip_stream);
 
 /*
  * As ddl_merge_fragment, and in the same pass also writes the new Theta, rounded to
@@ -159,8 +162,7 @@ DDL_API ddl_status ddl_merge_fragment_bcast(float* theta, float* v, void* theta_
  * NULL, misaligned or too small, and ALIAS if the workspace overlaps any array of the call.
  */
 DDL_API size_t ddl_rda_workspace_bytes(size_t n, size_t group_len, int M);
-DDL_API ddl_status ddl_rda_merge_fragment(float* theta, float* v,
-                                          const void* const* learner_params,
+DDL_API ddl_status ddl_rda_merge_fragment(float* theta, float* v, const void* const* learner_params,
                                           ddl_dtype learner_dtype, const uint64_t* token_counts,
                                           const uint8_t* quorum_mask, int M, size_t n,
                                           size_t group_len, float lr, float mu, void* workspace,
@@ -234,7 +236,8 @@ DDL_API ddl_status ddl_plan_create(const ddl_fragment* frags, int num_frags, ddl
 
 /* Merge the fragments named by syncs[0..count) (distinct fragment indices). A contributing
  * learner whose pointer was NULL at plan creation is INVALID_ARG. */
-DDL_API ddl_status ddl_plan_merge(ddl_plan* plan, const ddl_sync* syncs, int count, void* hip_stream);
+DDL_API ddl_status ddl_plan_merge(ddl_plan* plan, const ddl_sync* syncs, int count,
+                                  void* hip_stream);
 
 /* Frees the plan's device table. The caller must first make sure no enqueued merge of this
  * plan is still running. NULL is a no-op. */
@@ -255,8 +258,8 @@ DDL_API size_t ddl_plan_num_elements(const ddl_plan* plan);
  * Host-only; produces the tensor lists that ddl_plan_create / ddl_merge_batch take.
  * Errors: INVALID_ARG (num_tensors < 0, num_fragments < 1, NULL with num_tensors > 0).
  */
-DDL_API ddl_status ddl_balanced_fragments(const uint64_t* sizes, int num_tensors,
-                                          int num_fragments, int* fragment_of);
+DDL_API ddl_status ddl_balanced_fragments(const uint64_t* sizes, int num_tensors, int num_fragments,
+                                          int* fragment_of);
 
 /*
  * Measurement aid, not part of the method: a plain device-to-device streaming copy of `bytes`
