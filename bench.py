@@ -60,6 +60,8 @@ def parse_args():
                     help="one norm per row of the last dimension, or one per tensor")
     ap.add_argument("--bcast", action="store_true",
                     help="also write the new Theta as bf16 in the same pass (+2 B/param)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step in a HIP graph and time replays (plan API, avg merge)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tiles-per-block", type=int, default=None)
     ap.add_argument("--max-blocks-per-cu", type=int, default=None)
@@ -221,6 +223,30 @@ def main():
             for fi in wl.arrival_order:
                 ddl.merge_batch([calls[fi]])
 
+    if args.graph:
+        if args.api != "plan" or args.merge != "avg":
+            sys.stderr.write("bench.py: --graph needs the plan API and the avg merge\n")
+            sys.exit(2)
+        eager_step = step
+        graphs = []
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for _ in range(replicas):
+                eager_step()                    # warm-up outside capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        for _ in range(replicas):               # one graph per replica, in visiting order
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                eager_step()
+            graphs.append(g)
+        gcount = [0]
+
+        def step():
+            graphs[gcount[0] % replicas].replay()
+            gcount[0] += 1
+
     launches_per_step = len(wl.arrival_order) if args.merge == "avg" else wl.num_segments
     torch.cuda.synchronize()
 
@@ -280,6 +306,7 @@ def main():
             "launches_per_step": launches_per_step,
             "replicas": replicas,
             "bf16_broadcast_copy": bool(args.bcast),
+            "hip_graph": bool(args.graph),
             "tiles_per_block": ddl.get_option("tiles_per_block"),
             "max_blocks_per_cu": ddl.get_option("max_blocks_per_cu"),
         },
