@@ -43,7 +43,8 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="dense_block",
-                    choices=["tiny", "dense_block", "large_dense", "moe", "streaming_model"])
+                    choices=["tiny", "dense_block", "large_dense", "moe", "moe_stacked",
+                             "streaming_model"])
     ap.add_argument("--api", default="plan", choices=["plan", "batch"],
                     help="resident plan (default) or the one-shot ddl_merge_batch per step")
     ap.add_argument("--replicas", type=int, default=None,
@@ -134,6 +135,42 @@ def cpu_baseline(torch, ddl_synth, wl, data, budget_s=20.0):
     }
 
 
+def detail_pass(torch, launch_lists, counter, replicas, reps, extra_bytes_per_step):
+    """After the timed region: ``reps`` more steps with a HIP event before every launch, for
+    the spread over steps (median, best) and, for workloads of several fragments, the time
+    and rate of each fragment (median over the repetitions).  The extra events put small
+    gaps between launches, so these figures are a little below the headline ones."""
+    import statistics
+    per_step, per_launch = [], {}
+    for _ in range(reps):
+        ll = launch_lists[counter[0] % replicas]
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(ll) + 1)]
+        for (_, _, fn), ev in zip(ll, evs):
+            ev.record()
+            fn()
+        evs[-1].record()
+        counter[0] += 1
+        torch.cuda.synchronize()
+        per_step.append(evs[0].elapsed_time(evs[-1]))
+        for k, (fi, nb, _) in enumerate(ll):
+            per_launch.setdefault((k, fi, nb), []).append(evs[k].elapsed_time(evs[k + 1]))
+    step_bytes = sum(nb for _, nb, _ in launch_lists[0]) + extra_bytes_per_step
+    med, best = statistics.median(per_step), min(per_step)
+    out = {
+        "steps": reps,
+        "gpu_ms_per_step_median": med,
+        "gpu_ms_per_step_best": best,
+        "gbps_median": step_bytes / (med * 1e-3) / 1e9,
+        "gbps_best": step_bytes / (best * 1e-3) / 1e9,
+    }
+    if 1 < len(launch_lists[0]) <= 64 and extra_bytes_per_step == 0:
+        out["per_launch"] = [
+            {"order": k, "fragment": fi, "ms": round(statistics.median(ts), 5),
+             "gbps": round(nb / (statistics.median(ts) * 1e-3) / 1e9, 1)}
+            for (k, fi, nb), ts in sorted(per_launch.items())]
+    return out
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -209,19 +246,31 @@ def main():
     data = copies[0][0]
     counter = [0]
 
-    def step():
-        _, plan, calls = copies[counter[0] % replicas]
-        counter[0] += 1
+    def launch_list(copy):
+        """One step over one copy as a list of (fragment index, bytes, callable)."""
+        _, plan, calls = copy
+        out = []
         if plan == "rda":
             for s, f, g, ws in calls:
-                ddl.rda_merge_fragment(s.theta, s.v, s.learners, f.token_counts, f.quorum_mask, g,
-                                       f.lr, f.mu, ws)
+                nb = s.theta.numel() * f.bytes_per_param
+                out.append((f.index, nb, lambda s=s, f=f, g=g, ws=ws: ddl.rda_merge_fragment(
+                    s.theta, s.v, s.learners, f.token_counts, f.quorum_mask, g, f.lr, f.mu, ws)))
         elif plan is not None:
-            for c in calls:
-                plan.merge(c)
+            for fi, c in zip(wl.arrival_order, calls):
+                out.append((fi, wl.fragments[fi].numel * wl.fragments[fi].bytes_per_param,
+                            lambda c=c, plan=plan: plan.merge(c)))
         else:
             for fi in wl.arrival_order:
-                ddl.merge_batch([calls[fi]])
+                out.append((fi, wl.fragments[fi].numel * wl.fragments[fi].bytes_per_param,
+                            lambda fr=calls[fi]: ddl.merge_batch([fr])))
+        return out
+
+    launch_lists = [launch_list(c) for c in copies]
+
+    def step():
+        for _, _, fn in launch_lists[counter[0] % replicas]:
+            fn()
+        counter[0] += 1
 
     if args.graph:
         if args.api != "plan" or args.merge != "avg":
@@ -264,6 +313,9 @@ def main():
     t1 = time.perf_counter()
     wall_ms = (t1 - t0) * 1e3 / steps
     gpu_ms = ev0.elapsed_time(ev1) / steps
+
+    detail = None if args.graph else detail_pass(torch, launch_lists, counter, replicas,
+                                                 min(steps, 40), 2 * wl.numel if args.bcast else 0)
 
     params_per_s = wl.numel / (wall_ms * 1e-3)
     alg_bytes = wl.algorithmic_bytes + (2 * wl.numel if args.bcast else 0)
@@ -319,13 +371,15 @@ def main():
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBPS,
             "traffic": traffic,
-            "kernel": "ddl_merge_kernel" if args.merge == "avg" else "rda sweeps (5 kernels)",
+            "kernel": "ddl_merge_kernel" if args.merge == "avg" else "rda kernel(s) of one tensor",
             "avg_launch_ms": kernel_ms,
             "algorithmic_bytes_per_launch": alg_bytes / launches_per_step,
             "copy_probe_gbps": copy_gbps,
             "frac_of_copy_probe": achieved / copy_gbps,
         },
     }
+    if detail is not None:
+        out["detail"] = detail
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(torch, ddl_synth, wl, data)
     print(json.dumps(out))

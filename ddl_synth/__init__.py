@@ -151,14 +151,21 @@ def large_dense(d_model: int = 4096, d_ff: int = 14336, blocks: int = 4) -> Work
     return Workload("large_dense", [f], [0])
 
 
-def moe(d_model: int = 2048, d_ff: int = 1408, experts: int = 64) -> Workload:
+def moe(d_model: int = 2048, d_ff: int = 1408, experts: int = 64,
+        stacked: bool = False) -> Workload:
     """64 experts, each three separate d_model x d_ff matrices, plus the router matrix: one
     fragment of 193 tensors; M=16 bf16 learners, 11 of 16 present, heavy-tailed lognormal
-    token counters (median 2^20, sigma 1)."""
+    token counters (median 2^20, sigma 1).  ``stacked`` keeps the same parameters in the other
+    common storage layout: the experts' matrices stacked into three [experts, ., .] tensors,
+    4 tensors in all."""
     rng = np.random.default_rng(seed_for("moe", "meta"))
     M = 16
     tensors: List[TensorSpec] = []
-    for e in range(experts):
+    if stacked:
+        tensors += [TensorSpec("experts.W_gate", (experts, d_model, d_ff)),
+                    TensorSpec("experts.W_up", (experts, d_model, d_ff)),
+                    TensorSpec("experts.W_down", (experts, d_ff, d_model))]
+    for e in range(0 if stacked else experts):
         tensors += [TensorSpec(f"expert{e}.W_gate", (d_model, d_ff)),
                     TensorSpec(f"expert{e}.W_up", (d_model, d_ff)),
                     TensorSpec(f"expert{e}.W_down", (d_ff, d_model))]
@@ -166,7 +173,7 @@ def moe(d_model: int = 2048, d_ff: int = 1408, experts: int = 64) -> Workload:
     tokens = [max(1, int(round(x))) for x in rng.lognormal(np.log(2.0 ** 20), 1.0, size=M)]
     f = FragmentSpec(0, tensors, M=M, learner_dtype="bf16", token_counts=tokens,
                      quorum_mask=_choose_quorum(rng, M, 11), drift=[1e-3] * M)
-    return Workload("moe", [f], [0])
+    return Workload("moe_stacked" if stacked else "moe", [f], [0])
 
 
 def streaming_model(d_model: int = 4096, d_ff: int = 14336, blocks: int = 32,
@@ -220,6 +227,7 @@ WORKLOADS = {
     "dense_block": dense_block,
     "large_dense": large_dense,
     "moe": moe,
+    "moe_stacked": lambda: moe(stacked=True),
     "streaming_model": streaming_model,
 }
 
@@ -235,6 +243,8 @@ def reduced(name: str) -> Workload:
         return large_dense(d_model=72, d_ff=251, blocks=4)
     if name == "moe":
         return moe(d_model=64, d_ff=45, experts=64)
+    if name == "moe_stacked":
+        return moe(d_model=64, d_ff=45, experts=64, stacked=True)
     if name == "streaming_model":
         return streaming_model(d_model=48, d_ff=163, blocks=32, vocab=1003)
     raise KeyError(name)

@@ -11,7 +11,7 @@ from ddl_testutil import check_segment, oracle_segment, random_problem
 pytestmark = pytest.mark.gpu
 
 DEV = "cuda:0"
-NAMES = ["tiny", "dense_block", "large_dense", "moe", "streaming_model"]
+NAMES = ["tiny", "dense_block", "large_dense", "moe", "moe_stacked", "streaming_model"]
 
 
 @pytest.fixture(scope="module")

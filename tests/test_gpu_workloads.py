@@ -86,6 +86,10 @@ def test_moe_full_batch_api(ddl):
     _run_full(ddl, ddl_synth.moe(), batch_api=True)
 
 
+def test_moe_stacked_full(ddl):
+    _run_full(ddl, ddl_synth.moe(stacked=True))
+
+
 def test_streaming_model_full(ddl):
     """8.3 B parameters, about 166 GB resident: all six learners' copies, Theta and v."""
     free, _total = torch.cuda.mem_get_info()

@@ -17,6 +17,10 @@ def test_workload_sizes():
     m = ddl_synth.moe()
     assert m.numel == 553_779_200 and m.num_segments == 193
     assert m.fragments[0].Mq == 11 and m.fragments[0].bytes_per_param == 38
+    ms = ddl_synth.WORKLOADS["moe_stacked"]()
+    assert ms.numel == m.numel and ms.num_segments == 4 and ms.name == "moe_stacked"
+    assert ms.fragments[0].token_counts == m.fragments[0].token_counts
+    assert ms.fragments[0].quorum_mask == m.fragments[0].quorum_mask
     s = ddl_synth.streaming_model()
     assert s.numel == 8_309_964_800 and len(s.fragments) == 33
     assert sorted(s.arrival_order) == list(range(33)) and s.arrival_order != list(range(33))
