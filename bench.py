@@ -45,8 +45,9 @@ def parse_args():
     ap.add_argument("--workload", default="dense_block",
                     choices=["tiny", "dense_block", "large_dense", "moe", "moe_stacked",
                              "streaming_model"])
-    ap.add_argument("--api", default="plan", choices=["plan", "batch"],
-                    help="resident plan (default) or the one-shot ddl_merge_batch per step")
+    ap.add_argument("--api", default="plan", choices=["plan", "batch", "tensor"],
+                    help="resident plan (default); the one-shot ddl_merge_batch per fragment; "
+                         "or, for --merge rda, one ddl_rda_merge_fragment call per tensor")
     ap.add_argument("--replicas", type=int, default=None,
                     help="independent copies of the workload visited round-robin, one per step, "
                          "so that no step finds its data in the 256 MB last-level cache "
@@ -219,7 +220,19 @@ def main():
             for s in segs:
                 s.bcast = (torch.empty(s.theta.numel(), dtype=torch.bfloat16, device="cuda:0")
                            if args.bcast else None)
-        if args.merge == "rda":
+        if args.merge == "rda" and args.api == "plan":
+            plan = ddl.Plan([ddl.Fragment([(s.theta, s.v, s.learners) for s in segs], M=f.M,
+                                          learner_dtype=dt[f.learner_dtype])
+                             for f, segs in zip(wl.fragments, data)])
+            plan.set_rda_groups([t.shape[-1] if args.rda_group == "row" else 0
+                                 for f in wl.fragments for t in f.tensors])
+            ws = torch.empty(max(256, plan.rda_workspace_bytes), dtype=torch.uint8,
+                             device="cuda:0")
+            calls = [plan.prepare([(fi, wl.fragments[fi].token_counts,
+                                    wl.fragments[fi].quorum_mask, wl.fragments[fi].lr,
+                                    wl.fragments[fi].mu)]) for fi in wl.arrival_order]
+            copies.append((data, ("rda-plan", plan, ws), calls))
+        elif args.merge == "rda":
             calls = []
             for fi in wl.arrival_order:
                 f = wl.fragments[fi]
@@ -250,7 +263,12 @@ def main():
         """One step over one copy as a list of (fragment index, bytes, callable)."""
         _, plan, calls = copy
         out = []
-        if plan == "rda":
+        if isinstance(plan, tuple):
+            _, rplan, ws = plan
+            for fi, c in zip(wl.arrival_order, calls):
+                out.append((fi, wl.fragments[fi].numel * wl.fragments[fi].bytes_per_param,
+                            lambda c=c, rplan=rplan, ws=ws: rplan.rda_merge(c, ws)))
+        elif plan == "rda":
             for s, f, g, ws in calls:
                 nb = s.theta.numel() * f.bytes_per_param
                 out.append((f.index, nb, lambda s=s, f=f, g=g, ws=ws: ddl.rda_merge_fragment(
@@ -296,7 +314,13 @@ def main():
             graphs[gcount[0] % replicas].replay()
             gcount[0] += 1
 
-    launches_per_step = len(wl.arrival_order) if args.merge == "avg" else wl.num_segments
+    if args.merge == "rda" and args.api == "batch":
+        sys.stderr.write("bench.py: --merge rda goes with --api plan or --api tensor\n")
+        sys.exit(2)
+    if args.merge == "avg" and args.api == "tensor":
+        sys.stderr.write("bench.py: --api tensor is for --merge rda\n")
+        sys.exit(2)
+    launches_per_step = wl.num_segments if args.api == "tensor" else len(wl.arrival_order)
     torch.cuda.synchronize()
 
     # ---- timed region ---------------------------------------------------------------------
@@ -352,7 +376,8 @@ def main():
             "state_dtype": "f32",
             "lr": wl.fragments[0].lr,
             "mu": wl.fragments[0].mu,
-            "api": ("ddl_rda_merge_fragment" if args.merge == "rda" else
+            "api": ("ddl_rda_merge_fragment" if args.api == "tensor" else
+                    "ddl_plan_rda_merge" if args.merge == "rda" else
                     "ddl_plan_merge" if args.api == "plan" else "ddl_merge_batch"),
             "merge": args.merge if args.merge == "avg" else f"rda/{args.rda_group}",
             "launches_per_step": launches_per_step,
@@ -371,7 +396,9 @@ def main():
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBPS,
             "traffic": traffic,
-            "kernel": "ddl_merge_kernel" if args.merge == "avg" else "rda kernel(s) of one tensor",
+            "kernel": ("ddl_merge_kernel" if args.merge == "avg" else
+                       "rda kernel(s) of one tensor" if args.api == "tensor" else
+                       "rda kernel(s) of one fragment"),
             "avg_launch_ms": kernel_ms,
             "algorithmic_bytes_per_launch": alg_bytes / launches_per_step,
             "copy_probe_gbps": copy_gbps,

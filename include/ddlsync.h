@@ -155,9 +155,11 @@ DDL_API ddl_status ddl_merge_fragment_bcast(float* theta, float* v, void* theta_
  *                    may overlap in time
  *   other arguments  as ddl_merge_fragment
  *
- * Enqueues five kernels (three sweeps over the data, two per-group reductions); allocates
- * nothing.  Results are reproducible (no atomics).  HBM traffic is up to three reads of the
- * learners and of Theta; groups that fit the caches are re-read from there.
+ * Allocates nothing.  Many groups of at most 16384 elements on 16-byte-aligned arrays (n and
+ * group_len multiples of four) take one kernel that reads every byte once; other shapes make
+ * three sweeps over the data (one kernel, or five for long or few groups: three sweeps and two
+ * per-group reductions), i.e. up to three reads of the learners and of Theta, partly served
+ * from the caches.  Results are reproducible (no atomics).
  * Errors as ddl_merge_fragment, plus INVALID_ARG for group_len == 0 or a workspace that is
  * NULL, misaligned or too small, and ALIAS if the workspace overlaps any array of the call.
  */
@@ -246,6 +248,37 @@ DDL_API ddl_status ddl_plan_destroy(ddl_plan* plan);
 /* Number of fragments / total elements of a plan (0 for NULL). */
 DDL_API int ddl_plan_num_fragments(const ddl_plan* plan);
 DDL_API size_t ddl_plan_num_elements(const ddl_plan* plan);
+
+/*
+ * Radial-directional averaging (Appendix D.2; see ddl_rda_merge_fragment for the formula and
+ * the readings) through a plan: the fragments named by the syncs are merged tensor by tensor,
+ * each tensor in groups of its own length, and all tensors of a fragment whose groups fit the
+ * one-pass kernel go out in ONE launch per group-length class (up to 1024, 2048, 4096, 8192,
+ * 16384 elements) instead of one launch per tensor.
+ *
+ * ddl_plan_set_rda_groups   group_len[s] for every segment the plan was created with, empty
+ *                           ones included, fragment by fragment in creation order
+ *                           (num_segments = their total); 0 or a value above the segment's n
+ *                           means one group for the whole tensor.  Uploads a small device
+ *                           table (allocates; not for capture); may be called again to change
+ *                           the grouping once no merge of the plan is running.
+ * ddl_plan_rda_workspace_bytes   size of the scratch the merges of this plan need (0 before
+ *                           ddl_plan_set_rda_groups): the largest ddl_rda_workspace_bytes over
+ *                           the plan's tensors.
+ * ddl_plan_rda_merge        as ddl_plan_merge, with the RDA merge.  workspace: device scratch,
+ *                           256-byte aligned, at least ddl_plan_rda_workspace_bytes(plan),
+ *                           overwritten, not shared by calls that may overlap in time.  Only
+ *                           enqueues kernels.  The optional theta_bf16 output of a segment is
+ *                           not written by this call.
+ * Errors as ddl_plan_merge; INVALID_ARG also if the groups were never set, num_segments does
+ * not match the plan, or the workspace is NULL, misaligned or too small; ALIAS if the
+ * workspace overlaps an array of a fragment that is due.  Theta and v are untouched on error.
+ */
+DDL_API ddl_status ddl_plan_set_rda_groups(ddl_plan* plan, const size_t* group_len,
+                                           size_t num_segments);
+DDL_API size_t ddl_plan_rda_workspace_bytes(const ddl_plan* plan);
+DDL_API ddl_status ddl_plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, int count,
+                                      void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Balanced tensor fragmentation (Section 5.1; Appendix C, "Balanced tensor fragmentation"):

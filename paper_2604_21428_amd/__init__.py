@@ -89,6 +89,12 @@ def _load() -> ctypes.CDLL:
                                            u8p, ctypes.c_int, ctypes.c_size_t, ctypes.c_size_t,
                                            ctypes.c_float, ctypes.c_float, ctypes.c_void_p,
                                            ctypes.c_size_t, ctypes.c_void_p]
+    lib.ddl_plan_set_rda_groups.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_size_t),
+                                            ctypes.c_size_t]
+    lib.ddl_plan_rda_workspace_bytes.argtypes = [ctypes.c_void_p]
+    lib.ddl_plan_rda_workspace_bytes.restype = ctypes.c_size_t
+    lib.ddl_plan_rda_merge.argtypes = [ctypes.c_void_p, ctypes.POINTER(_Sync), ctypes.c_int,
+                                       ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     lib.ddl_balanced_fragments.argtypes = [u64p, ctypes.c_int, ctypes.c_int,
                                            ctypes.POINTER(ctypes.c_int)]
     lib.ddl_copy_probe.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
@@ -99,7 +105,7 @@ def _load() -> ctypes.CDLL:
                  "ddl_merge_fragment_weighted", "ddl_merge_batch", "ddl_plan_create",
                  "ddl_plan_merge", "ddl_plan_destroy", "ddl_set_option", "ddl_get_option",
                  "ddl_copy_probe", "ddl_balanced_fragments", "ddl_merge_fragment_bcast",
-                 "ddl_rda_merge_fragment"):
+                 "ddl_rda_merge_fragment", "ddl_plan_set_rda_groups", "ddl_plan_rda_merge"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -368,6 +374,32 @@ class Plan:
             syncs = self.prepare(syncs)
         arr, count, _keep = syncs
         _check(_lib.ddl_plan_merge(self._h, arr, count, _stream_handle(stream)), "ddl_plan_merge")
+
+    def set_rda_groups(self, group_len: Sequence[int]) -> None:
+        """ddl_plan_set_rda_groups: the RDA group length of every segment of the plan, fragment
+        by fragment in creation order (0: one group per tensor)."""
+        n = len(group_len)
+        arr = (ctypes.c_size_t * max(1, n))(*[int(g) for g in group_len])
+        _check(_lib.ddl_plan_set_rda_groups(self._h, arr, n), "ddl_plan_set_rda_groups")
+
+    @property
+    def rda_workspace_bytes(self) -> int:
+        return _lib.ddl_plan_rda_workspace_bytes(self._h)
+
+    def rda_merge(self, syncs, workspace: Optional[torch.Tensor], stream=None) -> None:
+        """ddl_plan_rda_merge: ``merge`` with radial-directional averaging; ``workspace`` is a
+        device byte tensor of at least ``rda_workspace_bytes``."""
+        if not (isinstance(syncs, tuple) and len(syncs) == 3 and isinstance(syncs[1], int)):
+            syncs = self.prepare(syncs)
+        arr, count, _keep = syncs
+        if workspace is None:
+            ptr, nbytes = None, 0
+        else:
+            if not workspace.is_cuda or not workspace.is_contiguous():
+                raise TypeError("workspace must be a contiguous device tensor")
+            ptr, nbytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+        _check(_lib.ddl_plan_rda_merge(self._h, arr, count, ptr, nbytes, _stream_handle(stream)),
+               "ddl_plan_rda_merge")
 
     def destroy(self) -> None:
         if self._h:

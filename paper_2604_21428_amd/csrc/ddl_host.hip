@@ -13,6 +13,9 @@
 
 #include "../../include/ddlsync.h"
 #include "ddl_device.h"
+#include "ddl_host_internal.h"
+
+using namespace ddlh;
 
 static_assert(DDL_MAXL == DDL_MAX_LEARNERS, "device and public learner limits differ");
 
@@ -22,11 +25,15 @@ namespace {
 
 thread_local std::string g_err;
 
-ddl_status runtime_error(hipError_t e, const char* what)
+}  // namespace
+
+ddl_status ddlh::runtime_error(hipError_t e, const char* what)
 {
     g_err = std::string(what) + ": " + hipGetErrorString(e);
     return DDL_ERR_RUNTIME;
 }
+
+namespace {
 
 #define DDL_HIP(call)                                              \
     do {                                                           \
@@ -88,16 +95,11 @@ uint32_t lds_cap_bytes()
 // ------------------------------------------------------------------------------------------
 // weights
 // ------------------------------------------------------------------------------------------
-struct Quorum {
-    int Mq = 0;
-    float w[DDL_MAXL];
-    uint8_t idx[DDL_MAXL];
-    uint32_t present_bits = 0;
-};
+}  // namespace
 
-bool finite_nonneg(float x) { return std::isfinite(x) && x >= 0.0f; }
+bool ddlh::finite_nonneg(float x) { return std::isfinite(x) && x >= 0.0f; }
 
-ddl_status weights_tokens(const uint64_t* t, const uint8_t* q, int M, double* w)
+ddl_status ddlh::weights_tokens(const uint64_t* t, const uint8_t* q, int M, double* w)
 {
     if (!t || !q || !w || M < 1 || M > DDL_MAX_LEARNERS) return DDL_ERR_INVALID_ARG;
     unsigned __int128 S = 0;  // exact: M counters below 2^64
@@ -110,6 +112,8 @@ ddl_status weights_tokens(const uint64_t* t, const uint8_t* q, int M, double* w)
     for (int m = 0; m < M; ++m) w[m] = q[m] ? (double)t[m] / Sd : 0.0;
     return DDL_OK;
 }
+
+namespace {
 
 ddl_status weights_quality(const uint64_t* t, const uint64_t* s, const uint8_t* q, int M, double* w)
 {
@@ -147,8 +151,10 @@ ddl_status weights_given(const double* in, int M, double* w)
     return DDL_OK;
 }
 
+}  // namespace
+
 // Drop learners of weight zero; round the rest once to fp32 for the device.
-void compact(const double* w, int M, Quorum& out)
+void ddlh::compact(const double* w, int M, Quorum& out)
 {
     out.Mq = 0;
     out.present_bits = 0;
@@ -165,6 +171,8 @@ void compact(const double* w, int M, Quorum& out)
         out.idx[j] = 0;
     }
 }
+
+namespace {
 
 // ------------------------------------------------------------------------------------------
 // overlap check: an output range (Theta, v) may overlap nothing; inputs may overlap inputs
@@ -247,32 +255,6 @@ void fill_item(DdlItem& it, const Quorum& q, float lr, float mu, uint32_t seg_be
 // ------------------------------------------------------------------------------------------
 // table of segment descriptors for a set of fragments
 // ------------------------------------------------------------------------------------------
-struct FragInfo {
-    uint32_t seg_begin = 0, num_segs = 0, tiles = 0;
-    uint32_t coarse_begin = 0, coarse_shift = 0;
-    int M = 0;
-    ddl_dtype dt = DDL_F32;
-    uint64_t elems = 0;
-    uint32_t nonnull_bits = 0;  // learners whose pointer is non-NULL in every segment
-};
-
-struct Table {
-    std::vector<DdlSegDesc> segs;  // empty segments are left out
-    std::vector<FragInfo> frags;
-    std::vector<uint32_t> coarse;  // per fragment: descriptor (relative) holding tile i << shift
-    uint64_t elems = 0;
-
-    size_t seg_bytes() const { return segs.size() * sizeof(DdlSegDesc); }
-    size_t bytes() const { return seg_bytes() + coarse.size() * sizeof(uint32_t); }
-    // Device image: the descriptors followed by the coarse index.
-    void copy_to(void* dst) const
-    {
-        std::memcpy(dst, segs.data(), seg_bytes());
-        std::memcpy(static_cast<char*>(dst) + seg_bytes(), coarse.data(),
-                    coarse.size() * sizeof(uint32_t));
-    }
-};
-
 // About four coarse entries per descriptor: a tile's two bracketing entries are then almost
 // always equal.  One extra entry past the end keeps entry i + 1 readable for every tile.
 void build_coarse(Table& T, FragInfo& fi)
@@ -309,6 +291,8 @@ ddl_status build_table(const ddl_fragment* frags, int num_frags, const uint32_t*
                        Table& T)
 {
     T.segs.clear();
+    T.origin.clear();
+    T.given_segs = 0;
     T.coarse.clear();
     T.frags.assign((size_t)num_frags, FragInfo());
     T.elems = 0;
@@ -323,6 +307,7 @@ ddl_status build_table(const ddl_fragment* frags, int num_frags, const uint32_t*
         uint64_t tiles = 0;
         for (int s = 0; s < f.num_segs; ++s) {
             const ddl_segment& g = f.segs[s];
+            const uint32_t position = T.given_segs++;
             if (g.n == 0) continue;
             uint32_t bits = learner_bits[i];
             if (bits == 0xffffffffu) {  // plan creation: every non-NULL learner counts
@@ -339,6 +324,7 @@ ddl_status build_table(const ddl_fragment* frags, int num_frags, const uint32_t*
             DdlSegDesc d;
             fill_desc(d, g.theta, g.v, g.theta_bf16, g.learner_params, f.M, g.n, (uint32_t)tiles);
             T.segs.push_back(d);
+            T.origin.push_back(position);
             tiles += (g.n + DDL_TILE - 1) / DDL_TILE;
             fi.elems += g.n;
         }
@@ -439,12 +425,6 @@ ddl_status merge_flat(float* theta, float* v, void* theta_bf16, const void* cons
 }
 
 }  // namespace
-
-struct ddl_plan {
-    int device = 0;
-    Table table;
-    void* d_table = nullptr;  // descriptors followed by the coarse index
-};
 
 extern "C" {
 
@@ -645,6 +625,7 @@ ddl_status ddl_plan_destroy(ddl_plan* plan)
 {
     if (!plan) return DDL_OK;
     ddl_status st = DDL_OK;
+    if (plan->rda) ddl_rda_plan_free(plan->rda);
     if (plan->d_table) {
         const hipError_t e = hipFree(plan->d_table);
         if (e != hipSuccess) st = runtime_error(e, "hipFree");

@@ -29,10 +29,12 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <new>
 #include <vector>
 
 #include "../../include/ddlsync.h"
 #include "ddl_device.h"
+#include "ddl_host_internal.h"
 #include "ddl_kernel_util.h"
 
 #define DDL_RDA_CHUNK 8192  // elements per workgroup and sweep: 8 groups of four per lane
@@ -392,19 +394,12 @@ __device__ __forceinline__ void launder(u32x4& r)
 // Launch shape (a'), for groups of at most K * 4 * NTH elements on the aligned path: the
 // workgroup loads its whole group ONCE into registers (learner values stay packed as loaded)
 // and makes the three sweeps over the registers.  HBM traffic equals that of direct averaging.
+// th, vv, lp: addresses of the group's first element; nvec: its length in groups of four.
 template <typename L, int MQ, int K, int NTH>
-__global__ void __launch_bounds__(NTH) rda_row_kernel(const DdlRdaArgs a)
+__device__ __forceinline__ void rda_row_body(uint64_t th, uint64_t vv, const uint64_t (&lp)[MQ],
+                                             const float (&w)[MQ], uint32_t nvec, float lr,
+                                             float mu, float* lds /* NTH / 64 + 1 floats */)
 {
-    __shared__ float lds[NTH / 64 + 1];
-    typedef typename L::elem elem;
-    const uint64_t g0 = (uint64_t)blockIdx.x * a.group_len;
-    const uint64_t g1 = a.n - g0 < a.group_len ? a.n : g0 + a.group_len;
-    const uint32_t nvec = (uint32_t)(g1 - g0) / 4;  // the host sends only multiples of four here
-    const uint64_t th = a.theta + g0 * 4, vv = a.v + g0 * 4;
-    uint64_t lp[MQ];
-#pragma unroll
-    for (int j = 0; j < MQ; ++j) lp[j] = a.learner[j] + g0 * sizeof(elem);
-
     typename L::raw raw[K][MQ];
     f32x4 T[K];
 #pragma unroll
@@ -450,8 +445,8 @@ __global__ void __launch_bounds__(NTH) rda_row_kernel(const DdlRdaArgs a)
 #pragma unroll
     for (int j = 0; j < MQ; ++j) {
         const float N = sqrtf(block_sum_all<NTH>(ss[j], lds));
-        R = fmaf(a.w[j], N, R);
-        c[j] = N > 0.0f ? a.w[j] / N : 0.0f;
+        R = fmaf(w[j], N, R);
+        c[j] = N > 0.0f ? w[j] / N : 0.0f;
     }
 
 #pragma unroll
@@ -478,7 +473,6 @@ __global__ void __launch_bounds__(NTH) rda_row_kernel(const DdlRdaArgs a)
     for (int u = 0; u < K; ++u)
 #pragma unroll
         for (int j = 0; j < MQ; ++j) launder(raw[u][j]);
-    const float lr = a.lr, mu = a.mu;
     f32x4 V[K];
 #pragma unroll
     for (int u = 0; u < K; ++u) {
@@ -507,6 +501,82 @@ __global__ void __launch_bounds__(NTH) rda_row_kernel(const DdlRdaArgs a)
     }
 }
 
+// One tensor: workgroup b takes group b.
+template <typename L, int MQ, int K, int NTH>
+__global__ void __launch_bounds__(NTH) rda_row_kernel(const DdlRdaArgs a)
+{
+    __shared__ float lds[NTH / 64 + 1];
+    typedef typename L::elem elem;
+    const uint64_t g0 = (uint64_t)blockIdx.x * a.group_len;
+    const uint64_t g1 = a.n - g0 < a.group_len ? a.n : g0 + a.group_len;
+    const uint32_t nvec = (uint32_t)(g1 - g0) / 4;  // the host sends only multiples of four here
+    uint64_t lp[MQ];
+    float w[MQ];
+#pragma unroll
+    for (int j = 0; j < MQ; ++j) {
+        lp[j] = a.learner[j] + g0 * sizeof(elem);
+        w[j] = a.w[j];
+    }
+    rda_row_body<L, MQ, K, NTH>(a.theta + g0 * 4, a.v + g0 * 4, lp, w, nvec, a.lr, a.mu, lds);
+}
+
+// Many tensors of one fragment in one launch: workgroup b takes row b of the concatenation
+// of the listed tensors' groups.  The tensor is found through a coarse index (entry i names
+// the list entry that holds row i << shift), then the descriptor table gives its addresses;
+// all of that is block-uniform and read with scalar loads from constant address space.
+struct DdlRdaRowRef {
+    uint32_t seg;        // descriptor index in the plan's table
+    uint32_t row_begin;  // first row of this tensor within the launch
+    uint32_t group_len;  // elements per group: a multiple of four
+    uint32_t pad;
+};
+
+struct DdlRdaRowsArgs {
+    const DdlSegDesc* segs;
+    const DdlRdaRowRef* refs;  // first list entry of this launch
+    const uint32_t* coarse;    // first coarse entry of this launch
+    uint32_t coarse_shift;
+    float lr, mu;
+    float w[DDL_MAXL];      // normalised weights of the contributing learners, compacted
+    uint8_t idx[DDL_MAXL];  // learner index of compacted entry j
+};
+
+template <typename L, int MQ, int K, int NTH>
+__global__ void __launch_bounds__(NTH) rda_rows_kernel(const DdlRdaRowsArgs a)
+{
+    __shared__ float lds[NTH / 64 + 1];
+    typedef typename L::elem elem;
+    const uint32_t r = blockIdx.x;
+    const DDL_CONST DdlRdaRowRef* refs =
+        reinterpret_cast<const DDL_CONST DdlRdaRowRef*>(reinterpret_cast<uint64_t>(a.refs));
+    const DDL_CONST uint32_t* coarse =
+        reinterpret_cast<const DDL_CONST uint32_t*>(reinterpret_cast<uint64_t>(a.coarse)) +
+        (r >> a.coarse_shift);
+    uint32_t lo = coarse[0], hi = coarse[1];  // last list entry whose row_begin <= r
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi + 1) >> 1;
+        if (refs[mid].row_begin <= r) lo = mid; else hi = mid - 1;
+    }
+    const DDL_CONST DdlRdaRowRef* ref = refs + lo;
+    const DDL_CONST DdlSegDesc* sp =
+        reinterpret_cast<const DDL_CONST DdlSegDesc*>(reinterpret_cast<uint64_t>(a.segs)) + ref->seg;
+    const uint64_t glen = ref->group_len;
+    const uint64_t n = sp->n;
+    const uint64_t g0 = (uint64_t)(r - ref->row_begin) * glen;
+    const uint64_t g1 = n - g0 < glen ? n : g0 + glen;
+    const uint32_t nvec = uniform((uint32_t)(g1 - g0) / 4);
+    const uint64_t th = uniform(reinterpret_cast<uint64_t>(sp->theta) + g0 * 4);
+    const uint64_t vv = uniform(reinterpret_cast<uint64_t>(sp->v) + g0 * 4);
+    uint64_t lp[MQ];
+    float w[MQ];
+#pragma unroll
+    for (int j = 0; j < MQ; ++j) {
+        lp[j] = uniform(reinterpret_cast<uint64_t>(sp->learner[a.idx[j]]) + g0 * sizeof(elem));
+        w[j] = a.w[j];
+    }
+    rda_row_body<L, MQ, K, NTH>(th, vv, lp, w, nvec, a.lr, a.mu, lds);
+}
+
 // Registers the row kernel keeps per lane: K groups of (packed learners + Theta + v); a
 // 1024-thread workgroup leaves each lane 128 registers, a 256-thread one 512.
 template <typename L, int MQ, int K, int NTH>
@@ -516,48 +586,86 @@ constexpr bool row_kernel_fits()
 }
 
 typedef void (*rda_fn)(const DdlRdaArgs);
+typedef void (*rda_rows_fn)(const DdlRdaRowsArgs);
+
+// The register-resident shapes, smallest first: K groups of four per lane, workgroup size,
+// longest group held.
+struct RowClass {
+    int K;
+    uint32_t threads;
+    uint32_t max_len;
+};
+constexpr int kNumRowClasses = 5;
+constexpr RowClass kRowClass[kNumRowClasses] = {
+    {1, 256, 1024}, {2, 256, 2048}, {4, 256, 4096}, {8, 256, 8192}, {4, 1024, 16384}};
+
+// Smallest class that holds a group of `len` elements; kNumRowClasses if none does.
+int row_class_for(uint64_t len)
+{
+    for (int c = 0; c < kNumRowClasses; ++c)
+        if (len <= kRowClass[c].max_len) return c;
+    return kNumRowClasses;
+}
 
 template <typename L, int MQ, int K, int NTH>
-rda_fn row_kernel_or_null()
+void row_kernels_or_null(rda_fn& one, rda_rows_fn& many)
 {
-    if constexpr (row_kernel_fits<L, MQ, K, NTH>())
-        return rda_row_kernel<L, MQ, K, NTH>;
-    else
-        return nullptr;
+    if constexpr (row_kernel_fits<L, MQ, K, NTH>()) {
+        one = rda_row_kernel<L, MQ, K, NTH>;
+        many = rda_rows_kernel<L, MQ, K, NTH>;
+    } else {
+        one = nullptr;
+        many = nullptr;
+    }
 }
 
-// The row kernel with the smallest footprint that holds `len` elements, if its registers fit.
+// The row kernels of class `cls` (one tensor / many tensors), or null if their registers do
+// not fit for this learner type and count.
 template <typename L, int MQ>
-rda_fn pick_row(uint64_t len, uint32_t& threads)
+void pick_row(int cls, rda_fn& one, rda_rows_fn& many)
 {
-    threads = 256;
-    if (len <= 1 * 1024) return row_kernel_or_null<L, MQ, 1, 256>();
-    if (len <= 2 * 1024) return row_kernel_or_null<L, MQ, 2, 256>();
-    if (len <= 4 * 1024) return row_kernel_or_null<L, MQ, 4, 256>();
-    if (len <= 8 * 1024) return row_kernel_or_null<L, MQ, 8, 256>();
-    threads = 1024;
-    if (len <= 16 * 1024) return row_kernel_or_null<L, MQ, 4, 1024>();
-    return nullptr;
+    one = nullptr;
+    many = nullptr;
+    switch (cls) {
+        case 0: row_kernels_or_null<L, MQ, 1, 256>(one, many); break;
+        case 1: row_kernels_or_null<L, MQ, 2, 256>(one, many); break;
+        case 2: row_kernels_or_null<L, MQ, 4, 256>(one, many); break;
+        case 3: row_kernels_or_null<L, MQ, 8, 256>(one, many); break;
+        case 4: row_kernels_or_null<L, MQ, 4, 1024>(one, many); break;
+        default: break;
+    }
 }
+
+struct Kernels {
+    rda_fn sumsq = nullptr, dirsq = nullptr, apply = nullptr, group = nullptr, row = nullptr;
+    rda_rows_fn rows = nullptr;
+};
 
 template <typename L>
-void pick(int Mq, uint64_t group_len, rda_fn& k1, rda_fn& k2, rda_fn& k3, rda_fn& kg, rda_fn& kr,
-          uint32_t& kr_threads)
+void pick(int Mq, int cls, Kernels& k)
 {
     switch (Mq) {
-#define DDL_CASE(k)                        \
-    case k:                                \
-        k1 = rda_sumsq_kernel<L, k>;       \
-        k2 = rda_dirsq_kernel<L, k>;       \
-        k3 = rda_apply_kernel<L, k>;       \
-        kg = rda_group_kernel<L, k>;       \
-        kr = pick_row<L, k>(group_len, kr_threads); \
+#define DDL_CASE(q)                              \
+    case q:                                      \
+        k.sumsq = rda_sumsq_kernel<L, q>;        \
+        k.dirsq = rda_dirsq_kernel<L, q>;        \
+        k.apply = rda_apply_kernel<L, q>;        \
+        k.group = rda_group_kernel<L, q>;        \
+        pick_row<L, q>(cls, k.row, k.rows);      \
         break;
         DDL_CASE(1) DDL_CASE(2) DDL_CASE(3) DDL_CASE(4) DDL_CASE(5) DDL_CASE(6) DDL_CASE(7)
         DDL_CASE(8) DDL_CASE(9) DDL_CASE(10) DDL_CASE(11) DDL_CASE(12) DDL_CASE(13)
         DDL_CASE(14) DDL_CASE(15) DDL_CASE(16)
 #undef DDL_CASE
     }
+}
+
+void pick(ddl_dtype dt, int Mq, int cls, Kernels& k)
+{
+    if (dt == DDL_F32)
+        pick<LearnerF32>(Mq, cls, k);
+    else
+        pick<LearnerBF16>(Mq, cls, k);
 }
 
 struct Geometry {
@@ -597,6 +705,45 @@ constexpr uint32_t kGroupKernelMinGroups = 512;
 
 inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
+// Enqueues the RDA merge of ONE tensor.  `a` holds the tensor, the compacted learners and
+// weights, n, group_len (already clamped to n), vec_ok, lr and mu; the workspace fields are
+// filled in here.  g = geometry(n, group_len, Mq).
+ddl_status launch_one(ddl_dtype dt, int Mq, DdlRdaArgs& a, const Geometry& g, void* workspace,
+                      hipStream_t stream)
+{
+    a.chunks_per_group = (uint32_t)g.chunks_per_group;
+    const uint64_t ws = (uint64_t)(uintptr_t)workspace;
+    a.partial1 = ws + g.off_partial1;
+    a.coef = ws + g.off_coef;
+    a.mean_norm = ws + g.off_mean;
+    a.partial2 = ws + g.off_partial2;
+    a.scale = ws + g.off_scale;
+
+    const int cls = row_class_for(a.group_len);
+    Kernels k;
+    pick(dt, Mq, cls, k);
+    if (!k.sumsq) return DDL_ERR_INVALID_ARG;
+    const dim3 block(DDL_BLOCK);
+    const uint32_t groups = (uint32_t)g.groups;
+    if (k.row && a.vec_ok && a.n % 4 == 0 && groups >= kGroupKernelMinGroups) {
+        hipLaunchKernelGGL(k.row, dim3(groups), dim3(kRowClass[cls].threads), 0, stream, a);
+    } else if (a.group_len <= kGroupKernelMaxLen && groups >= kGroupKernelMinGroups) {
+        const long cap = ddl_opt_rda_blocks_per_cu;
+        uint32_t lds = cap > 0 ? (uint32_t)(DDL_LDS_PER_CU / cap) & ~511u : 0u;
+        if (lds > 60 * 1024) lds = 60 * 1024;  // static LDS of the kernel comes on top
+        hipLaunchKernelGGL(k.group, dim3(groups), block, lds, stream, a);
+    } else {
+        const dim3 grid((uint32_t)g.chunks), rgrid(groups);
+        hipLaunchKernelGGL(k.sumsq, grid, block, 0, stream, a);
+        hipLaunchKernelGGL(rda_norms_kernel, rgrid, block, 0, stream, a, Mq);
+        hipLaunchKernelGGL(k.dirsq, grid, block, 0, stream, a);
+        hipLaunchKernelGGL(rda_scale_kernel, rgrid, block, 0, stream, a);
+        hipLaunchKernelGGL(k.apply, grid, block, 0, stream, a);
+    }
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? DDL_OK : ddlh::runtime_error(e, "RDA kernel launch");
+}
+
 }  // namespace
 
 extern "C" size_t ddl_rda_workspace_bytes(size_t n, size_t group_len, int M)
@@ -617,7 +764,7 @@ extern "C" ddl_status ddl_rda_merge_fragment(float* theta, float* v,
     ddl_status st = ddl_compute_weights(token_counts, quorum_mask, M, w);
     if (st != DDL_OK) return st;
     if (learner_dtype != DDL_F32 && learner_dtype != DDL_BF16) return DDL_ERR_INVALID_ARG;
-    if (!std::isfinite(lr) || lr < 0.0f || !std::isfinite(mu) || mu < 0.0f) return DDL_ERR_INVALID_ARG;
+    if (!ddlh::finite_nonneg(lr) || !ddlh::finite_nonneg(mu)) return DDL_ERR_INVALID_ARG;
     if (group_len == 0) return DDL_ERR_INVALID_ARG;
     if (n == 0) return DDL_OK;
     if (!theta || !v || !learner_params || !aligned(theta, 4) || !aligned(v, 4))
@@ -659,41 +806,253 @@ extern "C" ddl_status ddl_rda_merge_fragment(float* theta, float* v,
     a.v = (uint64_t)(uintptr_t)v;
     a.n = n;
     a.group_len = std::min<uint64_t>(group_len, n);
-    a.chunks_per_group = (uint32_t)g.chunks_per_group;
     a.vec_ok = vec_ok ? 1u : 0u;
     a.lr = lr;
     a.mu = mu;
-    const uint64_t ws = (uint64_t)(uintptr_t)workspace;
-    a.partial1 = ws + g.off_partial1;
-    a.coef = ws + g.off_coef;
-    a.mean_norm = ws + g.off_mean;
-    a.partial2 = ws + g.off_partial2;
-    a.scale = ws + g.off_scale;
+    return launch_one(learner_dtype, Mq, a, g, workspace, static_cast<hipStream_t>(hip_stream));
+}
 
-    rda_fn k1 = nullptr, k2 = nullptr, k3 = nullptr, kg = nullptr, kr = nullptr;
-    uint32_t kr_threads = DDL_BLOCK;
-    if (learner_dtype == DDL_F32)
-        pick<LearnerF32>(Mq, a.group_len, k1, k2, k3, kg, kr, kr_threads);
-    else
-        pick<LearnerBF16>(Mq, a.group_len, k1, k2, k3, kg, kr, kr_threads);
-    if (!k1) return DDL_ERR_INVALID_ARG;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const dim3 block(DDL_BLOCK);
-    const uint32_t groups = (uint32_t)g.groups;
-    if (kr && vec_ok && n % 4 == 0 && groups >= kGroupKernelMinGroups) {
-        hipLaunchKernelGGL(kr, dim3(groups), dim3(kr_threads), 0, stream, a);
-    } else if (a.group_len <= kGroupKernelMaxLen && groups >= kGroupKernelMinGroups) {
-        const long cap = ddl_opt_rda_blocks_per_cu;
-        uint32_t lds = cap > 0 ? (uint32_t)(DDL_LDS_PER_CU / cap) & ~511u : 0u;
-        if (lds > 60 * 1024) lds = 60 * 1024;  // static LDS of the kernel comes on top
-        hipLaunchKernelGGL(kg, dim3(groups), block, lds, stream, a);
-    } else {
-        const dim3 grid((uint32_t)g.chunks), rgrid(groups);
-        hipLaunchKernelGGL(k1, grid, block, 0, stream, a);
-        hipLaunchKernelGGL(rda_norms_kernel, rgrid, block, 0, stream, a, Mq);
-        hipLaunchKernelGGL(k2, grid, block, 0, stream, a);
-        hipLaunchKernelGGL(rda_scale_kernel, rgrid, block, 0, stream, a);
-        hipLaunchKernelGGL(k3, grid, block, 0, stream, a);
+// ------------------------------------------------------------------------------------------
+// RDA through a plan: all tensors of a fragment whose groups fit the register-resident row
+// kernels go out in one launch per row class; the rest take the one-tensor path above.
+// ------------------------------------------------------------------------------------------
+struct DdlRdaPlan {
+    struct Class {
+        uint32_t ref_begin = 0, num_refs = 0, rows = 0, coarse_begin = 0, coarse_shift = 0;
+    };
+    struct Frag {
+        Class cls[kNumRowClasses];
+        std::vector<uint32_t> other;  // descriptors that always take the one-tensor path
+    };
+    std::vector<uint64_t> group_len;  // per descriptor, clamped to its n
+    std::vector<Frag> frags;
+    std::vector<DdlRdaRowRef> refs;
+    std::vector<uint32_t> coarse;
+    void* d_image = nullptr;  // refs followed by the coarse index
+    size_t workspace_bytes = 0;
+};
+
+void ddl_rda_plan_free(DdlRdaPlan* p)
+{
+    if (!p) return;
+    if (p->d_image) (void)hipFree(p->d_image);
+    delete p;
+}
+
+namespace {
+
+// Can descriptor d with groups of g elements go through a row kernel, whatever the quorum?
+bool row_eligible(const DdlSegDesc& d, int M, uint64_t g)
+{
+    const uint32_t all = (1u << M) - 1u;
+    return g % 4 == 0 && d.n % 4 == 0 && row_class_for(g) < kNumRowClasses && d.base_aligned &&
+           (all & ~(uint32_t)d.learner_aligned) == 0;
+}
+
+struct RdaWork {
+    uint32_t frag;
+    ddlh::Quorum q;
+    float lr, mu;
+};
+
+}  // namespace
+
+extern "C" ddl_status ddl_plan_set_rda_groups(ddl_plan* plan, const size_t* group_len,
+                                              size_t num_segments)
+{
+    if (!plan || num_segments != plan->table.given_segs || (num_segments > 0 && !group_len))
+        return DDL_ERR_INVALID_ARG;
+    const ddlh::Table& T = plan->table;
+    DdlRdaPlan* R = new (std::nothrow) DdlRdaPlan();
+    if (!R) return DDL_ERR_RUNTIME;
+    R->group_len.resize(T.segs.size());
+    R->frags.resize(T.frags.size());
+    for (size_t f = 0; f < T.frags.size(); ++f) {
+        const ddlh::FragInfo& fi = T.frags[f];
+        DdlRdaPlan::Frag& rf = R->frags[f];
+        std::vector<uint32_t> members[kNumRowClasses];
+        for (uint32_t d = fi.seg_begin; d < fi.seg_begin + fi.num_segs; ++d) {
+            const DdlSegDesc& sd = T.segs[d];
+            uint64_t g = group_len[T.origin[d]];
+            if (g == 0 || g > sd.n) g = sd.n;
+            R->group_len[d] = g;
+            Geometry geo;
+            if (!geometry(sd.n, g, fi.M, geo)) {
+                delete R;
+                return DDL_ERR_INVALID_ARG;
+            }
+            R->workspace_bytes = std::max(R->workspace_bytes, geo.bytes);
+            if (row_eligible(sd, fi.M, g))
+                members[row_class_for(g)].push_back(d);
+            else
+                rf.other.push_back(d);
+        }
+        for (int c = 0; c < kNumRowClasses; ++c) {
+            DdlRdaPlan::Class& k = rf.cls[c];
+            k.ref_begin = (uint32_t)R->refs.size();
+            k.coarse_begin = (uint32_t)R->coarse.size();
+            uint64_t rows = 0;
+            for (uint32_t d : members[c]) {
+                const uint64_t g = R->group_len[d];
+                if (rows > 0x7fffffffull) break;
+                R->refs.push_back({d, (uint32_t)rows, (uint32_t)g, 0u});
+                rows += (T.segs[d].n + g - 1) / g;
+            }
+            if (rows > 0x7fffffffull) {
+                delete R;
+                return DDL_ERR_INVALID_ARG;
+            }
+            k.num_refs = (uint32_t)members[c].size();
+            k.rows = (uint32_t)rows;
+            if (k.num_refs == 0) continue;
+            // About four coarse entries per tensor, and one past the end so that entry i + 1
+            // is readable for every row.
+            const uint64_t target = 4ull * k.num_refs;
+            while (k.coarse_shift < 31 && (rows >> (k.coarse_shift + 1)) >= target)
+                ++k.coarse_shift;
+            const uint32_t entries = (k.rows >> k.coarse_shift) + 2;
+            const DdlRdaRowRef* refs = R->refs.data() + k.ref_begin;
+            uint32_t s = 0;
+            for (uint32_t i = 0; i < entries; ++i) {
+                const uint64_t row = (uint64_t)i << k.coarse_shift;
+                while (s + 1 < k.num_refs && refs[s + 1].row_begin <= row) ++s;
+                R->coarse.push_back(row < rows ? s : k.num_refs - 1);
+            }
+        }
     }
-    return hipGetLastError() == hipSuccess ? DDL_OK : DDL_ERR_RUNTIME;
+    const size_t ref_bytes = R->refs.size() * sizeof(DdlRdaRowRef);
+    const size_t bytes = ref_bytes + R->coarse.size() * sizeof(uint32_t);
+    if (bytes > 0) {
+        std::vector<char> image(bytes);
+        std::memcpy(image.data(), R->refs.data(), ref_bytes);
+        std::memcpy(image.data() + ref_bytes, R->coarse.data(), bytes - ref_bytes);
+        hipError_t e = hipMalloc(&R->d_image, bytes);
+        if (e == hipSuccess) e = hipMemcpy(R->d_image, image.data(), bytes, hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            ddl_rda_plan_free(R);
+            return ddlh::runtime_error(e, "RDA plan upload");
+        }
+    }
+    if (plan->rda) ddl_rda_plan_free(plan->rda);
+    plan->rda = R;
+    return DDL_OK;
+}
+
+extern "C" size_t ddl_plan_rda_workspace_bytes(const ddl_plan* plan)
+{
+    return plan && plan->rda ? plan->rda->workspace_bytes : 0;
+}
+
+extern "C" ddl_status ddl_plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, int count,
+                                         void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!plan || !plan->rda || count < 0 || (count > 0 && !syncs)) return DDL_ERR_INVALID_ARG;
+    if (count == 0) return DDL_OK;
+    const ddlh::Table& T = plan->table;
+    const DdlRdaPlan& R = *plan->rda;
+    if (R.workspace_bytes > 0 &&
+        (!workspace || !aligned(workspace, 256) || workspace_bytes < R.workspace_bytes))
+        return DDL_ERR_INVALID_ARG;
+    const uintptr_t ws_lo = (uintptr_t)workspace, ws_hi = ws_lo + R.workspace_bytes;
+    auto hits_workspace = [&](const void* p, uint64_t bytes) {
+        const uintptr_t lo = (uintptr_t)p;
+        return p && lo < ws_hi && ws_lo < lo + bytes;
+    };
+
+    // Everything is validated before anything is enqueued.
+    std::vector<RdaWork> work;
+    work.reserve((size_t)count);
+    std::vector<char> seen(T.frags.size(), 0);
+    for (int i = 0; i < count; ++i) {
+        const ddl_sync& s = syncs[i];
+        if (s.fragment < 0 || (size_t)s.fragment >= T.frags.size()) return DDL_ERR_INVALID_ARG;
+        if (seen[(size_t)s.fragment]) return DDL_ERR_ALIAS;
+        seen[(size_t)s.fragment] = 1;
+        if (!ddlh::finite_nonneg(s.lr) || !ddlh::finite_nonneg(s.mu)) return DDL_ERR_INVALID_ARG;
+        const ddlh::FragInfo& f = T.frags[(size_t)s.fragment];
+        double w[DDL_MAXL];
+        const ddl_status st = ddlh::weights_tokens(s.token_counts, s.quorum_mask, f.M, w);
+        if (st != DDL_OK) return st;
+        RdaWork wk;
+        wk.frag = (uint32_t)s.fragment;
+        wk.lr = s.lr;
+        wk.mu = s.mu;
+        ddlh::compact(w, f.M, wk.q);
+        if (f.num_segs > 0 && (wk.q.present_bits & ~f.nonnull_bits)) return DDL_ERR_INVALID_ARG;
+        const size_t b = f.dt == DDL_BF16 ? 2 : 4;
+        for (uint32_t d = f.seg_begin; d < f.seg_begin + f.num_segs; ++d) {
+            const DdlSegDesc& sd = T.segs[d];
+            bool hit = hits_workspace(sd.theta, 4 * sd.n) || hits_workspace(sd.v, 4 * sd.n);
+            for (int j = 0; j < wk.q.Mq; ++j)
+                hit = hit || hits_workspace(sd.learner[wk.q.idx[j]], b * sd.n);
+            if (hit) return DDL_ERR_ALIAS;
+        }
+        work.push_back(wk);
+    }
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const DdlSegDesc* d_segs = static_cast<const DdlSegDesc*>(plan->d_table);
+    const DdlRdaRowRef* d_refs = static_cast<const DdlRdaRowRef*>(R.d_image);
+    const uint32_t* d_coarse = reinterpret_cast<const uint32_t*>(
+        static_cast<const char*>(R.d_image) + R.refs.size() * sizeof(DdlRdaRowRef));
+
+    // One tensor through the one-tensor path.
+    auto one_tensor = [&](const ddlh::FragInfo& f, const RdaWork& wk, uint32_t d) -> ddl_status {
+        const DdlSegDesc& sd = T.segs[d];
+        DdlRdaArgs a;
+        std::memset(&a, 0, sizeof a);
+        a.theta = (uint64_t)(uintptr_t)sd.theta;
+        a.v = (uint64_t)(uintptr_t)sd.v;
+        a.n = sd.n;
+        a.group_len = R.group_len[d];
+        a.lr = wk.lr;
+        a.mu = wk.mu;
+        bool vec_ok = aligned(sd.theta, 16) && aligned(sd.v, 16) && a.group_len % 4 == 0;
+        for (int j = 0; j < wk.q.Mq; ++j) {
+            const void* p = sd.learner[wk.q.idx[j]];
+            vec_ok = vec_ok && aligned(p, 16);
+            a.learner[j] = (uint64_t)(uintptr_t)p;
+            a.w[j] = wk.q.w[j];
+        }
+        a.vec_ok = vec_ok ? 1u : 0u;
+        Geometry g;
+        if (!geometry(sd.n, a.group_len, wk.q.Mq, g)) return DDL_ERR_INVALID_ARG;
+        return launch_one(f.dt, wk.q.Mq, a, g, workspace, stream);
+    };
+
+    for (const RdaWork& wk : work) {
+        const ddlh::FragInfo& f = T.frags[wk.frag];
+        const DdlRdaPlan::Frag& rf = R.frags[wk.frag];
+        for (int c = 0; c < kNumRowClasses; ++c) {
+            const DdlRdaPlan::Class& k = rf.cls[c];
+            if (k.num_refs == 0) continue;
+            Kernels fn;
+            pick(f.dt, wk.q.Mq, c, fn);
+            if (fn.rows) {
+                DdlRdaRowsArgs a;
+                std::memset(&a, 0, sizeof a);
+                a.segs = d_segs;
+                a.refs = d_refs + k.ref_begin;
+                a.coarse = d_coarse + k.coarse_begin;
+                a.coarse_shift = k.coarse_shift;
+                a.lr = wk.lr;
+                a.mu = wk.mu;
+                std::memcpy(a.w, wk.q.w, sizeof a.w);
+                std::memcpy(a.idx, wk.q.idx, sizeof a.idx);
+                hipLaunchKernelGGL(fn.rows, dim3(k.rows), dim3(kRowClass[c].threads), 0, stream, a);
+                const hipError_t e = hipGetLastError();
+                if (e != hipSuccess) return ddlh::runtime_error(e, "RDA rows kernel launch");
+            } else {  // this many learners do not fit the registers of this class
+                for (uint32_t r = 0; r < k.num_refs; ++r) {
+                    const ddl_status st = one_tensor(f, wk, R.refs[k.ref_begin + r].seg);
+                    if (st != DDL_OK) return st;
+                }
+            }
+        }
+        for (uint32_t d : rf.other) {
+            const ddl_status st = one_tensor(f, wk, d);
+            if (st != DDL_OK) return st;
+        }
+    }
+    return DDL_OK;
 }
