@@ -37,6 +37,9 @@
 #include "ddl_host_internal.h"
 #include "ddl_kernel_util.h"
 
+#ifndef DDL_RDA_V_EARLY
+#define DDL_RDA_V_EARLY 0  // 1: the row kernels load v with the first sweep instead of the last
+#endif
 #define DDL_RDA_CHUNK 8192  // elements per workgroup and sweep: 8 groups of four per lane
 
 struct DdlRdaArgs {
@@ -402,9 +405,15 @@ __device__ __forceinline__ void rda_row_body(uint64_t th, uint64_t vv, const uin
 {
     typename L::raw raw[K][MQ];
     f32x4 T[K];
+#if DDL_RDA_V_EARLY
+    f32x4 V[K];
+#endif
 #pragma unroll
     for (int u = 0; u < K; ++u) {
         const uint32_t g = threadIdx.x + u * NTH;
+#if DDL_RDA_V_EARLY
+        V[u] = g < nvec ? ld<f32x4, true>(vv, g) : f32x4(0.0f);
+#endif
         if (g < nvec) {
 #pragma unroll
             for (int j = 0; j < MQ; ++j) raw[u][j] = ld<typename L::raw, true>(lp[j], g);
@@ -473,12 +482,14 @@ __device__ __forceinline__ void rda_row_body(uint64_t th, uint64_t vv, const uin
     for (int u = 0; u < K; ++u)
 #pragma unroll
         for (int j = 0; j < MQ; ++j) launder(raw[u][j]);
+#if !DDL_RDA_V_EARLY
     f32x4 V[K];
 #pragma unroll
     for (int u = 0; u < K; ++u) {
         const uint32_t g = threadIdx.x + u * NTH;
         V[u] = g < nvec ? ld<f32x4, true>(vv, g) : f32x4(0.0f);
     }
+#endif
 #pragma unroll
     for (int u = 0; u < K; ++u) {
         const uint32_t g = threadIdx.x + u * NTH;
@@ -577,27 +588,34 @@ __global__ void __launch_bounds__(NTH) rda_rows_kernel(const DdlRdaRowsArgs a)
     rda_row_body<L, MQ, K, NTH>(th, vv, lp, w, nvec, a.lr, a.mu, lds);
 }
 
-// Registers the row kernel keeps per lane: K groups of (packed learners + Theta + v); a
-// 1024-thread workgroup leaves each lane 128 registers, a 256-thread one 512.
+// Registers the row kernel keeps per lane: K groups of (packed learners + Theta + v), plus
+// about six per learner while a sweep runs (the four differences of a group, a sum, a
+// coefficient); a 1024-thread workgroup leaves each lane 128 registers, smaller ones 256 and
+// more.
 template <typename L, int MQ, int K, int NTH>
 constexpr bool row_kernel_fits()
 {
-    return K * ((int)(sizeof(typename L::raw) / 4) * MQ + 8) <= (NTH > 256 ? 80 : 192);
+    const int data = K * ((int)(sizeof(typename L::raw) / 4) * MQ + 8);
+    return NTH > 512 ? data + 6 * MQ <= 116 : data <= 192;
 }
 
 typedef void (*rda_fn)(const DdlRdaArgs);
 typedef void (*rda_rows_fn)(const DdlRdaRowsArgs);
 
-// The register-resident shapes, smallest first: K groups of four per lane, workgroup size,
-// longest group held.
+// The register-resident shapes, smallest first: X(class, K groups of four per lane, workgroup
+// size); a class holds groups of up to K * 4 * threads elements.
+#ifndef DDL_RDA_ROW_CLASSES
+#define DDL_RDA_ROW_CLASSES(X) X(0, 1, 256) X(1, 2, 256) X(2, 4, 256) X(3, 8, 256) X(4, 4, 1024)
+#endif
 struct RowClass {
     int K;
     uint32_t threads;
     uint32_t max_len;
 };
-constexpr int kNumRowClasses = 5;
-constexpr RowClass kRowClass[kNumRowClasses] = {
-    {1, 256, 1024}, {2, 256, 2048}, {4, 256, 4096}, {8, 256, 8192}, {4, 1024, 16384}};
+#define DDL_X(c, k, nth) {k, nth, k * 4 * nth},
+constexpr RowClass kRowClass[] = {DDL_RDA_ROW_CLASSES(DDL_X)};
+#undef DDL_X
+constexpr int kNumRowClasses = (int)(sizeof(kRowClass) / sizeof(kRowClass[0]));
 
 // Smallest class that holds a group of `len` elements; kNumRowClasses if none does.
 int row_class_for(uint64_t len)
@@ -627,11 +645,10 @@ void pick_row(int cls, rda_fn& one, rda_rows_fn& many)
     one = nullptr;
     many = nullptr;
     switch (cls) {
-        case 0: row_kernels_or_null<L, MQ, 1, 256>(one, many); break;
-        case 1: row_kernels_or_null<L, MQ, 2, 256>(one, many); break;
-        case 2: row_kernels_or_null<L, MQ, 4, 256>(one, many); break;
-        case 3: row_kernels_or_null<L, MQ, 8, 256>(one, many); break;
-        case 4: row_kernels_or_null<L, MQ, 4, 1024>(one, many); break;
+#define DDL_X(c, k, nth) \
+    case c: row_kernels_or_null<L, MQ, k, nth>(one, many); break;
+        DDL_RDA_ROW_CLASSES(DDL_X)
+#undef DDL_X
         default: break;
     }
 }
@@ -705,6 +722,15 @@ constexpr uint32_t kGroupKernelMinGroups = 512;
 
 inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
+// Unused dynamic LDS that caps the resident workgroups per compute unit (option
+// rda_blocks_per_cu; 0: no cap).
+uint32_t row_lds_cap()
+{
+    const long cap = ddl_opt_rda_blocks_per_cu;
+    uint32_t lds = cap > 0 ? (uint32_t)(DDL_LDS_PER_CU / cap) & ~511u : 0u;
+    return lds > 60 * 1024 ? 60 * 1024 : lds;  // static LDS of the kernel comes on top
+}
+
 // Enqueues the RDA merge of ONE tensor.  `a` holds the tensor, the compacted learners and
 // weights, n, group_len (already clamped to n), vec_ok, lr and mu; the workspace fields are
 // filled in here.  g = geometry(n, group_len, Mq).
@@ -726,12 +752,10 @@ ddl_status launch_one(ddl_dtype dt, int Mq, DdlRdaArgs& a, const Geometry& g, vo
     const dim3 block(DDL_BLOCK);
     const uint32_t groups = (uint32_t)g.groups;
     if (k.row && a.vec_ok && a.n % 4 == 0 && groups >= kGroupKernelMinGroups) {
-        hipLaunchKernelGGL(k.row, dim3(groups), dim3(kRowClass[cls].threads), 0, stream, a);
+        hipLaunchKernelGGL(k.row, dim3(groups), dim3(kRowClass[cls].threads), row_lds_cap(), stream,
+                           a);
     } else if (a.group_len <= kGroupKernelMaxLen && groups >= kGroupKernelMinGroups) {
-        const long cap = ddl_opt_rda_blocks_per_cu;
-        uint32_t lds = cap > 0 ? (uint32_t)(DDL_LDS_PER_CU / cap) & ~511u : 0u;
-        if (lds > 60 * 1024) lds = 60 * 1024;  // static LDS of the kernel comes on top
-        hipLaunchKernelGGL(k.group, dim3(groups), block, lds, stream, a);
+        hipLaunchKernelGGL(k.group, dim3(groups), block, row_lds_cap(), stream, a);
     } else {
         const dim3 grid((uint32_t)g.chunks), rgrid(groups);
         hipLaunchKernelGGL(k.sumsq, grid, block, 0, stream, a);
@@ -1039,7 +1063,8 @@ extern "C" ddl_status ddl_plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, 
                 a.mu = wk.mu;
                 std::memcpy(a.w, wk.q.w, sizeof a.w);
                 std::memcpy(a.idx, wk.q.idx, sizeof a.idx);
-                hipLaunchKernelGGL(fn.rows, dim3(k.rows), dim3(kRowClass[c].threads), 0, stream, a);
+                hipLaunchKernelGGL(fn.rows, dim3(k.rows), dim3(kRowClass[c].threads), row_lds_cap(),
+                                   stream, a);
                 const hipError_t e = hipGetLastError();
                 if (e != hipSuccess) return ddlh::runtime_error(e, "RDA rows kernel launch");
             } else {  // this many learners do not fit the registers of this class
