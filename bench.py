@@ -33,6 +33,10 @@ MEASURED_TRAFFIC_BYTES = {
     "dense_block": 1107038826,   # profiles/ddl_merge_kernel_dense_block.txt
     "large_dense": 27240225002,  # profiles/ddl_merge_kernel_large_workloads.txt
 }
+# The same for one sync with the RDA merge through the plan, one norm per row.
+MEASURED_TRAFFIC_BYTES_RDA_ROWS = {
+    "dense_block": 1107347345,   # profiles/ddl_rda_kernels.txt
+}
 
 METRIC = "merged params/sec and achieved HBM GB/s (% of peak), merge+outer Nesterov"
 
@@ -349,8 +353,14 @@ def main():
     kernel_ms = gpu_ms / launches_per_step
     achieved = alg_bytes / launches_per_step / (kernel_ms * 1e-3) / 1e9
     copy_gbps = time_copy_probe(ddl, torch)
-    traffic = (None if args.bcast or args.merge != "avg"
-               else MEASURED_TRAFFIC_BYTES.get(wl.name))
+    if args.bcast or args.balanced:
+        traffic = None
+    elif args.merge == "avg":
+        traffic = MEASURED_TRAFFIC_BYTES.get(wl.name)
+    elif args.api == "plan" and args.rda_group == "row":
+        traffic = MEASURED_TRAFFIC_BYTES_RDA_ROWS.get(wl.name)
+    else:
+        traffic = None
 
     out = {
         "metric": METRIC,
