@@ -127,10 +127,21 @@ def cpu_baseline(torch, ddl_synth, wl, data, budget_s=20.0):
                 break
         if t_single >= budget_s:
             break
+    model = ""
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
     return {
         "value": done_params / t_multi,
         "unit": "params/s",
         "cores": cores,
+        "cpu_model": model,
+        "host_cpus": os.cpu_count(),
         "kind": "oracle",
         "sample": (f"{tensors} tensor(s), {done_params} params of workload {wl.name} "
                    f"(of {wl.numel}); same fp64 scalar loop chunked over {cores} threads"),
