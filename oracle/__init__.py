@@ -75,6 +75,14 @@ def load(path: str | None = None) -> ctypes.CDLL:
                                                            ctypes.c_size_t, ctypes.c_size_t,
                                                            ctypes.c_float, ctypes.c_float]
     lib.ddl_oracle_rda_merge_fragment.restype = ctypes.c_int
+    u8pp = ctypes.POINTER(ctypes.c_void_p)
+    lib.ddl_oracle_q4_encode.argtypes = [f32p, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t,
+                                         ctypes.c_size_t, u8p, f32p]
+    lib.ddl_oracle_q4_encode.restype = ctypes.c_int
+    lib.ddl_oracle_q4_merge_fragment.argtypes = [f64p, f64p, f32p, f32p, u8pp, u8pp, u64p, u8p,
+                                                 ctypes.c_int, ctypes.c_size_t, ctypes.c_size_t,
+                                                 ctypes.c_float, ctypes.c_float]
+    lib.ddl_oracle_q4_merge_fragment.restype = ctypes.c_int
     lib.ddl_oracle_round_bf16.argtypes = [f32p, ctypes.POINTER(ctypes.c_uint16), ctypes.c_size_t]
     lib.ddl_oracle_round_bf16.restype = None
     if path is None:
@@ -233,6 +241,59 @@ def round_bf16(x: np.ndarray, lib=None) -> np.ndarray:
     out = np.empty(x.shape, dtype=np.uint16)
     lib.ddl_oracle_round_bf16(_ptr(x, ctypes.c_float), _ptr(out, ctypes.c_uint16), x.size)
     return out
+
+
+def q4_encode(theta: np.ndarray, learner: np.ndarray, block_len: int, lib=None):
+    """4-bit block-wise encoding of one learner's outer gradient theta - learner.  Returns
+    (codes uint8[(n + 1) // 2], scales float32[ceil(n / block_len)])."""
+    lib = lib or load()
+    theta = np.ascontiguousarray(theta, dtype=np.float32)
+    n = theta.shape[0]
+    table, dtype, keep = _learner_table([learner], n)
+    codes = np.zeros((n + 1) // 2, dtype=np.uint8)
+    scales = np.zeros(-(-n // block_len) if n else 0, dtype=np.float32)
+    rc = lib.ddl_oracle_q4_encode(_ptr(theta, ctypes.c_float), table[0], dtype, n, block_len,
+                                  _ptr(codes, ctypes.c_uint8), _ptr(scales, ctypes.c_float))
+    del keep
+    if rc != OK:
+        raise OracleError(rc)
+    return codes, scales
+
+
+def q4_merge_fragment(theta: np.ndarray, v: np.ndarray, codes: Sequence[np.ndarray | None],
+                      scales: Sequence[np.ndarray | None], token_counts, quorum_mask,
+                      block_len: int, lr: float, mu: float, lib=None):
+    """One fragment sync from 4-bit outer gradients (codes + per-block scales per learner).
+    Returns (theta_new, v_new) as float64 arrays."""
+    lib = lib or load()
+    theta = np.ascontiguousarray(theta, dtype=np.float32)
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    n = theta.shape[0]
+    M = len(codes)
+    assert len(scales) == M and v.shape == (n,)
+    t = _counts(token_counts, M)
+    q = _mask(quorum_mask, M)
+    ctab, stab = (ctypes.c_void_p * M)(), (ctypes.c_void_p * M)()
+    keep = []
+    for m in range(M):
+        if codes[m] is None or scales[m] is None:
+            ctab[m] = stab[m] = None
+            continue
+        c = np.ascontiguousarray(codes[m], dtype=np.uint8)
+        s = np.ascontiguousarray(scales[m], dtype=np.float32)
+        assert c.shape == ((n + 1) // 2,) and s.shape == (-(-n // block_len) if n else 0,)
+        ctab[m], stab[m] = c.ctypes.data, s.ctypes.data
+        keep += [c, s]
+    theta_out = np.empty(n, dtype=np.float64)
+    v_out = np.empty(n, dtype=np.float64)
+    rc = lib.ddl_oracle_q4_merge_fragment(
+        _ptr(theta_out, ctypes.c_double), _ptr(v_out, ctypes.c_double),
+        _ptr(theta, ctypes.c_float), _ptr(v, ctypes.c_float), ctab, stab,
+        _ptr(t, ctypes.c_uint64), _ptr(q, ctypes.c_uint8), M, n, block_len, lr, mu)
+    del keep
+    if rc != OK:
+        raise OracleError(rc)
+    return theta_out, v_out
 
 
 def merge_batch(fragments) -> list:

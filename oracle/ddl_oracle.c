@@ -16,6 +16,10 @@
  * Nothing here is blocked, fused, vectorised or reordered: one loop over the
  * elements, one inner loop over the learners, in the order the paper writes the
  * sums.
+ *
+ * PARITY UNPINNED (against the paper) for the 4-bit outer-gradient functions
+ * ddl_oracle_q4_encode / ddl_oracle_q4_merge_fragment: the paper states only
+ * the width; the block-wise format is this build's choice.  See their comment.
  */
 #include <math.h>
 #include <pthread.h>
@@ -333,6 +337,104 @@ void ddl_oracle_round_bf16(const float* x, uint16_t* out, size_t n)
 {
     for (size_t i = 0; i < n; ++i)
         out[i] = round_bf16(x[i]);
+}
+
+/*
+ * 4-bit outer gradients (Appendix D.3, "Outer gradients compression": outer gradients are
+ * compressed to int4 before the merge).  PARITY UNPINNED against the paper: it fixes only the
+ * width, 4 bits per value; block size, scale and rounding below are this build's choice of a
+ * plain symmetric block-wise integer quantiser.  Given that format, the arithmetic is the
+ * definition written out and is pinned by the tests (hand-packed bytes, round-trip error
+ * bound, agreement with the direct-averaging oracle on exactly representable values).
+ *
+ * Format, per learner: the flat fragment is cut into blocks of `block_len` consecutive
+ * elements (the last may be shorter); block b has one fp32 scale s_b; element i has a signed
+ * 4-bit code q_i in two's complement, two codes per byte, element 2k in the low nibble of
+ * byte k and element 2k+1 in its high nibble.  The value an (s, q) pair stands for is s * q.
+ */
+static int q4_code(const uint8_t* codes, size_t i)
+{
+    unsigned nib = (i & 1) ? (codes[i >> 1] >> 4) : (codes[i >> 1] & 0x0fu);
+    return nib >= 8 ? (int)nib - 16 : (int)nib;
+}
+
+/*
+ * Encoder: the outer gradient d_i = Theta_i - theta_{m,i} is formed in fp32; per block
+ * a = max |d_i|, s = a / 7, q_i = round-half-even(d_i / s) clamped to [-7, 7]; an all-zero
+ * block gets s = 0 and q = 0.  A floating-point value decides an integer here, so every step
+ * is taken in fp32, the precision the GPU encoder works in (fp32 subtraction, IEEE division,
+ * round to nearest even), not in double.  `codes_out` has (n + 1) / 2 bytes (an unused high
+ * nibble is 0), `scales_out` has ceil(n / block_len) entries.
+ */
+int ddl_oracle_q4_encode(const float* theta, const void* learner, int learner_dtype, size_t n,
+                         size_t block_len, uint8_t* codes_out, float* scales_out)
+{
+    if (block_len == 0 || (learner_dtype != ORACLE_F32 && learner_dtype != ORACLE_BF16))
+        return ORACLE_BAD_ARG;
+    if (n > 0 && (!theta || !learner || !codes_out || !scales_out))
+        return ORACLE_BAD_ARG;
+    memset(codes_out, 0, (n + 1) / 2);
+    for (size_t b0 = 0, b = 0; b0 < n; b0 += block_len, ++b) {
+        size_t b1 = b0 + block_len < n ? b0 + block_len : n;
+        float a = 0.0f;
+        for (size_t i = b0; i < b1; ++i) {
+            float d = theta[i] - (float)learner_value(learner, learner_dtype, i);
+            if (fabsf(d) > a)
+                a = fabsf(d);
+        }
+        float s = a / 7.0f;
+        scales_out[b] = s;
+        if (!(s > 0.0f))
+            continue;
+        for (size_t i = b0; i < b1; ++i) {
+            float d = theta[i] - (float)learner_value(learner, learner_dtype, i);
+            float r = nearbyintf(d / s); /* default rounding mode: to nearest, ties to even */
+            if (r > 7.0f) r = 7.0f;
+            if (r < -7.0f) r = -7.0f;
+            unsigned nib = (unsigned)((int)r & 0x0f);
+            codes_out[i >> 1] |= (uint8_t)((i & 1) ? nib << 4 : nib);
+        }
+    }
+    return ORACLE_OK;
+}
+
+/*
+ * Merge of 4-bit outer gradients + OuterOpt: the outer gradient of learner m at element i is
+ * s_{m, i / block_len} * q_{m,i}; the rest is weighted direct averaging and the outer step
+ * exactly as in merge_range, in double.  Learners of weight zero are skipped.
+ */
+int ddl_oracle_q4_merge_fragment(double* theta_out, double* v_out, const float* theta,
+                                 const float* v, const uint8_t* const* codes,
+                                 const float* const* scales, const uint64_t* token_counts,
+                                 const uint8_t* quorum_mask, int M, size_t n, size_t block_len,
+                                 float lr, float mu)
+{
+    double w[ORACLE_MAX_LEARNERS];
+    int rc = ddl_oracle_weights(token_counts, quorum_mask, M, w);
+    if (rc != ORACLE_OK)
+        return rc;
+    if (block_len == 0 || !codes || !scales)
+        return ORACLE_BAD_ARG;
+    if (!(lr >= 0.0f) || !(mu >= 0.0f) || isinf(lr) || isinf(mu))
+        return ORACLE_BAD_ARG;
+    if (n > 0 && (!theta_out || !v_out || !theta || !v))
+        return ORACLE_BAD_ARG;
+    for (int m = 0; m < M; ++m)
+        if (w[m] != 0.0 && n > 0 && (!codes[m] || !scales[m]))
+            return ORACLE_BAD_ARG;
+    for (size_t i = 0; i < n; ++i) {
+        double Delta = 0.0;
+        for (int m = 0; m < M; ++m) {
+            if (w[m] == 0.0)
+                continue;
+            double d = (double)scales[m][i / block_len] * (double)q4_code(codes[m], i);
+            Delta += w[m] * d;
+        }
+        double v_new = (double)mu * (double)v[i] + Delta;
+        theta_out[i] = (double)theta[i] - (double)lr * (Delta + (double)mu * v_new);
+        v_out[i] = v_new;
+    }
+    return ORACLE_OK;
 }
 
 /*

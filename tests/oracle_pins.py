@@ -49,6 +49,13 @@ class OracleApi:
     def merge_weighted(self, theta, v, learners, w, lr, mu):
         return oracle.merge_fragment_weighted(theta, v, learners, w, lr, mu, lib=self.lib)
 
+    def q4_encode(self, theta, learner, block_len):
+        return oracle.q4_encode(theta, learner, block_len, lib=self.lib)
+
+    def q4_merge(self, theta, v, codes, scales, t, q, block_len, lr, mu):
+        return oracle.q4_merge_fragment(theta, v, codes, scales, t, q, block_len, lr, mu,
+                                        lib=self.lib)
+
 
 def f32(x):
     return np.ascontiguousarray(np.asarray(x, dtype=np.float32))
@@ -623,6 +630,125 @@ def pin_rda_zero_gradient_cases(o: OracleApi):
     assert np.allclose(d2, [1.5, 2.0, 0.0, 0.0], rtol=0, atol=1e-15)
     d3 = _rda_delta(o, theta, [same, other, None], [1, 1, 7], [1, 1, 0], 2)
     assert np.array_equal(d2, d3)
+
+
+# ---------------------------------------------------------------------------------------
+# 4-bit outer gradients.  The paper gives only the width (Appendix D.3); the block-wise
+# symmetric format is this build's, so these pins fix the oracle to that format's definition
+# (hand-packed bytes, hand-rounded codes), to the error bound any such quantiser has, and to
+# the already pinned direct-averaging oracle on values the format holds exactly.
+# ---------------------------------------------------------------------------------------
+def _q4_unpack(codes: np.ndarray, n: int) -> np.ndarray:
+    """Independent decoder: element 2k = low nibble of byte k, 2k+1 = high nibble, two's
+    complement."""
+    lo = (codes & 0x0F).astype(np.int16)
+    hi = (codes >> 4).astype(np.int16)
+    q = np.empty(2 * codes.size, dtype=np.int16)
+    q[0::2], q[1::2] = lo, hi
+    q[q >= 8] -= 16
+    return q[:n]
+
+
+def pin_q4_hand_packed_bytes(o: OracleApi):
+    """Bytes 0x97 0x04 0x20 0xE2 with scale 0.5 stand for 0.5 * [7,-7,4,0,0,2,2,-2]; one
+    learner, lr 1, mu 0: Theta' = Theta - Delta, v' = Delta."""
+    codes = np.array([0x97, 0x04, 0x20, 0xE2], dtype=np.uint8)
+    scales = np.array([0.5], dtype=np.float32)
+    theta = f32(np.arange(8) * 0.25)
+    th, v = o.q4_merge(theta, f32(np.zeros(8)), [codes], [scales], [5], [1], 8, 1.0, 0.0)
+    d = 0.5 * np.array([7, -7, 4, 0, 0, 2, 2, -2], dtype=np.float64)
+    assert np.array_equal(v, d)
+    assert np.array_equal(th, theta.astype(np.float64) - d)
+
+
+def pin_q4_encode_rounds_half_to_even_and_clamps(o: OracleApi):
+    """Outer gradient [7,-7,3.5,0.5,-0.5,1.5,2.5,-2.5] has absmax 7 -> scale 1 and codes
+    [7,-7,4,0,0,2,2,-2] (ties to even); packed low nibble first."""
+    theta = f32(np.zeros(8))
+    learner = f32(-np.array([7, -7, 3.5, 0.5, -0.5, 1.5, 2.5, -2.5]))
+    codes, scales = o.q4_encode(theta, learner, 8)
+    assert scales.tolist() == [1.0]
+    assert codes.tolist() == [0x97, 0x04, 0x20, 0xE2]
+    # an odd tail: the unused high nibble stays 0; a zero block has scale 0 and codes 0
+    theta = f32(np.zeros(11))
+    learner = f32(np.array([0, 0, 0, 0, -14, 7, 1, 0, 3, 0, -3]))
+    codes, scales = o.q4_encode(theta, learner, 4)
+    assert scales.tolist() == [0.0, 2.0, np.float32(3.0) / np.float32(7.0)]
+    assert _q4_unpack(codes, 11).tolist() == [0, 0, 0, 0, 7, -4, 0, 0, -7, 0, 7]
+    assert codes[5] >> 4 == 0
+
+
+def pin_q4_round_trip_error_bound(o: OracleApi):
+    """Any symmetric round-to-nearest quantiser with step s leaves |d - s q| <= s / 2, hits
+    +-7 at the block's largest element, and never leaves [-7, 7]."""
+    rng = np.random.default_rng(11)
+    for dtype in ("f32", "bf16"):
+        for n, B in ((1000, 64), (777, 128), (64, 1024), (129, 8)):
+            theta = f32(rng.normal(0, 0.02, n))
+            learner = f32(theta + rng.normal(0, 1e-3, n))
+            if dtype == "bf16":
+                learner = bf16_bits(learner)
+            lf = bf16_to_f64(learner) if dtype == "bf16" else learner.astype(np.float64)
+            d = (theta - lf.astype(np.float32)).astype(np.float64)   # fp32 subtraction
+            codes, scales = o.q4_encode(theta, learner, B)
+            q = _q4_unpack(codes, n)
+            assert q.min() >= -7 and q.max() <= 7
+            for b in range(scales.size):
+                lo, hi = b * B, min(n, (b + 1) * B)
+                s = float(scales[b])
+                a = np.abs(d[lo:hi]).max()
+                assert abs(s - a / 7) <= 1e-7 * a
+                assert np.all(np.abs(d[lo:hi] - s * q[lo:hi]) <= 0.5 * s * (1 + 1e-6))
+                assert abs(q[lo:hi][np.argmax(np.abs(d[lo:hi]))]) == 7
+
+
+def pin_q4_merge_matches_direct_average_on_exact_values(o: OracleApi):
+    """Learner values Theta - s q that fp32 holds exactly: the 4-bit merge must equal the
+    (pinned) direct-averaging oracle on those learners, and re-encoding them must give back
+    the same codes and scales."""
+    rng = np.random.default_rng(12)
+    n, B, M = 300, 32, 4
+    nb = -(-n // B)
+    theta = f32(rng.integers(-512, 512, n) / 1024.0)
+    v = f32(rng.integers(-64, 64, n) / 4096.0)
+    codes, scales, learners = [], [], []
+    for m in range(M):
+        q = rng.integers(-7, 8, n)
+        for b in range(nb):                       # every block reaches +-7 somewhere
+            q[b * B] = 7 if (b + m) % 2 else -7
+        s = (2.0 ** rng.integers(-12, -8, nb)).astype(np.float32)
+        packed = np.zeros((n + 1) // 2, dtype=np.uint8)
+        nib = (q & 0x0F).astype(np.uint8)
+        packed[: n // 2] = nib[0:n - n % 2:2] | (nib[1::2] << 4)
+        if n % 2:
+            packed[-1] = nib[-1]
+        learners.append(f32(theta.astype(np.float64) - np.repeat(s, B)[:n].astype(np.float64) * q))
+        codes.append(packed)
+        scales.append(s)
+        c2, s2 = o.q4_encode(theta, learners[-1], B)
+        assert np.array_equal(c2, packed) and np.array_equal(s2, s)
+    t, mask = [3, 5, 7, 11], [1, 0, 1, 1]
+    ref = o.merge(theta, v, learners, t, mask, 0.7, 0.9)
+    got = o.q4_merge(theta, v, [codes[0], None, codes[2], codes[3]],
+                     [scales[0], None, scales[2], scales[3]], t, mask, B, 0.7, 0.9)
+    assert np.allclose(got[0], ref[0], rtol=0, atol=1e-15)
+    assert np.allclose(got[1], ref[1], rtol=0, atol=1e-15)
+
+
+def pin_q4_zero_codes_and_linearity(o: OracleApi):
+    """All-zero codes give Delta = 0 (v' = mu v); doubling every scale doubles Delta."""
+    rng = np.random.default_rng(13)
+    n, B = 101, 16
+    theta, v = f32(rng.normal(0, 0.02, n)), f32(rng.normal(0, 1e-4, n))
+    zc = np.zeros((n + 1) // 2, dtype=np.uint8)
+    s = f32(rng.uniform(1e-4, 1e-3, -(-n // B)))
+    th, vv = o.q4_merge(theta, v, [zc, zc], [s, s], [1, 2], [1, 1], B, 0.7, 0.9)
+    assert np.array_equal(vv, np.float64(np.float32(0.9)) * v.astype(np.float64))
+    c = rng.integers(0, 256, (n + 1) // 2).astype(np.uint8)
+    d1 = o.q4_merge(theta, f32(np.zeros(n)), [c], [s], [1], [1], B, 1.0, 0.0)[1]
+    d2 = o.q4_merge(theta, f32(np.zeros(n)), [c], [f32(2 * s)], [1], [1], B, 1.0, 0.0)[1]
+    assert np.array_equal(d2, 2 * d1)
+    assert np.array_equal(d1, np.repeat(s.astype(np.float64), B)[:n] * _q4_unpack(c, n))
 
 
 ALL_PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_") and callable(v)]

@@ -54,7 +54,24 @@ MUTANTS = [
     ("rda_sign", "double d = (double)theta[i] - learner_value(learner_params[m], learner_dtype, i);\n                u +=",
      "double d = learner_value(learner_params[m], learner_dtype, i) - (double)theta[i];\n                u +="),
     ("rda_groups_merged", "size_t hi = n - lo < group_len ? n : lo + group_len;", "size_t hi = n; group_len = n;"),
-    ("rda_momentum_dropped", "double v_new = (double)mu * (double)v[i] + Delta;", "double v_new = Delta;"),
+    ("rda_momentum_dropped",
+     "double v_new = (double)mu * (double)v[i] + Delta;\n            theta_out[i] = Theta -",
+     "double v_new = Delta;\n            theta_out[i] = Theta -"),
+    ("q4_momentum_dropped",
+     "double v_new = (double)mu * (double)v[i] + Delta;\n        theta_out[i] = (double)theta[i] -",
+     "double v_new = Delta;\n        theta_out[i] = (double)theta[i] -"),
+    ("q4_nibble_order", "(i & 1) ? (codes[i >> 1] >> 4) : (codes[i >> 1] & 0x0fu)",
+     "(i & 1) ? (codes[i >> 1] & 0x0fu) : (codes[i >> 1] >> 4)"),
+    ("q4_no_sign_extension", "return nib >= 8 ? (int)nib - 16 : (int)nib;", "return (int)nib;"),
+    ("q4_scale_index", "(double)scales[m][i / block_len]", "(double)scales[m][i / block_len ? 0 : 0]"),
+    ("q4_scale_dropped", "double d = (double)scales[m][i / block_len] * (double)q4_code(codes[m], i);",
+     "double d = (double)q4_code(codes[m], i);"),
+    ("q4_unweighted", "Delta += w[m] * d;", "Delta += d;"),
+    ("q4_encode_truncates", "float r = nearbyintf(d / s);", "float r = truncf(d / s);"),
+    ("q4_encode_scale_over_8", "float s = a / 7.0f;", "float s = a / 8.0f;"),
+    ("q4_encode_sign", "float d = theta[i] - (float)learner_value(learner, learner_dtype, i);\n            float r =",
+     "float d = (float)learner_value(learner, learner_dtype, i) - theta[i];\n            float r ="),
+    ("q4_encode_pack_order", "(i & 1) ? nib << 4 : nib", "(i & 1) ? nib : nib << 4"),
     ("chunk_overlap", "size_t lo = per * (size_t)t;", "size_t lo = per * (size_t)t + (t ? 1 : 0);"),
 ]
 
