@@ -171,6 +171,38 @@ DDL_API ddl_status ddl_rda_merge_fragment(float* theta, float* v, const void* co
                                           size_t workspace_bytes, void* hip_stream);
 
 /*
+ * 4-bit outer gradients (Appendix D.3, "Outer gradients compression": outer gradients are
+ * compressed from bf16 to int4 before the merge).  The paper fixes only the width; the format
+ * is this library's, a plain symmetric block-wise integer quantiser:
+ *   - the flat fragment is cut into blocks of block_len consecutive elements (block_len a
+ *     multiple of 8, at least 8; the last block may be shorter);
+ *   - per learner, block b has one fp32 scale and element i a signed 4-bit code in two's
+ *     complement, two codes per byte: element 2k in the low nibble of byte k, element 2k + 1 in
+ *     its high nibble; (n + 1) / 2 bytes of codes, ceil(n / block_len) scales;
+ *   - a (scale, code) pair stands for the outer-gradient value scale * code.
+ *
+ * ddl_q4_encode        the learner side: d = Theta - theta_m in fp32, scale = max|d| / 7 over
+ *                      the block, code = round-half-even(d / scale) clamped to [-7, 7]; a block
+ *                      of zeros gets scale 0 and codes 0.  theta, learner_params: device, n
+ *                      elements, 16-byte aligned; codes_out, scales_out: device, 4-byte aligned,
+ *                      written (an unused high nibble is 0).  Reproducible bit for bit.
+ * ddl_q4_merge_fragment   the syncer side: Delta_i = sum_m w_m scale_m[i / block_len] code_m[i]
+ *                      with the quorum weights of ddl_merge_fragment, then the same outer
+ *                      Nesterov step, in place on theta and v (device, 16-byte aligned).
+ *                      codes, scales: HOST arrays of M DEVICE pointers (4-byte aligned); entries
+ *                      of learners of weight zero are never read and may be NULL.
+ * Both only enqueue a kernel.  Errors as ddl_merge_fragment; INVALID_ARG also for a bad
+ * block_len or a misaligned array, ALIAS if an output overlaps any other array of the call.
+ */
+DDL_API ddl_status ddl_q4_encode(const float* theta, const void* learner_params,
+                                 ddl_dtype learner_dtype, size_t n, size_t block_len,
+                                 uint8_t* codes_out, float* scales_out, void* hip_stream);
+DDL_API ddl_status ddl_q4_merge_fragment(float* theta, float* v, const uint8_t* const* codes,
+                                         const float* const* scales, const uint64_t* token_counts,
+                                         const uint8_t* quorum_mask, int M, size_t n,
+                                         size_t block_len, float lr, float mu, void* hip_stream);
+
+/*
  * A fragment as the paper forms it: a set of whole tensors (Section 5.1 and Appendix C,
  * balanced tensor fragmentation), each tensor its own flat array ("segment").  All segments of
  * a fragment share the fragment's counters, mask, lr and mu (per-fragment counters c_{m,p},

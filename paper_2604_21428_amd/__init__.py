@@ -95,6 +95,12 @@ def _load() -> ctypes.CDLL:
     lib.ddl_plan_rda_workspace_bytes.restype = ctypes.c_size_t
     lib.ddl_plan_rda_merge.argtypes = [ctypes.c_void_p, ctypes.POINTER(_Sync), ctypes.c_int,
                                        ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.ddl_q4_encode.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t,
+                                  ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p,
+                                  ctypes.c_void_p]
+    lib.ddl_q4_merge_fragment.argtypes = [ctypes.c_void_p, ctypes.c_void_p, vpp, vpp, u64p, u8p,
+                                          ctypes.c_int, ctypes.c_size_t, ctypes.c_size_t,
+                                          ctypes.c_float, ctypes.c_float, ctypes.c_void_p]
     lib.ddl_balanced_fragments.argtypes = [u64p, ctypes.c_int, ctypes.c_int,
                                            ctypes.POINTER(ctypes.c_int)]
     lib.ddl_copy_probe.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
@@ -105,7 +111,8 @@ def _load() -> ctypes.CDLL:
                  "ddl_merge_fragment_weighted", "ddl_merge_batch", "ddl_plan_create",
                  "ddl_plan_merge", "ddl_plan_destroy", "ddl_set_option", "ddl_get_option",
                  "ddl_copy_probe", "ddl_balanced_fragments", "ddl_merge_fragment_bcast",
-                 "ddl_rda_merge_fragment", "ddl_plan_set_rda_groups", "ddl_plan_rda_merge"):
+                 "ddl_rda_merge_fragment", "ddl_plan_set_rda_groups", "ddl_plan_rda_merge",
+                 "ddl_q4_encode", "ddl_q4_merge_fragment"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -255,6 +262,60 @@ def rda_merge_fragment(theta: torch.Tensor, v: torch.Tensor,
                                        group_len, lr, mu, workspace.data_ptr(),
                                        workspace.numel() * workspace.element_size(),
                                        _stream_handle(stream)), "ddl_rda_merge_fragment")
+
+
+def q4_encode(theta: torch.Tensor, learner: torch.Tensor, block_len: int,
+              codes: Optional[torch.Tensor] = None, scales: Optional[torch.Tensor] = None,
+              stream=None):
+    """ddl_q4_encode: 4-bit block-wise codes and fp32 scales of the outer gradient
+    theta - learner.  Returns (codes uint8[(n + 1) // 2], scales float32[ceil(n / block_len)]),
+    allocated here unless given."""
+    n = theta.numel()
+    if learner.numel() != n or not learner.is_cuda or not learner.is_contiguous():
+        raise ValueError("learner must be a contiguous device tensor of theta's size")
+    blocks = -(-n // block_len) if n and block_len > 0 else 0
+    if codes is None:
+        codes = torch.empty((n + 1) // 2, dtype=torch.uint8, device=theta.device)
+    if scales is None:
+        scales = torch.empty(blocks, dtype=torch.float32, device=theta.device)
+    if codes.dtype != torch.uint8 or codes.numel() < (n + 1) // 2 or not codes.is_cuda:
+        raise ValueError("codes must be a device uint8 tensor of (n + 1) // 2 bytes")
+    if scales.dtype != torch.float32 or not scales.is_cuda or scales.numel() < blocks:
+        raise ValueError("scales must be a device float32 tensor of ceil(n / block_len) entries")
+    _check(_lib.ddl_q4_encode(_state_ptr(theta, "theta"), learner.data_ptr(),
+                              _dtype_code(learner.dtype), n, block_len, codes.data_ptr(),
+                              scales.data_ptr(), _stream_handle(stream)), "ddl_q4_encode")
+    return codes, scales
+
+
+def q4_merge_fragment(theta: torch.Tensor, v: torch.Tensor,
+                      codes: Sequence[Optional[torch.Tensor]],
+                      scales: Sequence[Optional[torch.Tensor]], token_counts, quorum_mask,
+                      block_len: int, lr: float, mu: float, stream=None) -> None:
+    """ddl_q4_merge_fragment: in-place sync of one flat fragment from the learners' 4-bit
+    outer gradients (codes + per-block scales, as ``q4_encode`` writes them)."""
+    n = theta.numel()
+    if v.numel() != n:
+        raise ValueError("theta and v differ in size")
+    M = len(codes)
+    if len(scales) != M:
+        raise ValueError("one scales tensor per codes tensor")
+    ctab, stab = (ctypes.c_void_p * M)(), (ctypes.c_void_p * M)()
+    for m in range(M):
+        c, s = codes[m], scales[m]
+        if c is not None:
+            if c.dtype != torch.uint8 or not c.is_cuda or c.numel() < (n + 1) // 2:
+                raise ValueError("codes must be device uint8 tensors of (n + 1) // 2 bytes")
+            ctab[m] = c.data_ptr()
+        if s is not None:
+            if s.dtype != torch.float32 or not s.is_cuda:
+                raise ValueError("scales must be device float32 tensors")
+            if block_len > 0 and s.numel() < -(-n // block_len):
+                raise ValueError("scales tensor too short")
+            stab[m] = s.data_ptr()
+    _check(_lib.ddl_q4_merge_fragment(_state_ptr(theta, "theta"), _state_ptr(v, "v"), ctab, stab,
+                                      _u64(token_counts, M), _u8(quorum_mask, M), M, n, block_len,
+                                      lr, mu, _stream_handle(stream)), "ddl_q4_merge_fragment")
 
 
 def merge_fragment_weighted(theta: torch.Tensor, v: torch.Tensor,

@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libddlsync.so")
-SOURCES = ["ddl_kernels.hip", "ddl_host.hip", "ddl_partition.hip", "ddl_rda.hip"]
+SOURCES = ["ddl_kernels.hip", "ddl_host.hip", "ddl_partition.hip", "ddl_rda.hip", "ddl_q4.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 instructions are disabled on purpose: the compiler otherwise forms them from

@@ -92,11 +92,13 @@ uint32_t lds_cap_bytes()
     return b > 64 * 1024 ? 64 * 1024 : b;
 }
 
+}  // namespace
+
+uint32_t ddlh::merge_lds_cap_bytes() { return lds_cap_bytes(); }
+
 // ------------------------------------------------------------------------------------------
 // weights
 // ------------------------------------------------------------------------------------------
-}  // namespace
-
 bool ddlh::finite_nonneg(float x) { return std::isfinite(x) && x >= 0.0f; }
 
 ddl_status ddlh::weights_tokens(const uint64_t* t, const uint8_t* q, int M, double* w)

@@ -53,6 +53,9 @@ ddl_status weights_tokens(const uint64_t* t, const uint8_t* q, int M, double* w)
 // Drops learners of weight zero; rounds the rest once to fp32.
 void compact(const double* w, int M, Quorum& out);
 bool finite_nonneg(float x);
+// Unused dynamic LDS per workgroup that enforces the max_blocks_per_cu option on the
+// streaming merge kernels (0: no cap).
+uint32_t merge_lds_cap_bytes();
 // Records the message for ddl_last_error_message and returns DDL_ERR_RUNTIME.
 ddl_status runtime_error(hipError_t e, const char* what);
 
