@@ -59,9 +59,11 @@ def parse_args():
     ap.add_argument("--balanced", type=int, default=0, metavar="P",
                     help="regroup the workload's tensors into P balanced fragments with "
                          "ddl_balanced_fragments (the paper uses P = 24)")
-    ap.add_argument("--merge", default="avg", choices=["avg", "rda"],
+    ap.add_argument("--merge", default="avg", choices=["avg", "rda", "q4"],
                     help="avg: weighted direct averaging (the metric's path); rda: "
-                         "radial-directional averaging, one ddl_rda_merge_fragment per tensor")
+                         "radial-directional averaging; q4: merge of 4-bit block-wise outer "
+                         "gradients (each fragment stored as one flat array)")
+    ap.add_argument("--q4-block", type=int, default=128, help="elements per scale block (q4)")
     ap.add_argument("--rda-group", default="row", choices=["row", "tensor"],
                     help="one norm per row of the last dimension, or one per tensor")
     ap.add_argument("--bcast", action="store_true",
@@ -235,7 +237,30 @@ def main():
             for s in segs:
                 s.bcast = (torch.empty(s.theta.numel(), dtype=torch.bfloat16, device="cuda:0")
                            if args.bcast else None)
-        if args.merge == "rda" and args.api == "plan":
+        if args.merge == "q4":
+            # Each fragment as ONE flat array (its tensors back to back); the learners' outer
+            # gradients are encoded once, outside the timed region, as a learner would send them.
+            calls = []
+            for fi in wl.arrival_order:
+                f = wl.fragments[fi]
+                theta = torch.cat([s.theta for s in data[fi]])
+                v = torch.cat([s.v for s in data[fi]])
+                codes, scales = [], []
+                for m in range(f.M):
+                    if not (f.quorum_mask[m] and f.token_counts[m] > 0):
+                        codes.append(None)
+                        scales.append(None)
+                        continue
+                    c, sc = ddl.q4_encode(theta, torch.cat([s.learners[m] for s in data[fi]]),
+                                          args.q4_block)
+                    codes.append(c)
+                    scales.append(sc)
+                calls.append((f, theta, v, codes, scales))
+                data[fi] = None
+            torch.cuda.synchronize()
+            torch.cuda.empty_cache()
+            copies.append((data, "q4", calls))
+        elif args.merge == "rda" and args.api == "plan":
             plan = ddl.Plan([ddl.Fragment([(s.theta, s.v, s.learners) for s in segs], M=f.M,
                                           learner_dtype=dt[f.learner_dtype])
                              for f, segs in zip(wl.fragments, data)])
@@ -283,6 +308,13 @@ def main():
             for fi, c in zip(wl.arrival_order, calls):
                 out.append((fi, wl.fragments[fi].numel * wl.fragments[fi].bytes_per_param,
                             lambda c=c, rplan=rplan, ws=ws: rplan.rda_merge(c, ws)))
+        elif plan == "q4":
+            for f, theta, v, codes, scales in calls:
+                nb = theta.numel() * 16 + sum(c.numel() + 4 * sc.numel()
+                                              for c, sc in zip(codes, scales) if c is not None)
+                out.append((f.index, nb, lambda f=f, theta=theta, v=v, codes=codes, scales=scales:
+                            ddl.q4_merge_fragment(theta, v, codes, scales, f.token_counts,
+                                                  f.quorum_mask, args.q4_block, f.lr, f.mu)))
         elif plan == "rda":
             for s, f, g, ws in calls:
                 nb = s.theta.numel() * f.bytes_per_param
@@ -329,6 +361,9 @@ def main():
             graphs[gcount[0] % replicas].replay()
             gcount[0] += 1
 
+    if args.merge == "q4" and (args.bcast or args.balanced or args.api != "plan"):
+        sys.stderr.write("bench.py: --merge q4 takes none of --bcast, --balanced, --api\n")
+        sys.exit(2)
     if args.merge == "rda" and args.api == "batch":
         sys.stderr.write("bench.py: --merge rda goes with --api plan or --api tensor\n")
         sys.exit(2)
@@ -357,7 +392,10 @@ def main():
                                                  min(steps, 40), 2 * wl.numel if args.bcast else 0)
 
     params_per_s = wl.numel / (wall_ms * 1e-3)
-    alg_bytes = wl.algorithmic_bytes + (2 * wl.numel if args.bcast else 0)
+    if args.merge == "q4":
+        alg_bytes = sum(nb for _, nb, _ in launch_lists[0])
+    else:
+        alg_bytes = wl.algorithmic_bytes + (2 * wl.numel if args.bcast else 0)
     # The step consists of merge-kernel launches only (no copies, no other kernels), so the
     # event time per step divided by the launches per step is the average launch duration,
     # gaps between back-to-back launches included.
@@ -368,7 +406,7 @@ def main():
         traffic = None
     elif args.merge == "avg":
         traffic = MEASURED_TRAFFIC_BYTES.get(wl.name)
-    elif args.api == "plan" and args.rda_group == "row":
+    elif args.merge == "rda" and args.api == "plan" and args.rda_group == "row":
         traffic = MEASURED_TRAFFIC_BYTES_RDA_ROWS.get(wl.name)
     else:
         traffic = None
@@ -397,10 +435,13 @@ def main():
             "state_dtype": "f32",
             "lr": wl.fragments[0].lr,
             "mu": wl.fragments[0].mu,
-            "api": ("ddl_rda_merge_fragment" if args.api == "tensor" else
+            "api": ("ddl_q4_merge_fragment" if args.merge == "q4" else
+                    "ddl_rda_merge_fragment" if args.api == "tensor" else
                     "ddl_plan_rda_merge" if args.merge == "rda" else
                     "ddl_plan_merge" if args.api == "plan" else "ddl_merge_batch"),
-            "merge": args.merge if args.merge == "avg" else f"rda/{args.rda_group}",
+            "merge": (args.merge if args.merge == "avg" else
+                      f"q4/block{args.q4_block}" if args.merge == "q4" else
+                      f"rda/{args.rda_group}"),
             "launches_per_step": launches_per_step,
             "replicas": replicas,
             "bf16_broadcast_copy": bool(args.bcast),
@@ -418,6 +459,7 @@ def main():
             "frac": achieved / HBM_PEAK_GBPS,
             "traffic": traffic,
             "kernel": ("ddl_merge_kernel" if args.merge == "avg" else
+                       "q4_merge_kernel" if args.merge == "q4" else
                        "rda kernel(s) of one tensor" if args.api == "tensor" else
                        "rda kernel(s) of one fragment"),
             "avg_launch_ms": kernel_ms,
@@ -428,7 +470,7 @@ def main():
     }
     if detail is not None:
         out["detail"] = detail
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.merge != "q4":   # the oracle leg times the bf16 path
         out["cpu_baseline"] = cpu_baseline(torch, ddl_synth, wl, data)
     print(json.dumps(out))
 
