@@ -42,6 +42,8 @@ struct DdlQ4EncodeArgs {
     uint64_t n;
     uint32_t block_len;
     uint32_t num_blocks;
+    uint32_t lanes_per_block;  // power of two, 2..64, lanes_per_block * 4 <= block_len
+    uint32_t pad;
 };
 
 namespace {
@@ -112,73 +114,74 @@ __global__ void __launch_bounds__(DDL_BLOCK) q4_merge_kernel(const DdlQ4Args a)
     }
 }
 
-// Encoder: one wavefront per block.  Lanes walk the block in chunks of eight elements (one
-// 32-bit word of codes), first for the block's largest magnitude, then again to quantise.
+// Encoder: a group of `lanes_per_block` lanes (a power of two, at most a wavefront) per block;
+// a wavefront holds 64 / lanes_per_block blocks side by side.  The lanes of a group walk their
+// block in chunks of four elements (one 16-bit word of codes), first for the block's largest
+// magnitude (combined by lane shuffles within the group), then again to quantise (the second
+// walk finds the block in the cache).
 template <typename L>
 __global__ void __launch_bounds__(DDL_BLOCK) q4_encode_kernel(const DdlQ4EncodeArgs a)
 {
     typedef typename L::elem elem;
     const uint32_t lane = threadIdx.x & 63;
-    const uint32_t b = blockIdx.x * (DDL_BLOCK / 64) + (threadIdx.x >> 6);
-    if (b >= a.num_blocks) return;  // whole wavefronts leave together: no barrier below
-    const uint64_t b0 = (uint64_t)b * a.block_len;
-    const uint32_t len = a.n - b0 < a.block_len ? (uint32_t)(a.n - b0) : a.block_len;
-    const uint32_t chunks = (len + 7) / 8;
+    const uint32_t lpb = a.lanes_per_block;
+    const uint64_t wave = (uint64_t)blockIdx.x * (DDL_BLOCK / 64) + (threadIdx.x >> 6);
+    const uint64_t b = wave * (64 / lpb) + lane / lpb;
+    const uint32_t gl = lane & (lpb - 1);  // lane within its group
+    // Lanes whose block does not exist keep len = 0: they skip both walks but still take part
+    // in the shuffles, which every lane of the wavefront reaches.
+    const bool active = b < a.num_blocks;
+    const uint64_t b0 = active ? b * a.block_len : 0;
+    const uint32_t len = !active ? 0u : a.n - b0 < a.block_len ? (uint32_t)(a.n - b0) : a.block_len;
+    const uint32_t chunks = (len + 3) / 4;
     const DDL_GLOBAL float* th = reinterpret_cast<const DDL_GLOBAL float*>(a.theta) + b0;
     const DDL_GLOBAL elem* lp = reinterpret_cast<const DDL_GLOBAL elem*>(a.learner) + b0;
 
-    auto diffs = [&](uint32_t c, float (&d)[8]) {  // outer gradients of chunk c, 0 past the end
-        const uint32_t e = c * 8;
-        if (e + 8 <= len) {
-            const f32x4 t0 = *reinterpret_cast<const DDL_GLOBAL f32x4*>(th + e);
-            const f32x4 t1 = *reinterpret_cast<const DDL_GLOBAL f32x4*>(th + e + 4);
-            const typename L::raw r0 = *reinterpret_cast<const DDL_GLOBAL typename L::raw*>(lp + e);
-            const typename L::raw r1 =
-                *reinterpret_cast<const DDL_GLOBAL typename L::raw*>(lp + e + 4);
-            float x0[4], x1[4];
-            L::widen(r0, x0);
-            L::widen(r1, x1);
-            const float t[8] = {t0.x, t0.y, t0.z, t0.w, t1.x, t1.y, t1.z, t1.w};
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                d[k] = t[k] - x0[k];
-                d[k + 4] = t[k + 4] - x1[k];
-            }
+    auto diffs = [&](uint32_t c, float (&d)[4]) {  // outer gradients of chunk c, 0 past the end
+        const uint32_t e = c * 4;
+        if (e + 4 <= len) {
+            const f32x4 t = *reinterpret_cast<const DDL_GLOBAL f32x4*>(th + e);
+            const typename L::raw r = *reinterpret_cast<const DDL_GLOBAL typename L::raw*>(lp + e);
+            float x[4];
+            L::widen(r, x);
+            d[0] = t.x - x[0];
+            d[1] = t.y - x[1];
+            d[2] = t.z - x[2];
+            d[3] = t.w - x[3];
         } else {
 #pragma unroll
-            for (int k = 0; k < 8; ++k) d[k] = e + k < len ? th[e + k] - L::widen1(lp[e + k]) : 0.0f;
+            for (int k = 0; k < 4; ++k) d[k] = e + k < len ? th[e + k] - L::widen1(lp[e + k]) : 0.0f;
         }
     };
 
     float amax = 0.0f;
-    for (uint32_t c = lane; c < chunks; c += 64) {
-        float d[8];
+    for (uint32_t c = gl; c < chunks; c += lpb) {
+        float d[4];
         diffs(c, d);
 #pragma unroll
-        for (int k = 0; k < 8; ++k) amax = fmaxf(amax, fabsf(d[k]));
+        for (int k = 0; k < 4; ++k) amax = fmaxf(amax, fabsf(d[k]));
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, 64));
+    for (uint32_t o = lpb >> 1; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, (int)o, 64));
     const float s = __fdiv_rn(amax, 7.0f);
-    if (lane == 0) *(reinterpret_cast<DDL_GLOBAL float*>(a.scales) + b) = s;
+    if (active && gl == 0) *(reinterpret_cast<DDL_GLOBAL float*>(a.scales) + b) = s;
 
-    for (uint32_t c = lane; c < chunks; c += 64) {
-        float d[8];
+    for (uint32_t c = gl; c < chunks; c += lpb) {
+        float d[4];
         diffs(c, d);
         uint32_t word = 0;
         if (s > 0.0f) {
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
+            for (int k = 0; k < 4; ++k) {
                 float r = rintf(__fdiv_rn(d[k], s));  // to nearest, ties to even
                 r = fminf(fmaxf(r, -7.0f), 7.0f);
                 word |= ((uint32_t)(int32_t)r & 0xfu) << (4 * k);
             }
         }
-        const uint64_t e = b0 + (uint64_t)c * 8;  // a multiple of eight: byte e / 2, word e / 8
-        if (c * 8 + 8 <= len) {
-            *(reinterpret_cast<DDL_GLOBAL uint32_t*>(a.codes) + e / 8) = word;
+        const uint64_t e = b0 + (uint64_t)c * 4;  // a multiple of four: byte e / 2
+        if (c * 4 + 4 <= len) {
+            *(reinterpret_cast<DDL_GLOBAL uint16_t*>(a.codes) + e / 4) = (uint16_t)word;
         } else {  // the tensor's last, partial chunk: only the bytes that exist
-            const uint32_t bytes = (len - c * 8 + 1) / 2;
+            const uint32_t bytes = (len - c * 4 + 1) / 2;
             for (uint32_t k = 0; k < bytes; ++k)
                 *(reinterpret_cast<DDL_GLOBAL uint8_t*>(a.codes) + e / 2 + k) = (uint8_t)(word >> (8 * k));
         }
@@ -236,8 +239,12 @@ extern "C" ddl_status ddl_q4_encode(const float* theta, const void* learner_para
     a.n = n;
     a.block_len = (uint32_t)block_len;
     a.num_blocks = (uint32_t)blocks;
-    const uint32_t per = DDL_BLOCK / 64;
-    const dim3 grid((a.num_blocks + per - 1) / per), block(DDL_BLOCK);
+    a.lanes_per_block = 2;  // block_len >= 8
+    while (a.lanes_per_block < 64 && (size_t)a.lanes_per_block * 8 <= block_len)
+        a.lanes_per_block *= 2;
+    const uint64_t per_wave = 64 / a.lanes_per_block;
+    const uint64_t waves = (blocks + per_wave - 1) / per_wave;
+    const dim3 grid((uint32_t)((waves + DDL_BLOCK / 64 - 1) / (DDL_BLOCK / 64))), block(DDL_BLOCK);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (learner_dtype == DDL_F32)
         hipLaunchKernelGGL(q4_encode_kernel<LearnerF32>, grid, block, 0, stream, a);
