@@ -34,6 +34,9 @@ MEASURED_TRAFFIC_BYTES = {
     "large_dense": 27240225002,  # profiles/ddl_merge_kernel_large_workloads.txt
 }
 # The same for one sync with the RDA merge through the plan, one norm per row.
+MEASURED_TRAFFIC_BYTES_Q4_BLOCK128 = {
+    "dense_block": 899423015,    # profiles/ddl_q4_kernels.txt
+}
 MEASURED_TRAFFIC_BYTES_RDA_ROWS = {
     "dense_block": 1107347345,   # profiles/ddl_rda_kernels.txt
 }
@@ -406,6 +409,8 @@ def main():
         traffic = None
     elif args.merge == "avg":
         traffic = MEASURED_TRAFFIC_BYTES.get(wl.name)
+    elif args.merge == "q4" and args.q4_block == 128:
+        traffic = MEASURED_TRAFFIC_BYTES_Q4_BLOCK128.get(wl.name)
     elif args.merge == "rda" and args.api == "plan" and args.rda_group == "row":
         traffic = MEASURED_TRAFFIC_BYTES_RDA_ROWS.get(wl.name)
     else:
