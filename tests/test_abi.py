@@ -135,6 +135,107 @@ def test_argument_errors_need_no_device(ddl):
     assert lib.ddl_merge_batch(None, 1, None) == ddl.DDL_ERR_INVALID_ARG
 
 
+def test_argument_errors_of_the_other_entry_points_need_no_device(ddl):
+    """RDA, plan-RDA and 4-bit entry points: everything that is rejected before a launch,
+    with fake addresses."""
+    lib = ddl._lib
+    M = 2
+    tok = (ctypes.c_uint64 * M)(5, 6)
+    ones = (ctypes.c_uint8 * M)(1, 1)
+    zeros = (ctypes.c_uint8 * M)(0, 0)
+    table = (ctypes.c_void_p * M)(0x10000000, 0x20000000)
+    th, v, ws = ctypes.c_void_p(0x40000000), ctypes.c_void_p(0x50000000), ctypes.c_void_p(0x60000000)
+    n = 4096
+
+    def rda(mask=ones, g=64, work=ws, work_bytes=1 << 20, theta=th):
+        return lib.ddl_rda_merge_fragment(theta, v, table, ddl.DDL_BF16, tok, mask, M, n, g, 0.7,
+                                          0.9, work, work_bytes, None)
+
+    assert rda(mask=zeros) == ddl.DDL_ERR_EMPTY_QUORUM
+    assert rda(g=0) == ddl.DDL_ERR_INVALID_ARG
+    assert rda(work=None) == ddl.DDL_ERR_INVALID_ARG
+    assert rda(work=ctypes.c_void_p(0x60000010)) == ddl.DDL_ERR_INVALID_ARG       # 256-byte alignment
+    assert rda(work_bytes=16) == ddl.DDL_ERR_INVALID_ARG
+    assert rda(work=ctypes.c_void_p(0x40000000 + 256)) == ddl.DDL_ERR_ALIAS       # inside theta
+    assert lib.ddl_rda_workspace_bytes(0, 64, 2) == 0
+    assert lib.ddl_rda_workspace_bytes(n, 0, 2) == 0
+    assert lib.ddl_rda_workspace_bytes(n, 64, 17) == 0
+    assert lib.ddl_rda_workspace_bytes(n, 64, 2) > 0
+
+    assert lib.ddl_plan_rda_workspace_bytes(None) == 0
+    assert lib.ddl_plan_set_rda_groups(None, None, 0) == ddl.DDL_ERR_INVALID_ARG
+    assert lib.ddl_plan_rda_merge(None, None, 0, None, 0, None) == ddl.DDL_ERR_INVALID_ARG
+
+    codes = (ctypes.c_void_p * M)(0x70000000, 0x71000000)
+    scales = (ctypes.c_void_p * M)(0x72000000, 0x73000000)
+
+    def q4(mask=ones, B=128, theta=th, c=codes, s=scales, lr=0.7):
+        return lib.ddl_q4_merge_fragment(theta, v, c, s, tok, mask, M, n, B, lr, 0.9, None)
+
+    assert q4(mask=zeros) == ddl.DDL_ERR_EMPTY_QUORUM
+    for bad in (0, 4, 12, 100):
+        assert q4(B=bad) == ddl.DDL_ERR_INVALID_ARG
+    assert q4(lr=float("nan")) == ddl.DDL_ERR_INVALID_ARG
+    assert q4(theta=ctypes.c_void_p(0x40000004)) == ddl.DDL_ERR_INVALID_ARG       # 16-byte alignment
+    assert q4(c=(ctypes.c_void_p * M)(0x70000000, None)) == ddl.DDL_ERR_INVALID_ARG
+    assert q4(c=(ctypes.c_void_p * M)(0x70000002, 0x71000000)) == ddl.DDL_ERR_INVALID_ARG
+    assert q4(s=(ctypes.c_void_p * M)(0x72000000, 0x40000000 + 64)) == ddl.DDL_ERR_ALIAS
+    assert q4(c=(ctypes.c_void_p * M)(0x50000000 + 64, 0x71000000)) == ddl.DDL_ERR_ALIAS
+    # an absent learner's entries are not looked at
+    half = (ctypes.c_uint8 * M)(1, 0)
+    assert lib.ddl_q4_merge_fragment(th, v, (ctypes.c_void_p * M)(0x70000000, None),
+                                     (ctypes.c_void_p * M)(0x72000000, None), tok, half, M, 0,
+                                     128, 0.7, 0.9, None) == ddl.DDL_OK            # n = 0
+
+    def enc(dtype=ddl.DDL_BF16, B=128, learner=0x10000000, c=0x70000000, s=0x72000000, count=n):
+        return lib.ddl_q4_encode(th, ctypes.c_void_p(learner), dtype, count, B, ctypes.c_void_p(c),
+                                 ctypes.c_void_p(s), None)
+
+    assert enc(dtype=5) == ddl.DDL_ERR_INVALID_ARG
+    assert enc(B=20) == ddl.DDL_ERR_INVALID_ARG
+    assert enc(learner=0x10000008) == ddl.DDL_ERR_INVALID_ARG
+    assert enc(c=0x70000001) == ddl.DDL_ERR_INVALID_ARG
+    assert enc(c=0x40000000 + 128) == ddl.DDL_ERR_ALIAS
+    assert enc(s=0x10000000) == ddl.DDL_ERR_ALIAS
+    assert enc(count=0) == ddl.DDL_OK
+
+
+def test_a_plain_c_program_links_and_calls_the_library(ddl, tmp_path):
+    """The boundary is a C ABI: a C99 program compiled with gcc links against libddlsync.so
+    and calls its host-only entry points."""
+    import subprocess
+    src = tmp_path / "use.c"
+    src.write_text(r"""
+#include <stdio.h>
+#include "ddlsync.h"
+int main(void) {
+    uint64_t tokens[3] = {2, 5, 6};
+    uint8_t mask[3] = {1, 0, 1};
+    double w[3];
+    uint64_t sizes[5] = {7, 5, 4, 3, 3};
+    int frag[5];
+    if (ddl_version() < 100) return 1;
+    if (ddl_compute_weights(tokens, mask, 3, w) != DDL_OK) return 2;
+    if (w[0] != 0.25 || w[1] != 0.0 || w[2] != 0.75) return 3;
+    mask[0] = 0; mask[2] = 0;
+    if (ddl_compute_weights(tokens, mask, 3, w) != DDL_ERR_EMPTY_QUORUM) return 4;
+    if (ddl_balanced_fragments(sizes, 5, 2, frag) != DDL_OK) return 5;
+    printf("%d%d%d%d%d %s\n", frag[0], frag[1], frag[2], frag[3], frag[4],
+           ddl_status_string(DDL_ERR_EMPTY_QUORUM));
+    return 0;
+}
+""")
+    exe = tmp_path / "use"
+    libdir = os.path.dirname(ddl.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", libdir, "-lddlsync",
+                    "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib",
+                    "-Wl,--allow-shlib-undefined"], check=True)
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, (r.returncode, r.stderr)
+    assert r.stdout.strip() == "01101 empty quorum"   # 7|5, 5+4, 7+3, 9+3
+
+
 def test_options(ddl):
     assert ddl.get_option("tiles_per_block") >= 1
     assert ddl.get_option("max_blocks_per_cu") >= 0
