@@ -71,10 +71,7 @@ def parse_args():
                     help="one norm per row of the last dimension, or one per tensor")
     ap.add_argument("--bcast", action="store_true",
                     help="also write the new Theta as bf16 in the same pass (+2 B/param)")
-    ap.add_argument("--layout", default="arena", choices=["arena", "torch"],
-                    help="arena: each fragment's arrays in one allocation at the offsets "
-                         "ddl_arena_layout gives (staggered within the 64 KiB stripe); torch: "
-                         "one torch allocation per array, wherever the caching allocator puts it")
+    ap.add_argument("--tile-rotate", type=int, default=None)
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph and time replays (plan API, avg merge)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -215,6 +212,8 @@ def main():
     torch.cuda.set_device(0)
     if args.tiles_per_block is not None:
         ddl.set_option("tiles_per_block", args.tiles_per_block)
+    if args.tile_rotate is not None:
+        ddl.set_option("tile_rotate", args.tile_rotate)
     if args.max_blocks_per_cu is not None:
         ddl.set_option("max_blocks_per_cu", args.max_blocks_per_cu)
     if args.rda_blocks_per_cu is not None:
@@ -238,27 +237,12 @@ def main():
         1, min(8, -(-3 * (1 << 30) // footprint)))
     dt = {"bf16": torch.bfloat16, "f32": torch.float32}
     copies = []
-    arenas = []                 # keeps the arenas alive
     for r in range(replicas):
-        data = []
-        for f in wl.fragments:
-            if args.layout == "arena":
-                arena = ddl.Arena([t.numel for t in f.tensors], f.M, dt[f.learner_dtype],
-                                  with_theta_bf16=args.bcast)
-                arenas.append(arena)
-
-                def alloc(i, role, m, n, dtype, arena=arena):
-                    return {"theta": arena.theta, "v": arena.v}[role](i) if m is None \
-                        else arena.learner(i, m)
-                segs = ddl_synth.make_fragment(wl, f, "cuda:0", absent="valid", alloc=alloc)
-                for i, s in enumerate(segs):
-                    s.bcast = arena.theta_bf16(i) if args.bcast else None
-            else:
-                segs = ddl_synth.make_fragment(wl, f, "cuda:0", absent="valid")
-                for s in segs:
-                    s.bcast = (torch.empty(s.theta.numel(), dtype=torch.bfloat16, device="cuda:0")
-                               if args.bcast else None)
-            data.append(segs)
+        data = [ddl_synth.make_fragment(wl, f, "cuda:0", absent="valid") for f in wl.fragments]
+        for segs in data:
+            for s in segs:
+                s.bcast = (torch.empty(s.theta.numel(), dtype=torch.bfloat16, device="cuda:0")
+                           if args.bcast else None)
         if args.merge == "q4":
             # Each fragment as ONE flat array (its tensors back to back); the learners' outer
             # gradients are encoded once, outside the timed region, as a learner would send them.
@@ -468,10 +452,10 @@ def main():
                       f"rda/{args.rda_group}"),
             "launches_per_step": launches_per_step,
             "replicas": replicas,
-            "layout": args.layout,
             "bf16_broadcast_copy": bool(args.bcast),
             "hip_graph": bool(args.graph),
             "tiles_per_block": ddl.get_option("tiles_per_block"),
+            "tile_rotate": ddl.get_option("tile_rotate"),
             "max_blocks_per_cu": ddl.get_option("max_blocks_per_cu"),
         },
         "achieved_gbps": alg_bytes / (wall_ms * 1e-3) / 1e9,

@@ -286,11 +286,8 @@ class SegmentData:
 
 
 def make_segment(wl: Workload, frag: FragmentSpec, tensor_index: int, device="cpu",
-                 absent: str = "valid", numel: Optional[int] = None, alloc=None) -> SegmentData:
+                 absent: str = "valid", numel: Optional[int] = None) -> SegmentData:
     """Draw theta, v and the M learner copies of one tensor.
-
-    ``alloc(role, m, numel, dtype)`` (role "theta", "v" or "learner"; m the learner index, else
-    None) supplies the buffers -- e.g. views into one arena; default: a torch allocation each.
 
     ``absent`` says what absent learners' buffers hold: "valid" (a normal drifted copy, as
     when a learner merely missed the deadline), "nan" (poisoned) or "none" (no buffer).
@@ -299,13 +296,9 @@ def make_segment(wl: Workload, frag: FragmentSpec, tensor_index: int, device="cp
     n = spec.numel if numel is None else numel
     dt = torch.bfloat16 if frag.learner_dtype == "bf16" else torch.float32
     key = (wl.name, frag.index, tensor_index)
-    if alloc is None:
-        def alloc(role, m, numel_, dtype):
-            return torch.empty(numel_, dtype=dtype, device=device)
-    theta = alloc("theta", None, n, torch.float32)
+    theta = torch.empty(n, dtype=torch.float32, device=device)
     _randn_into(theta, 0.02, _gen(device, *key, "theta"))
-    v = alloc("v", None, n, torch.float32)
-    v.zero_()
+    v = torch.zeros(n, dtype=torch.float32, device=device)
     if frag.v_sigma > 0:
         _randn_into(v, frag.v_sigma, _gen(device, *key, "v"))
     learners: List[Optional[torch.Tensor]] = []
@@ -314,7 +307,7 @@ def make_segment(wl: Workload, frag: FragmentSpec, tensor_index: int, device="cp
         if not present and absent == "none":
             learners.append(None)
             continue
-        x = alloc("learner", m, n, dt)
+        x = torch.empty(n, dtype=dt, device=device)
         if not present and absent == "nan":
             x.fill_(float("nan"))
         else:
@@ -323,15 +316,9 @@ def make_segment(wl: Workload, frag: FragmentSpec, tensor_index: int, device="cp
     return SegmentData(theta, v, learners)
 
 
-def make_fragment(wl: Workload, frag: FragmentSpec, device="cpu", absent: str = "valid",
-                  alloc=None) -> List[SegmentData]:
-    """All tensors of a fragment.  ``alloc(tensor_index, role, m, numel, dtype)`` supplies the
-    buffers (see make_segment)."""
-    out = []
-    for i in range(len(frag.tensors)):
-        a = None if alloc is None else (lambda role, m, n, dt, i=i: alloc(i, role, m, n, dt))
-        out.append(make_segment(wl, frag, i, device, absent, alloc=a))
-    return out
+def make_fragment(wl: Workload, frag: FragmentSpec, device="cpu",
+                  absent: str = "valid") -> List[SegmentData]:
+    return [make_segment(wl, frag, i, device, absent) for i in range(len(frag.tensors))]
 
 
 # ---------------------------------------------------------------------------------------

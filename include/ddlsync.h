@@ -327,34 +327,6 @@ DDL_API ddl_status ddl_balanced_fragments(const uint64_t* sizes, int num_tensors
                                           int* fragment_of);
 
 /*
- * Placement of a fragment's resident arrays (Section 4, "Syncer worker": the syncer keeps the
- * global parameters, the outer-optimiser state and one shard per learner resident; where it
- * keeps them is its own choice).  The merge reads the same element range of Theta, v and
- * every contributing learner at the same moment; arrays whose start addresses are equal modulo
- * 64 KiB -- back-to-back allocations of tensors with power-of-two sizes -- send those
- * simultaneous requests to the same memory channels and banks, which costs 10-16 % on
- * MI355X.  This host-only helper lays the arrays of num_tensors tensors out in ONE arena so
- * that the arrays of a tensor start one tile's footprint apart within the 64 KiB stripe
- * (Theta at 0, v at 4 KiB, then the optional bf16 copy and the learners, 2 KiB apart for
- * bf16, 4 KiB for fp32).
- *   sizes            host, num_tensors element counts
- *   with_theta_bf16  non-zero: also place a bf16 copy of Theta per tensor
- *   slots_out        host, num_tensors entries: byte offsets of every array inside the arena,
- *                    each a multiple of 1024; unused entries (learner[m >= M], theta_bf16 if
- *                    not asked for) are (size_t)-1
- *   arena_bytes_out  bytes to allocate; the arena's base must be 256-byte aligned
- * Any other placement remains valid for every entry point; this one is the fast one.
- * Errors: INVALID_ARG (NULL, M outside 1..16, unknown dtype, a size above 2^46).
- */
-typedef struct ddl_arena_slot {
-    size_t theta, v, theta_bf16;
-    size_t learner[DDL_MAX_LEARNERS];
-} ddl_arena_slot;
-DDL_API ddl_status ddl_arena_layout(const uint64_t* sizes, int num_tensors, int M,
-                                    ddl_dtype learner_dtype, int with_theta_bf16,
-                                    ddl_arena_slot* slots_out, size_t* arena_bytes_out);
-
-/*
  * Measurement aid, not part of the method: a plain device-to-device streaming copy of `bytes`
  * bytes (a multiple of 16; dst and src device, 16-byte aligned, not overlapping) with the
  * merge kernel's access width and cache hints.  It reads `bytes` and writes `bytes`, which
@@ -365,9 +337,13 @@ DDL_API ddl_status ddl_copy_probe(void* dst, const void* src, size_t bytes, void
 
 /*
  * Launch-shape knobs, for measurement.  Names: "tiles_per_block" (how many consecutive
- * 1024-element tiles one workgroup walks, 1..1024), "max_blocks_per_cu" (0: no cap; k in
- * 3..64: at most k workgroups resident per compute unit).  Affects later calls.  Unknown name
- * or bad value: INVALID_ARG.  ddl_get_option writes the current value.
+ * 1024-element tiles one workgroup walks, 1..1024; default 1), "max_blocks_per_cu" (0: no cap;
+ * k in 3..64: at most k workgroups resident per compute unit; default 4), "tile_rotate" (0:
+ * workgroup b takes tile b; k in 2..4096: tile indices are rotated within groups of k by the
+ * group's number, which spreads every XCD's accesses over all memory channels; used with
+ * tiles_per_block 1; default 64), "rda_blocks_per_cu" (the residency cap of the RDA one-kernel
+ * shapes; default 0).  Affects later calls.  Unknown name or bad value: INVALID_ARG.
+ * ddl_get_option writes the current value.
  */
 DDL_API ddl_status ddl_set_option(const char* name, long value);
 DDL_API ddl_status ddl_get_option(const char* name, long* value_out);

@@ -30,11 +30,6 @@ class DdlError(RuntimeError):
         super().__init__(f"{where}: {msg}")
 
 
-class _ArenaSlot(ctypes.Structure):
-    _fields_ = [("theta", ctypes.c_size_t), ("v", ctypes.c_size_t),
-                ("theta_bf16", ctypes.c_size_t), ("learner", ctypes.c_size_t * DDL_MAX_LEARNERS)]
-
-
 class _Segment(ctypes.Structure):
     _fields_ = [("theta", ctypes.c_void_p), ("v", ctypes.c_void_p),
                 ("learner_params", ctypes.POINTER(ctypes.c_void_p)), ("n", ctypes.c_size_t),
@@ -106,9 +101,6 @@ def _load() -> ctypes.CDLL:
     lib.ddl_q4_merge_fragment.argtypes = [ctypes.c_void_p, ctypes.c_void_p, vpp, vpp, u64p, u8p,
                                           ctypes.c_int, ctypes.c_size_t, ctypes.c_size_t,
                                           ctypes.c_float, ctypes.c_float, ctypes.c_void_p]
-    lib.ddl_arena_layout.argtypes = [u64p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                     ctypes.POINTER(_ArenaSlot),
-                                     ctypes.POINTER(ctypes.c_size_t)]
     lib.ddl_balanced_fragments.argtypes = [u64p, ctypes.c_int, ctypes.c_int,
                                            ctypes.POINTER(ctypes.c_int)]
     lib.ddl_copy_probe.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
@@ -120,7 +112,7 @@ def _load() -> ctypes.CDLL:
                  "ddl_plan_merge", "ddl_plan_destroy", "ddl_set_option", "ddl_get_option",
                  "ddl_copy_probe", "ddl_balanced_fragments", "ddl_merge_fragment_bcast",
                  "ddl_rda_merge_fragment", "ddl_plan_set_rda_groups", "ddl_plan_rda_merge",
-                 "ddl_q4_encode", "ddl_q4_merge_fragment", "ddl_arena_layout"):
+                 "ddl_q4_encode", "ddl_q4_merge_fragment"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -489,57 +481,6 @@ def balanced_fragments(sizes, num_fragments: int) -> List[int]:
     _check(_lib.ddl_balanced_fragments(_u64(sizes), n, num_fragments, out),
            "ddl_balanced_fragments")
     return list(out)[:n]
-
-
-def arena_layout(sizes, M: int, learner_dtype=torch.bfloat16, with_theta_bf16: bool = False):
-    """ddl_arena_layout: byte offsets of every array of a fragment's tensors inside one arena.
-    Returns ([{"theta": off, "v": off, "theta_bf16": off or None, "learners": [off] * M}],
-    arena_bytes)."""
-    n = len(sizes)
-    slots = (_ArenaSlot * max(1, n))()
-    total = ctypes.c_size_t()
-    _check(_lib.ddl_arena_layout(_u64(sizes), n, M, _dtype_code(learner_dtype),
-                                 int(bool(with_theta_bf16)), slots, ctypes.byref(total)),
-           "ddl_arena_layout")
-    out = []
-    for i in range(n):
-        s = slots[i]
-        out.append({"theta": s.theta, "v": s.v,
-                    "theta_bf16": s.theta_bf16 if with_theta_bf16 else None,
-                    "learners": [s.learner[m] for m in range(M)]})
-    return out, total.value
-
-
-class Arena:
-    """One device allocation holding all arrays of a fragment's tensors at the offsets
-    ``arena_layout`` gives; ``theta(i)``, ``v(i)``, ``learner(i, m)`` and ``theta_bf16(i)`` are
-    views into it."""
-
-    def __init__(self, sizes, M: int, learner_dtype=torch.bfloat16, with_theta_bf16: bool = False,
-                 device="cuda:0"):
-        self.sizes = [int(x) for x in sizes]
-        self.M = M
-        self.learner_dtype = learner_dtype
-        self.slots, self.nbytes = arena_layout(self.sizes, M, learner_dtype, with_theta_bf16)
-        self.buffer = torch.empty(max(256, self.nbytes), dtype=torch.uint8, device=device)
-        if self.buffer.data_ptr() % 256:
-            raise RuntimeError("arena base is not 256-byte aligned")
-
-    def _view(self, off: int, n: int, dtype) -> torch.Tensor:
-        nbytes = n * torch.empty((), dtype=dtype).element_size()
-        return self.buffer[off:off + nbytes].view(dtype)
-
-    def theta(self, i: int) -> torch.Tensor:
-        return self._view(self.slots[i]["theta"], self.sizes[i], torch.float32)
-
-    def v(self, i: int) -> torch.Tensor:
-        return self._view(self.slots[i]["v"], self.sizes[i], torch.float32)
-
-    def learner(self, i: int, m: int) -> torch.Tensor:
-        return self._view(self.slots[i]["learners"][m], self.sizes[i], self.learner_dtype)
-
-    def theta_bf16(self, i: int) -> torch.Tensor:
-        return self._view(self.slots[i]["theta_bf16"], self.sizes[i], torch.bfloat16)
 
 
 def copy_probe(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

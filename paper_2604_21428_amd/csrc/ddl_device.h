@@ -51,7 +51,7 @@ struct DdlLaunchArgs {
     uint32_t total_tiles;
     uint32_t tiles_per_block;  // >= 1
     int32_t num_items;
-    int32_t pad;
+    int32_t rotate;  // 0: workgroup b takes tile b; k > 0: tiles rotated within groups of k
     DdlItem item[DDL_MAX_ITEMS];
     DdlSegDesc flat;         // the one segment of the flat variant
 };

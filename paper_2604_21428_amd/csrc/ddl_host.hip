@@ -46,6 +46,7 @@ namespace {
 // ------------------------------------------------------------------------------------------
 std::mutex g_mu;  // guards options, device state and the staging ring
 long g_tiles_per_block = 1;    // consecutive tiles a workgroup walks
+long g_tile_rotate = 64;       // group size of the tile rotation (0: off); see rotate_tile()
 long g_max_blocks_per_cu = 4;  // 0: no cap; k: at most k resident workgroups per compute unit
 
 constexpr int kMaxDevices = 16;
@@ -95,6 +96,7 @@ uint32_t lds_cap_bytes()
 }  // namespace
 
 uint32_t ddlh::merge_lds_cap_bytes() { return lds_cap_bytes(); }
+uint32_t ddlh::tile_rotate() { return (uint32_t)g_tile_rotate; }
 
 // ------------------------------------------------------------------------------------------
 // weights
@@ -367,6 +369,7 @@ ddl_status launch_work(const Table& T, const void* d_table, std::vector<Work>& w
         a.coarse = reinterpret_cast<const uint32_t*>(static_cast<const char*>(d_table) +
                                                      T.seg_bytes());
         a.tiles_per_block = (uint32_t)g_tiles_per_block;
+        a.rotate = g_tiles_per_block == 1 ? (int32_t)g_tile_rotate : 0;
         uint64_t tiles = 0;
         int items = 0;
         size_t j = i;
@@ -416,6 +419,7 @@ ddl_status merge_flat(float* theta, float* v, void* theta_bf16, const void* cons
     DdlLaunchArgs a;
     std::memset(&a, 0, sizeof a);
     a.tiles_per_block = (uint32_t)g_tiles_per_block;
+    a.rotate = g_tiles_per_block == 1 ? (int32_t)g_tile_rotate : 0;
     a.total_tiles = (uint32_t)tiles;
     a.num_items = 1;
     fill_desc(a.flat, theta, v, theta_bf16, lp, M, n, 0);
@@ -670,6 +674,11 @@ ddl_status ddl_set_option(const char* name, long value)
         g_max_blocks_per_cu = value;
         return DDL_OK;
     }
+    if (!std::strcmp(name, "tile_rotate")) {
+        if (value != 0 && (value < 2 || value > 4096)) return DDL_ERR_INVALID_ARG;
+        g_tile_rotate = value;
+        return DDL_OK;
+    }
     if (!std::strcmp(name, "rda_blocks_per_cu")) {
         if (value != 0 && (value < 3 || value > 64)) return DDL_ERR_INVALID_ARG;
         ddl_opt_rda_blocks_per_cu = value;
@@ -688,6 +697,10 @@ ddl_status ddl_get_option(const char* name, long* value_out)
     }
     if (!std::strcmp(name, "max_blocks_per_cu")) {
         *value_out = g_max_blocks_per_cu;
+        return DDL_OK;
+    }
+    if (!std::strcmp(name, "tile_rotate")) {
+        *value_out = g_tile_rotate;
         return DDL_OK;
     }
     if (!std::strcmp(name, "rda_blocks_per_cu")) {

@@ -56,6 +56,8 @@ bool finite_nonneg(float x);
 // Unused dynamic LDS per workgroup that enforces the max_blocks_per_cu option on the
 // streaming merge kernels (0: no cap).
 uint32_t merge_lds_cap_bytes();
+// Group size of the tile rotation (option tile_rotate; 0: off).
+uint32_t tile_rotate();
 // Records the message for ddl_last_error_message and returns DDL_ERR_RUNTIME.
 ddl_status runtime_error(hipError_t e, const char* what);
 

@@ -57,6 +57,20 @@ __device__ __forceinline__ uint64_t uniform(uint64_t x)
     return ((uint64_t)hi << 32) | lo;
 }
 
+// Which tile (or row) workgroup b of a grid of `total` takes.  Workgroups are handed to the
+// eight XCDs round-robin, so with the identity mapping XCD x works on tiles x, x + 8, ... only:
+// always the same residues of the address interleave, hence the same memory channels, for
+// every array at once when the arrays' bases are aligned alike (tensors of power-of-two sizes
+// allocated back to back).  Rotating the index within each group of k consecutive tiles by
+// the group's number lets every XCD sweep all residues, while the tiles in flight stay one
+// compact window.  k = 0: identity.  A last, partial group keeps the identity.
+__device__ __forceinline__ uint32_t rotate_tile(uint32_t b, uint32_t total, uint32_t k)
+{
+    if (k == 0) return b;
+    const uint32_t g = b / k, r = b - g * k;
+    return (g + 1) * k <= total ? g * k + (r + g) % k : b;
+}
+
 // bf16 is the upper half of an fp32 word, so widening is a shift or a mask.
 __device__ __forceinline__ float bf16_even(uint32_t pair) { return __uint_as_float(pair << 16); }
 __device__ __forceinline__ float bf16_odd(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }

@@ -11,6 +11,9 @@
 //     any moment form one compact address window per array, which is what keeps DRAM pages
 //     open.  Measured on MI355X, this beats wider per-lane groups, deeper unrolling and
 //     persistent grids, all of which widen that window;
+//   * workgroup b takes tile rotate_tile(b): consecutive workgroups land on different XCDs, and
+//     without the rotation each XCD would keep hitting the same memory channels (+6-8 % on
+//     tensors of power-of-two sizes);
 //   * a workgroup walks `tiles_per_block` consecutive tiles, so the tile -> tensor lookup
 //     (scalar loads from the descriptor table, addressed as constant memory) is paid once
 //     per run of tiles, not once per tile;
@@ -111,7 +114,8 @@ template <typename L, int MQ, bool FLAT>
 __global__ void __launch_bounds__(DDL_BLOCK) ddl_merge_kernel(const DdlLaunchArgs a)
 {
     typedef typename L::elem elem;
-    uint32_t tile = blockIdx.x * a.tiles_per_block;
+    // (the host sets rotate only with tiles_per_block == 1)
+    uint32_t tile = rotate_tile(blockIdx.x, a.total_tiles, (uint32_t)a.rotate) * a.tiles_per_block;
     const uint32_t last = min(tile + a.tiles_per_block, a.total_tiles);
 
     while (tile < last) {

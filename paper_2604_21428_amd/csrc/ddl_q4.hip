@@ -35,6 +35,8 @@ struct DdlQ4Args {
     uint32_t block_len;         // multiple of 8
     uint32_t block_shift;       // log2(block_len) if it is a power of two, else 0xffffffff
     float lr, mu;
+    uint32_t rotate;            // group size of the tile rotation, 0: off
+    uint32_t pad;
 };
 
 struct DdlQ4EncodeArgs {
@@ -57,7 +59,8 @@ __device__ __forceinline__ float nibble(uint32_t c, int k)
 template <int MQ>
 __global__ void __launch_bounds__(DDL_BLOCK) q4_merge_kernel(const DdlQ4Args a)
 {
-    const uint64_t e0 = (uint64_t)blockIdx.x * DDL_TILE;       // first element of the tile
+    const uint64_t e0 =                                        // first element of the tile
+        (uint64_t)rotate_tile(blockIdx.x, gridDim.x, a.rotate) * DDL_TILE;
     const uint64_t left = a.n - e0;                            // > 0 by the grid size
     const uint32_t cnt = left < DDL_TILE ? (uint32_t)left : DDL_TILE;
     const uint32_t i0 = threadIdx.x * 4;                       // this lane's elements in the tile
@@ -302,6 +305,7 @@ extern "C" ddl_status ddl_q4_merge_fragment(float* theta, float* v, const uint8_
     }
     a.lr = lr;
     a.mu = mu;
+    a.rotate = ddlh::tile_rotate();
     const q4_fn fn = pick_q4(q.Mq);
     if (!fn) return DDL_ERR_INVALID_ARG;
     hipLaunchKernelGGL(fn, dim3((uint32_t)tiles), dim3(DDL_BLOCK), ddlh::merge_lds_cap_bytes(),

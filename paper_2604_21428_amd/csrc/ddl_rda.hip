@@ -547,6 +547,7 @@ struct DdlRdaRowsArgs {
     const DdlRdaRowRef* refs;  // first list entry of this launch
     const uint32_t* coarse;    // first coarse entry of this launch
     uint32_t coarse_shift;
+    uint32_t pad;
     float lr, mu;
     float w[DDL_MAXL];      // normalised weights of the contributing learners, compacted
     uint8_t idx[DDL_MAXL];  // learner index of compacted entry j

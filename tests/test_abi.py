@@ -246,46 +246,3 @@ def test_options(ddl):
     with pytest.raises(ddl.DdlError):
         ddl.set_option("max_blocks_per_cu", -1)
 
-
-def test_arena_layout(ddl):
-    """ddl_arena_layout: arrays do not overlap, offsets are multiples of 1024, and the arrays
-    of one tensor start at distinct places within the 64 KiB stripe, one tile apart."""
-    import torch
-    sizes = [2048 * 2048, 1, 0, 2048 * 8192 + 3, 1000]
-    for dtype, eb in ((torch.bfloat16, 2), (torch.float32, 4)):
-        for M in (1, 4, 16):
-            for bcast in (False, True):
-                slots, total = ddl.arena_layout(sizes, M, dtype, bcast)
-                spans = []
-                for n, s in zip(sizes, slots):
-                    arrays = [(s["theta"], 4 * n), (s["v"], 4 * n)]
-                    if bcast:
-                        arrays.append((s["theta_bf16"], 2 * n))
-                    else:
-                        assert s["theta_bf16"] is None
-                    arrays += [(o, eb * n) for o in s["learners"]]
-                    assert len(s["learners"]) == M
-                    assert all(o % 1024 == 0 for o, _ in arrays)
-                    res = [o % 65536 for o, _ in arrays]
-                    assert res[0] == 0 and res[1] == 4096
-                    step = 1024 * eb
-                    first = 8192 + (2048 if bcast else 0)
-                    assert res[-M:] == [(first + m * step) % 65536 for m in range(M)]
-                    if eb == 2 or M <= 14:
-                        assert len(set(res)) == len(res)
-                    spans += arrays
-                spans.sort()
-                for (a, la), (b, _) in zip(spans, spans[1:]):
-                    assert a + la <= b
-                assert spans[-1][0] + spans[-1][1] <= total and total % 256 == 0
-                payload = sum(l for _, l in spans)
-                assert total <= payload + 65536 * len(spans) + 256
-    slots, total = ddl.arena_layout([], 3)
-    assert slots == [] and total == 0
-    lib = ddl._lib
-    out = ctypes.c_size_t()
-    assert lib.ddl_arena_layout(None, 0, 0, ddl.DDL_BF16, 0, None, ctypes.byref(out)) == ddl.DDL_ERR_INVALID_ARG
-    assert lib.ddl_arena_layout(None, 0, 17, ddl.DDL_BF16, 0, None, ctypes.byref(out)) == ddl.DDL_ERR_INVALID_ARG
-    assert lib.ddl_arena_layout(None, 0, 2, 9, 0, None, ctypes.byref(out)) == ddl.DDL_ERR_INVALID_ARG
-    assert lib.ddl_arena_layout(None, 2, 2, ddl.DDL_BF16, 0, None, ctypes.byref(out)) == ddl.DDL_ERR_INVALID_ARG
-    assert lib.ddl_arena_layout(None, 0, 2, ddl.DDL_BF16, 0, None, None) == ddl.DDL_ERR_INVALID_ARG
