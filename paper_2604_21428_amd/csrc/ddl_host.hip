@@ -640,7 +640,10 @@ ddl_status ddl_plan_destroy(ddl_plan* plan)
     return st;
 }
 
-int ddl_plan_num_fragments(const ddl_plan* plan) { return plan ? (int)plan->table.frags.size() : 0; }
+int ddl_plan_num_fragments(const ddl_plan* plan)
+{
+    return plan ? (int)plan->table.frags.size() : 0;
+}
 
 size_t ddl_plan_num_elements(const ddl_plan* plan) { return plan ? (size_t)plan->table.elems : 0; }
 

@@ -49,7 +49,10 @@ __device__ __forceinline__ void st(uint64_t base, uint32_t index, T x)
 // Values that are the same for every lane of a workgroup (tile geometry, base addresses) are
 // moved to scalar registers explicitly, so that sixteen 64-bit learner addresses do not sit
 // in vector registers of every lane.
-__device__ __forceinline__ uint32_t uniform(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
+__device__ __forceinline__ uint32_t uniform(uint32_t x)
+{
+    return __builtin_amdgcn_readfirstlane(x);
+}
 __device__ __forceinline__ uint64_t uniform(uint64_t x)
 {
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
@@ -73,7 +76,10 @@ __device__ __forceinline__ uint32_t rotate_tile(uint32_t b, uint32_t total, uint
 
 // bf16 is the upper half of an fp32 word, so widening is a shift or a mask.
 __device__ __forceinline__ float bf16_even(uint32_t pair) { return __uint_as_float(pair << 16); }
-__device__ __forceinline__ float bf16_odd(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }
+__device__ __forceinline__ float bf16_odd(uint32_t pair)
+{
+    return __uint_as_float(pair & 0xffff0000u);
+}
 
 // Learner element types: `raw` is the register image of the four elements a lane loads.
 struct LearnerF32 {

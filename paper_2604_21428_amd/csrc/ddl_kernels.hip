@@ -200,7 +200,8 @@ __global__ void __launch_bounds__(DDL_BLOCK) ddl_merge_kernel(const DdlLaunchArg
 
 // Plain streaming copy, 16 bytes per lane, one group per lane, same cache hints as the merge
 // kernel: the yardstick for what this GPU's HBM sustains and for scaling profiler counters.
-__global__ void __launch_bounds__(DDL_BLOCK) ddl_copy_kernel(uint64_t dst, uint64_t src, uint64_t n16)
+__global__ void __launch_bounds__(DDL_BLOCK) ddl_copy_kernel(uint64_t dst, uint64_t src,
+                                                             uint64_t n16)
 {
     const uint64_t base = (uint64_t)blockIdx.x * DDL_BLOCK;
     if (base + threadIdx.x < n16) {

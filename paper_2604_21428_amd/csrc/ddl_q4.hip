@@ -105,7 +105,8 @@ __global__ void __launch_bounds__(DDL_BLOCK) q4_merge_kernel(const DdlQ4Args a)
             float delta = 0.0f;
 #pragma unroll
             for (int j = 0; j < MQ; ++j) {
-                const uint32_t byte = *(reinterpret_cast<const DDL_GLOBAL uint8_t*>(a.codes[j]) + i / 2);
+                const uint32_t byte =
+                    *(reinterpret_cast<const DDL_GLOBAL uint8_t*>(a.codes[j]) + i / 2);
                 delta = fmaf(sw[j], nibble(byte, (int)(i & 1)), delta);
             }
             const float t = *(reinterpret_cast<const DDL_GLOBAL float*>(th) + e);
@@ -153,7 +154,8 @@ __global__ void __launch_bounds__(DDL_BLOCK) q4_encode_kernel(const DdlQ4EncodeA
             d[3] = t.w - x[3];
         } else {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) d[k] = e + k < len ? th[e + k] - L::widen1(lp[e + k]) : 0.0f;
+            for (int k = 0; k < 4; ++k)
+                d[k] = e + k < len ? th[e + k] - L::widen1(lp[e + k]) : 0.0f;
         }
     };
 
@@ -186,7 +188,8 @@ __global__ void __launch_bounds__(DDL_BLOCK) q4_encode_kernel(const DdlQ4EncodeA
         } else {  // the tensor's last, partial chunk: only the bytes that exist
             const uint32_t bytes = (len - c * 4 + 1) / 2;
             for (uint32_t k = 0; k < bytes; ++k)
-                *(reinterpret_cast<DDL_GLOBAL uint8_t*>(a.codes) + e / 2 + k) = (uint8_t)(word >> (8 * k));
+                *(reinterpret_cast<DDL_GLOBAL uint8_t*>(a.codes) + e / 2 + k) =
+                    (uint8_t)(word >> (8 * k));
         }
     }
 }
@@ -208,7 +211,10 @@ q4_fn pick_q4(int Mq)
 
 inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
-bool block_len_ok(size_t block_len) { return block_len >= 8 && block_len % 8 == 0 && block_len <= 0x40000000u; }
+bool block_len_ok(size_t block_len)
+{
+    return block_len >= 8 && block_len % 8 == 0 && block_len <= 0x40000000u;
+}
 
 }  // namespace
 

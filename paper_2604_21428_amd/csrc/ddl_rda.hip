@@ -200,7 +200,8 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_norms_kernel(const DdlRdaArgs a
 {
     __shared__ double lds[DDL_BLOCK];
     const uint32_t r = blockIdx.x;
-    const float* p1 = reinterpret_cast<const float*>(a.partial1) + (size_t)r * a.chunks_per_group * Mq;
+    const float* p1 =
+        reinterpret_cast<const float*>(a.partial1) + (size_t)r * a.chunks_per_group * Mq;
     float* coef = reinterpret_cast<float*>(a.coef) + (size_t)r * Mq;
     double R = 0.0;
     for (int j = 0; j < Mq; ++j) {
@@ -230,7 +231,8 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_dirsq_kernel(const DdlRdaArgs a
     chunk_range(a, blockIdx.x, begin, end, group);
     float c[MQ];
 #pragma unroll
-    for (int j = 0; j < MQ; ++j) c[j] = reinterpret_cast<const float*>(a.coef)[(size_t)group * MQ + j];
+    for (int j = 0; j < MQ; ++j)
+        c[j] = reinterpret_cast<const float*>(a.coef)[(size_t)group * MQ + j];
     float ss = 0.0f;
     sweep_chunk<L, MQ, false>(
         a, begin, end, false,
@@ -379,7 +381,8 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_group_kernel(const DdlRdaArgs a
             [&](const float (&d)[MQ], float t, float v, uint32_t e) {
                 const float delta = direction<MQ>(d, c);
                 const float v_new = fmaf(mu, v, delta);
-                *(reinterpret_cast<DDL_GLOBAL float*>(th) + e) = fmaf(-lr, fmaf(mu, v_new, delta), t);
+                *(reinterpret_cast<DDL_GLOBAL float*>(th) + e) =
+                    fmaf(-lr, fmaf(mu, v_new, delta), t);
                 *(reinterpret_cast<DDL_GLOBAL float*>(vv) + e) = v_new;
             });
     }
@@ -571,7 +574,8 @@ __global__ void __launch_bounds__(NTH) rda_rows_kernel(const DdlRdaRowsArgs a)
     }
     const DDL_CONST DdlRdaRowRef* ref = refs + lo;
     const DDL_CONST DdlSegDesc* sp =
-        reinterpret_cast<const DDL_CONST DdlSegDesc*>(reinterpret_cast<uint64_t>(a.segs)) + ref->seg;
+        reinterpret_cast<const DDL_CONST DdlSegDesc*>(reinterpret_cast<uint64_t>(a.segs)) +
+        ref->seg;
     const uint64_t glen = ref->group_len;
     const uint64_t n = sp->n;
     const uint64_t g0 = (uint64_t)(r - ref->row_begin) * glen;
@@ -817,7 +821,8 @@ extern "C" ddl_status ddl_rda_merge_fragment(float* theta, float* v,
     }
     Geometry g;
     if (!geometry(n, group_len, Mq, g)) return DDL_ERR_INVALID_ARG;
-    if (!workspace || !aligned(workspace, 256) || workspace_bytes < g.bytes) return DDL_ERR_INVALID_ARG;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < g.bytes)
+        return DDL_ERR_INVALID_ARG;
     r.push_back({(uintptr_t)workspace, (uintptr_t)workspace + g.bytes, true});
     std::sort(r.begin(), r.end(), [](const Range& x, const Range& y) { return x.lo < y.lo; });
     uintptr_t hi_any = 0, hi_out = 0;
