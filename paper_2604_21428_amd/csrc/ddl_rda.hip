@@ -90,14 +90,29 @@ __device__ __forceinline__ float block_sum(float x, float* lds /* NTH / 64 float
     return s;
 }
 
-// The same sum, delivered to every thread.
-template <int NTH = DDL_BLOCK>
-__device__ __forceinline__ float block_sum_all(float x, float* lds /* NTH / 64 + 1 floats */)
+// N sums at once, each delivered to every thread: lanes by butterfly, then the waves'
+// partial sums in sequence (a fixed order, the same in every thread).  Two barriers for all N.
+template <int NTH, int N>
+__device__ __forceinline__ void block_sum_all(float (&x)[N], float* lds /* NTH / 64 * N floats */)
 {
-    const float s = block_sum<NTH>(x, lds);
-    if (threadIdx.x == 0) lds[NTH / 64] = s;
+#pragma unroll
+    for (int j = 0; j < N; ++j)
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) x[j] += __shfl_xor(x[j], off, 64);
+    const int wave = threadIdx.x >> 6;
+    __syncthreads();  // lds may still be read from a previous call
+    if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+        for (int j = 0; j < N; ++j) lds[wave * N + j] = x[j];
+    }
     __syncthreads();
-    return lds[NTH / 64];
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        float s = 0.0f;
+#pragma unroll
+        for (int k = 0; k < NTH / 64; ++k) s += lds[k * N + j];
+        x[j] = s;
+    }
 }
 
 // Sum of count floats at p[k * stride], k < count, by the whole workgroup, in double and in a
@@ -302,7 +317,7 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_apply_kernel(const DdlRdaArgs a
 template <typename L, int MQ>
 __global__ void __launch_bounds__(DDL_BLOCK) rda_group_kernel(const DdlRdaArgs a)
 {
-    __shared__ float lds[DDL_BLOCK / 64 + 1];
+    __shared__ float lds[DDL_BLOCK / 64 * MQ];
     const uint64_t g0 = (uint64_t)blockIdx.x * a.group_len;
     const uint64_t g1 = a.n - g0 < a.group_len ? a.n : g0 + a.group_len;
 
@@ -327,9 +342,10 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_group_kernel(const DdlRdaArgs a
     }
     float c[MQ];
     float R = 0.0f;
+    block_sum_all<DDL_BLOCK, MQ>(ss, lds);
 #pragma unroll
     for (int j = 0; j < MQ; ++j) {
-        const float N = sqrtf(block_sum_all(ss[j], lds));
+        const float N = sqrtf(ss[j]);
         R = fmaf(a.w[j], N, R);
         c[j] = N > 0.0f ? a.w[j] / N : 0.0f;
     }
@@ -352,7 +368,9 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_group_kernel(const DdlRdaArgs a
                 uu = fmaf(u, u, uu);
             });
     }
-    const float U = sqrtf(block_sum_all(uu, lds));
+    float usum[1] = {uu};
+    block_sum_all<DDL_BLOCK, 1>(usum, lds);
+    const float U = sqrtf(usum[0]);
     const float scale = U > 0.0f ? R / U : 0.0f;
 #pragma unroll
     for (int j = 0; j < MQ; ++j) c[j] *= scale;
@@ -404,7 +422,7 @@ __device__ __forceinline__ void launder(u32x4& r)
 template <typename L, int MQ, int K, int NTH>
 __device__ __forceinline__ void rda_row_body(uint64_t th, uint64_t vv, const uint64_t (&lp)[MQ],
                                              const float (&w)[MQ], uint32_t nvec, float lr,
-                                             float mu, float* lds /* NTH / 64 + 1 floats */)
+                                             float mu, float* lds /* NTH / 64 * MQ floats */)
 {
     typename L::raw raw[K][MQ];
     f32x4 T[K];
@@ -454,9 +472,10 @@ __device__ __forceinline__ void rda_row_body(uint64_t th, uint64_t vv, const uin
     }
     float c[MQ];
     float R = 0.0f;
+    block_sum_all<NTH, MQ>(ss, lds);
 #pragma unroll
     for (int j = 0; j < MQ; ++j) {
-        const float N = sqrtf(block_sum_all<NTH>(ss[j], lds));
+        const float N = sqrtf(ss[j]);
         R = fmaf(w[j], N, R);
         c[j] = N > 0.0f ? w[j] / N : 0.0f;
     }
@@ -476,7 +495,9 @@ __device__ __forceinline__ void rda_row_body(uint64_t th, uint64_t vv, const uin
             uu = fmaf(x, x, uu);
         }
     }
-    const float U = sqrtf(block_sum_all<NTH>(uu, lds));
+    float usum[1] = {uu};
+    block_sum_all<NTH, 1>(usum, lds);
+    const float U = sqrtf(usum[0]);
     const float scale = U > 0.0f ? R / U : 0.0f;
 #pragma unroll
     for (int j = 0; j < MQ; ++j) c[j] *= scale;
@@ -519,7 +540,7 @@ __device__ __forceinline__ void rda_row_body(uint64_t th, uint64_t vv, const uin
 template <typename L, int MQ, int K, int NTH>
 __global__ void __launch_bounds__(NTH) rda_row_kernel(const DdlRdaArgs a)
 {
-    __shared__ float lds[NTH / 64 + 1];
+    __shared__ float lds[NTH / 64 * MQ];
     typedef typename L::elem elem;
     const uint64_t g0 = (uint64_t)blockIdx.x * a.group_len;
     const uint64_t g1 = a.n - g0 < a.group_len ? a.n : g0 + a.group_len;
@@ -559,7 +580,7 @@ struct DdlRdaRowsArgs {
 template <typename L, int MQ, int K, int NTH>
 __global__ void __launch_bounds__(NTH) rda_rows_kernel(const DdlRdaRowsArgs a)
 {
-    __shared__ float lds[NTH / 64 + 1];
+    __shared__ float lds[NTH / 64 * MQ];
     typedef typename L::elem elem;
     const uint32_t r = blockIdx.x;
     const DDL_CONST DdlRdaRowRef* refs =
