@@ -232,3 +232,42 @@ def test_launch_shape_options(ddl, tpb, cap):
         ddl.set_option("tiles_per_block", 0)
     with pytest.raises(ddl.DdlError):
         ddl.set_option("no_such_option", 1)
+
+
+@pytest.mark.parametrize("rot", [0, 2, 3, 7, 64, 100, 4096])
+def test_tile_rotation_values(ddl, rot):
+    """Any group size of the tile rotation visits every tile exactly once: whole groups, a
+    partial last group, grids smaller than one group, several fragments in one launch."""
+    old = ddl.get_option("tile_rotate")
+    try:
+        ddl.set_option("tile_rotate", rot)
+        assert ddl.get_option("tile_rotate") == rot
+        for name in ("dense_block", "moe", "streaming_model"):
+            wl = ddl_synth.reduced(name)
+            data, refs = _materialise(wl)
+            ddl.merge_batch([_fragment(ddl, f, segs) for f, segs in zip(wl.fragments, data)])
+            torch.cuda.synchronize()
+            _check_all(wl, data, refs)
+        k = max(rot, 1)
+        for tiles, extra in ((k, 0), (k + 1, 0), (3 * k, 5), (3 * k - 1, 1023), (1, 7)):
+            n = tiles * 1024 - (1024 - extra if extra else 0)
+            th, v, ls, tok, mask = random_problem(rot * 31 + tiles, n, 2, torch.bfloat16, DEV)
+            ref = oracle.merge_fragment(ddl_synth.to_host_array(th), ddl_synth.to_host_array(v),
+                                        [ddl_synth.to_host_array(x) for x in ls], tok, mask, 0.7, 0.9)
+            ddl.merge_fragment(th, v, ls, tok, mask, 0.7, 0.9)
+            enc = [ddl.q4_encode(th, x, 8) for x in ls]       # of the state after the merge
+            torch.cuda.synchronize()
+            check_segment(ddl_synth.SegmentData(th, v, ls), ref, f"rot {rot} n {n}")
+            ref4 = oracle.q4_merge_fragment(
+                ddl_synth.to_host_array(th), ddl_synth.to_host_array(v),
+                [c.cpu().numpy() for c, _ in enc], [ddl_synth.to_host_array(s) for _, s in enc],
+                tok, mask, 8, 0.7, 0.9)
+            ddl.q4_merge_fragment(th, v, [c for c, _ in enc], [s for _, s in enc], tok, mask, 8,
+                                  0.7, 0.9)
+            torch.cuda.synchronize()
+            check_segment(ddl_synth.SegmentData(th, v, ls), ref4, f"q4 rot {rot} n {n}")
+    finally:
+        ddl.set_option("tile_rotate", old)
+    for bad in (1, -1, 4097):
+        with pytest.raises(ddl.DdlError):
+            ddl.set_option("tile_rotate", bad)
