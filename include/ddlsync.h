@@ -300,8 +300,8 @@ DDL_API size_t ddl_plan_num_elements(const ddl_plan* plan);
  * ddl_plan_rda_merge        as ddl_plan_merge, with the RDA merge.  workspace: device scratch,
  *                           256-byte aligned, at least ddl_plan_rda_workspace_bytes(plan),
  *                           overwritten, not shared by calls that may overlap in time.  Only
- *                           enqueues kernels.  The optional theta_bf16 output of a segment is
- *                           not written by this call.
+ *                           enqueues kernels.  A segment's optional theta_bf16 receives the
+ *                           new Theta as bf16 in the same pass, as in ddl_plan_merge.
  * Errors as ddl_plan_merge; INVALID_ARG also if the groups were never set, num_segments does
  * not match the plan, or the workspace is NULL, misaligned or too small; ALIAS if the
  * workspace overlaps an array of a fragment that is due.  Theta and v are untouched on error.

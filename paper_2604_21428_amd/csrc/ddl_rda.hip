@@ -44,6 +44,7 @@
 
 struct DdlRdaArgs {
     uint64_t theta, v;          // device addresses
+    uint64_t theta_bf16;        // optional bf16 copy of the new Theta (0: none)
     uint64_t learner[DDL_MAXL]; // compacted: contributing learners only
     float w[DDL_MAXL];          // their normalised weights
     uint64_t n, group_len;
@@ -130,6 +131,14 @@ __device__ __forceinline__ double block_sum_strided(const float* p, uint32_t cou
         __syncthreads();
     }
     return lds[0];
+}
+
+// The new Theta of one group of four as bf16 (round to nearest even), for the broadcast copy.
+__device__ __forceinline__ u32x2 pack_bf16(const float (&t4)[4])
+{
+    const u32x2 p = {bf16_rne(t4[0]) | (bf16_rne(t4[1]) << 16),
+                     bf16_rne(t4[2]) | (bf16_rne(t4[3]) << 16)};
+    return p;
 }
 
 // Walks the chunk: F(d[MQ], theta, v, element index within the chunk, is the first argument
@@ -289,6 +298,7 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_apply_kernel(const DdlRdaArgs a
         c[j] = reinterpret_cast<const float*>(a.coef)[(size_t)group * MQ + j] * scale;
     const float lr = a.lr, mu = a.mu;
     const uint64_t th = a.theta + begin * 4, vv = a.v + begin * 4;
+    const uint64_t tb = a.theta_bf16 ? a.theta_bf16 + begin * 2 : 0;
     sweep_chunk<L, MQ, true>(
         a, begin, end, true,
         [&](const float (&d)[4][MQ], const f32x4& T, const f32x4& V, uint32_t g) {
@@ -304,12 +314,15 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_apply_kernel(const DdlRdaArgs a
             const f32x4 vn = {v4[0], v4[1], v4[2], v4[3]};
             st<f32x4>(th, g, tn);
             st<f32x4>(vv, g, vn);
+            if (tb) st<u32x2>(tb, g, pack_bf16(t4));
         },
         [&](const float (&d)[MQ], float t, float v, uint32_t e) {
             const float delta = direction<MQ>(d, c);
             const float v_new = fmaf(mu, v, delta);
-            *(reinterpret_cast<DDL_GLOBAL float*>(th) + e) = fmaf(-lr, fmaf(mu, v_new, delta), t);
+            const float t_new = fmaf(-lr, fmaf(mu, v_new, delta), t);
+            *(reinterpret_cast<DDL_GLOBAL float*>(th) + e) = t_new;
             *(reinterpret_cast<DDL_GLOBAL float*>(vv) + e) = v_new;
+            if (tb) *(reinterpret_cast<DDL_GLOBAL uint16_t*>(tb) + e) = (uint16_t)bf16_rne(t_new);
         });
 }
 
@@ -380,6 +393,7 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_group_kernel(const DdlRdaArgs a
     for (uint64_t begin = g0; begin < g1; begin += DDL_RDA_CHUNK) {
         const uint64_t end = begin + DDL_RDA_CHUNK < g1 ? begin + DDL_RDA_CHUNK : g1;
         const uint64_t th = a.theta + begin * 4, vv = a.v + begin * 4;
+        const uint64_t tb = a.theta_bf16 ? a.theta_bf16 + begin * 2 : 0;
         sweep_chunk<L, MQ, false>(
             a, begin, end, true,
             [&](const float (&d)[4][MQ], const f32x4& T, const f32x4& V, uint32_t g) {
@@ -395,13 +409,16 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_group_kernel(const DdlRdaArgs a
                 const f32x4 vn = {v4[0], v4[1], v4[2], v4[3]};
                 st<f32x4>(th, g, tn);
                 st<f32x4>(vv, g, vn);
+                if (tb) st<u32x2>(tb, g, pack_bf16(t4));
             },
             [&](const float (&d)[MQ], float t, float v, uint32_t e) {
                 const float delta = direction<MQ>(d, c);
                 const float v_new = fmaf(mu, v, delta);
-                *(reinterpret_cast<DDL_GLOBAL float*>(th) + e) =
-                    fmaf(-lr, fmaf(mu, v_new, delta), t);
+                const float t_new = fmaf(-lr, fmaf(mu, v_new, delta), t);
+                *(reinterpret_cast<DDL_GLOBAL float*>(th) + e) = t_new;
                 *(reinterpret_cast<DDL_GLOBAL float*>(vv) + e) = v_new;
+                if (tb)
+                    *(reinterpret_cast<DDL_GLOBAL uint16_t*>(tb) + e) = (uint16_t)bf16_rne(t_new);
             });
     }
 }
@@ -418,9 +435,11 @@ __device__ __forceinline__ void launder(u32x4& r)
 // Launch shape (a'), for groups of at most K * 4 * NTH elements on the aligned path: the
 // workgroup loads its whole group ONCE into registers (learner values stay packed as loaded)
 // and makes the three sweeps over the registers.  HBM traffic equals that of direct averaging.
-// th, vv, lp: addresses of the group's first element; nvec: its length in groups of four.
+// th, vv, tb, lp: addresses of the group's first element (tb: the optional bf16 copy of the new
+// Theta, 0 if none); nvec: its length in groups of four.
 template <typename L, int MQ, int K, int NTH>
-__device__ __forceinline__ void rda_row_body(uint64_t th, uint64_t vv, const uint64_t (&lp)[MQ],
+__device__ __forceinline__ void rda_row_body(uint64_t th, uint64_t vv, uint64_t tb,
+                                             const uint64_t (&lp)[MQ],
                                              const float (&w)[MQ], uint32_t nvec, float lr,
                                              float mu, float* lds /* NTH / 64 * MQ floats */)
 {
@@ -532,6 +551,7 @@ __device__ __forceinline__ void rda_row_body(uint64_t th, uint64_t vv, const uin
             const f32x4 vn = {v4[0], v4[1], v4[2], v4[3]};
             st<f32x4>(th, g, tn);
             st<f32x4>(vv, g, vn);
+            if (tb) st<u32x2>(tb, g, pack_bf16(t4));
         }
     }
 }
@@ -552,7 +572,9 @@ __global__ void __launch_bounds__(NTH) rda_row_kernel(const DdlRdaArgs a)
         lp[j] = a.learner[j] + g0 * sizeof(elem);
         w[j] = a.w[j];
     }
-    rda_row_body<L, MQ, K, NTH>(a.theta + g0 * 4, a.v + g0 * 4, lp, w, nvec, a.lr, a.mu, lds);
+    rda_row_body<L, MQ, K, NTH>(a.theta + g0 * 4, a.v + g0 * 4,
+                                a.theta_bf16 ? a.theta_bf16 + g0 * 2 : 0, lp, w, nvec, a.lr, a.mu,
+                                lds);
 }
 
 // Many tensors of one fragment in one launch: workgroup b takes row b of the concatenation
@@ -604,6 +626,8 @@ __global__ void __launch_bounds__(NTH) rda_rows_kernel(const DdlRdaRowsArgs a)
     const uint32_t nvec = uniform((uint32_t)(g1 - g0) / 4);
     const uint64_t th = uniform(reinterpret_cast<uint64_t>(sp->theta) + g0 * 4);
     const uint64_t vv = uniform(reinterpret_cast<uint64_t>(sp->v) + g0 * 4);
+    const uint64_t tb0 = reinterpret_cast<uint64_t>(sp->theta_bf16);
+    const uint64_t tb = uniform(tb0 ? tb0 + g0 * 2 : 0);
     uint64_t lp[MQ];
     float w[MQ];
 #pragma unroll
@@ -611,7 +635,7 @@ __global__ void __launch_bounds__(NTH) rda_rows_kernel(const DdlRdaRowsArgs a)
         lp[j] = uniform(reinterpret_cast<uint64_t>(sp->learner[a.idx[j]]) + g0 * sizeof(elem));
         w[j] = a.w[j];
     }
-    rda_row_body<L, MQ, K, NTH>(th, vv, lp, w, nvec, a.lr, a.mu, lds);
+    rda_row_body<L, MQ, K, NTH>(th, vv, tb, lp, w, nvec, a.lr, a.mu, lds);
 }
 
 // Registers the row kernel keeps per lane: K groups of (packed learners + Theta + v), plus
@@ -1033,7 +1057,8 @@ extern "C" ddl_status ddl_plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, 
         const size_t b = f.dt == DDL_BF16 ? 2 : 4;
         for (uint32_t d = f.seg_begin; d < f.seg_begin + f.num_segs; ++d) {
             const DdlSegDesc& sd = T.segs[d];
-            bool hit = hits_workspace(sd.theta, 4 * sd.n) || hits_workspace(sd.v, 4 * sd.n);
+            bool hit = hits_workspace(sd.theta, 4 * sd.n) || hits_workspace(sd.v, 4 * sd.n) ||
+                       hits_workspace(sd.theta_bf16, 2 * sd.n);
             for (int j = 0; j < wk.q.Mq; ++j)
                 hit = hit || hits_workspace(sd.learner[wk.q.idx[j]], b * sd.n);
             if (hit) return DDL_ERR_ALIAS;
@@ -1054,11 +1079,13 @@ extern "C" ddl_status ddl_plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, 
         std::memset(&a, 0, sizeof a);
         a.theta = (uint64_t)(uintptr_t)sd.theta;
         a.v = (uint64_t)(uintptr_t)sd.v;
+        a.theta_bf16 = (uint64_t)(uintptr_t)sd.theta_bf16;
         a.n = sd.n;
         a.group_len = R.group_len[d];
         a.lr = wk.lr;
         a.mu = wk.mu;
-        bool vec_ok = aligned(sd.theta, 16) && aligned(sd.v, 16) && a.group_len % 4 == 0;
+        bool vec_ok = aligned(sd.theta, 16) && aligned(sd.v, 16) && aligned(sd.theta_bf16, 8) &&
+                      a.group_len % 4 == 0;
         for (int j = 0; j < wk.q.Mq; ++j) {
             const void* p = sd.learner[wk.q.idx[j]];
             vec_ok = vec_ok && aligned(p, 16);

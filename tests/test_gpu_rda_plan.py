@@ -65,9 +65,10 @@ SHAPES = [(600, 1024), (5, 64), (300, 2048), (0, 16), (130, 4096), (64, 3000), (
           (40, 14336), (3, 20000), (7, 1001), (33, 16384), (50, 0), (9, 1408), (1, 4)]
 
 
+@pytest.mark.parametrize("bcast", [False, True], ids=["plain", "bcast"])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
 @pytest.mark.parametrize("M,present", [(3, 3), (4, 3), (8, 6), (16, 11), (16, 16)])
-def test_all_row_classes_in_one_fragment(ddl, dtype, M, present):
+def test_all_row_classes_in_one_fragment(ddl, dtype, M, present, bcast):
     rng = np.random.default_rng(M * 100 + present)
     mask = np.zeros(M, dtype=np.int64)
     mask[rng.choice(M, size=present, replace=False)] = 1
@@ -86,7 +87,11 @@ def test_all_row_classes_in_one_fragment(ddl, dtype, M, present):
                 tokens, list(mask), g if g else n, 0.7, 0.9))
         else:
             refs.append(None)
-        segs.append((theta, v, learners))
+        if bcast:      # the bf16 copy of the new Theta, written in the same pass
+            segs.append((theta, v, learners,
+                         torch.full((n,), float("nan"), dtype=torch.bfloat16, device=DEV)))
+        else:
+            segs.append((theta, v, learners))
         groups.append(g)
     plan = ddl.Plan([ddl.Fragment(segs, M=M, learner_dtype=dtype)])
     plan.set_rda_groups(groups)
@@ -94,11 +99,15 @@ def test_all_row_classes_in_one_fragment(ddl, dtype, M, present):
     print(f"plan RDA classes M={M} present={present} {dtype}", flush=True)
     plan.rda_merge([(0, tokens, list(mask), 0.7, 0.9)], ws)
     torch.cuda.synchronize()
-    for k, ((theta, v, _), ref) in enumerate(zip(segs, refs)):
+    for k, (seg, ref) in enumerate(zip(segs, refs)):
         if ref is None:
             continue
+        theta, v = seg[0], seg[1]
         assert_parity(ddl_synth.to_host_array(theta), ref[0], f"shape {SHAPES[k]} theta")
         assert_parity(ddl_synth.to_host_array(v), ref[1], f"shape {SHAPES[k]} v")
+        if bcast:      # round-to-nearest-even of the fp32 Theta the kernel itself wrote
+            want = oracle.round_bf16(ddl_synth.to_host_array(theta))
+            assert np.array_equal(ddl_synth.to_host_array(seg[3]), want), f"shape {SHAPES[k]} bf16"
     plan.destroy()
 
 
