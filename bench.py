@@ -267,7 +267,7 @@ def main():
             torch.cuda.empty_cache()
             copies.append((data, "q4", calls))
         elif args.merge == "rda" and args.api == "plan":
-            plan = ddl.Plan([ddl.Fragment([(s.theta, s.v, s.learners) for s in segs], M=f.M,
+            plan = ddl.Plan([ddl.Fragment([(s.theta, s.v, s.learners, s.bcast) for s in segs], M=f.M,
                                           learner_dtype=dt[f.learner_dtype])
                              for f, segs in zip(wl.fragments, data)])
             plan.set_rda_groups([t.shape[-1] if args.rda_group == "row" else 0
