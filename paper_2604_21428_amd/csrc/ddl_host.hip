@@ -369,7 +369,7 @@ ddl_status launch_work(const Table& T, const void* d_table, std::vector<Work>& w
         a.coarse = reinterpret_cast<const uint32_t*>(static_cast<const char*>(d_table) +
                                                      T.seg_bytes());
         a.tiles_per_block = (uint32_t)g_tiles_per_block;
-        a.rotate = g_tiles_per_block == 1 ? (int32_t)g_tile_rotate : 0;
+        a.rotate = (int32_t)g_tile_rotate;
         uint64_t tiles = 0;
         int items = 0;
         size_t j = i;
@@ -419,7 +419,7 @@ ddl_status merge_flat(float* theta, float* v, void* theta_bf16, const void* cons
     DdlLaunchArgs a;
     std::memset(&a, 0, sizeof a);
     a.tiles_per_block = (uint32_t)g_tiles_per_block;
-    a.rotate = g_tiles_per_block == 1 ? (int32_t)g_tile_rotate : 0;
+    a.rotate = (int32_t)g_tile_rotate;
     a.total_tiles = (uint32_t)tiles;
     a.num_items = 1;
     fill_desc(a.flat, theta, v, theta_bf16, lp, M, n, 0);

@@ -114,8 +114,7 @@ template <typename L, int MQ, bool FLAT>
 __global__ void __launch_bounds__(DDL_BLOCK) ddl_merge_kernel(const DdlLaunchArgs a)
 {
     typedef typename L::elem elem;
-    // (the host sets rotate only with tiles_per_block == 1)
-    uint32_t tile = rotate_tile(blockIdx.x, a.total_tiles, (uint32_t)a.rotate) * a.tiles_per_block;
+    uint32_t tile = rotate_tile(blockIdx.x, gridDim.x, (uint32_t)a.rotate) * a.tiles_per_block;
     const uint32_t last = min(tile + a.tiles_per_block, a.total_tiles);
 
     while (tile < last) {
