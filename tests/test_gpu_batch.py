@@ -271,3 +271,51 @@ def test_tile_rotation_values(ddl, rot):
     for bad in (1, -1, 4097):
         with pytest.raises(ddl.DdlError):
             ddl.set_option("tile_rotate", bad)
+
+
+def _random_workload(seed):
+    """A seeded workload of random structure: 1-12 fragments of 0-30 tensors each, sizes from
+    empty over tile edges to a few hundred thousand elements, random M, quorum, dtype, lr, mu."""
+    rng = np.random.default_rng(seed)
+    frags = []
+    edge = [0, 1, 3, 4, 5, 1023, 1024, 1025, 2047, 2048, 4096, 4099]
+    for fi in range(int(rng.integers(1, 13))):
+        M = int(rng.integers(1, 17))
+        mask = [int(x) for x in rng.integers(0, 2, size=M)]
+        if not any(mask):
+            mask[int(rng.integers(0, M))] = 1
+        tokens = [int(x) for x in rng.integers(0, 1 << 40, size=M)]
+        if not any(t for t, q in zip(tokens, mask) if q):
+            tokens[mask.index(1)] = 7
+        tensors = []
+        for ti in range(int(rng.integers(0, 31))):
+            n = int(rng.choice(edge)) if rng.random() < 0.6 else int(rng.integers(1, 300000))
+            tensors.append(ddl_synth.TensorSpec(f"t{ti}", (n,)))
+        frags.append(ddl_synth.FragmentSpec(
+            fi, tensors, M=M, learner_dtype="bf16" if rng.random() < 0.7 else "f32",
+            token_counts=tokens, quorum_mask=mask, drift=[1e-3] * M,
+            lr=float(np.float32(rng.uniform(0, 1))), mu=float(np.float32(rng.uniform(0, 0.99)))))
+    order = [int(x) for x in rng.permutation(len(frags))]
+    return ddl_synth.Workload(f"random{seed}", frags, order)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_structures_batch_and_plan(ddl, seed):
+    wl = _random_workload(seed)
+    for api in ("batch", "plan"):
+        data, refs = _materialise(wl, absent="nan" if seed % 2 else "none")
+        print(f"random structure seed {seed} {api}: {len(wl.fragments)} fragments, "
+              f"{wl.num_segments} tensors, {wl.numel} elements", flush=True)
+        if api == "batch":
+            ddl.merge_batch([_fragment(ddl, f, segs) for f, segs in zip(wl.fragments, data)])
+        else:
+            plan = ddl.Plan([_fragment(ddl, f, segs, with_sync=False)
+                             for f, segs in zip(wl.fragments, data)])
+            half = len(wl.arrival_order) // 2
+            for part in (wl.arrival_order[:half], wl.arrival_order[half:]):
+                if part:
+                    plan.merge([(fi, wl.fragments[fi].token_counts, wl.fragments[fi].quorum_mask,
+                                 wl.fragments[fi].lr, wl.fragments[fi].mu) for fi in part])
+            plan.destroy()
+        torch.cuda.synchronize()
+        _check_all(wl, data, refs)
