@@ -38,7 +38,7 @@ MEASURED_TRAFFIC_BYTES_Q4_BLOCK128 = {
     "dense_block": 899419746,    # profiles/ddl_q4_kernels.txt
 }
 MEASURED_TRAFFIC_BYTES_RDA_ROWS = {
-    "dense_block": 1107347345,   # profiles/ddl_rda_kernels.txt
+    "dense_block": 1107403362,   # profiles/ddl_rda_kernels.txt
 }
 
 METRIC = "merged params/sec and achieved HBM GB/s (% of peak), merge+outer Nesterov"
