@@ -51,7 +51,10 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="dense_block",
                     choices=["tiny", "dense_block", "large_dense", "moe", "moe_stacked",
-                             "streaming_model"])
+                             "streaming_model", "small_fragments"])
+    ap.add_argument("--syncs-per-call", type=int, default=1,
+                    help="fragments handed to one ddl_plan_merge call (plan API, avg merge): "
+                         "the library covers up to eight fragments with one launch")
     ap.add_argument("--api", default="plan", choices=["plan", "batch", "tensor"],
                     help="resident plan (default); the one-shot ddl_merge_batch per fragment; "
                          "or, for --merge rda, one ddl_rda_merge_fragment call per tensor")
@@ -292,9 +295,11 @@ def main():
             plan = ddl.Plan([ddl.Fragment([(s.theta, s.v, s.learners, s.bcast) for s in segs], M=f.M,
                                           learner_dtype=dt[f.learner_dtype])
                              for f, segs in zip(wl.fragments, data)])
+            k = max(1, args.syncs_per_call)
+            groups = [wl.arrival_order[i:i + k] for i in range(0, len(wl.arrival_order), k)]
             calls = [plan.prepare([(fi, wl.fragments[fi].token_counts,
                                     wl.fragments[fi].quorum_mask, wl.fragments[fi].lr,
-                                    wl.fragments[fi].mu)]) for fi in wl.arrival_order]
+                                    wl.fragments[fi].mu) for fi in grp]) for grp in groups]
             copies.append((data, plan, calls))
         else:
             frs = [ddl.Fragment([(s.theta, s.v, s.learners, s.bcast) for s in segs], f.token_counts,
@@ -327,9 +332,11 @@ def main():
                 out.append((f.index, nb, lambda s=s, f=f, g=g, ws=ws: ddl.rda_merge_fragment(
                     s.theta, s.v, s.learners, f.token_counts, f.quorum_mask, g, f.lr, f.mu, ws)))
         elif plan is not None:
-            for fi, c in zip(wl.arrival_order, calls):
-                out.append((fi, wl.fragments[fi].numel * wl.fragments[fi].bytes_per_param,
-                            lambda c=c, plan=plan: plan.merge(c)))
+            k = max(1, args.syncs_per_call)
+            groups = [wl.arrival_order[i:i + k] for i in range(0, len(wl.arrival_order), k)]
+            for grp, c in zip(groups, calls):
+                out.append((grp[0], sum(wl.fragments[fi].numel * wl.fragments[fi].bytes_per_param
+                                        for fi in grp), lambda c=c, plan=plan: plan.merge(c)))
         else:
             for fi in wl.arrival_order:
                 out.append((fi, wl.fragments[fi].numel * wl.fragments[fi].bytes_per_param,
@@ -376,7 +383,7 @@ def main():
     if args.merge == "avg" and args.api == "tensor":
         sys.stderr.write("bench.py: --api tensor is for --merge rda\n")
         sys.exit(2)
-    launches_per_step = wl.num_segments if args.api == "tensor" else len(wl.arrival_order)
+    launches_per_step = wl.num_segments if args.api == "tensor" else len(launch_lists[0])
     torch.cuda.synchronize()
 
     # ---- timed region ---------------------------------------------------------------------
@@ -451,6 +458,7 @@ def main():
                       f"q4/block{args.q4_block}" if args.merge == "q4" else
                       f"rda/{args.rda_group}"),
             "launches_per_step": launches_per_step,
+            "syncs_per_call": args.syncs_per_call,
             "replicas": replicas,
             "bf16_broadcast_copy": bool(args.bcast),
             "hip_graph": bool(args.graph),

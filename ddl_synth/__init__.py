@@ -198,6 +198,25 @@ def streaming_model(d_model: int = 4096, d_ff: int = 14336, blocks: int = 32,
     return Workload("streaming_model", frags, order)
 
 
+def small_fragments(d_model: int = 512, d_ff: int = 2048, blocks: int = 64) -> Workload:
+    """Many small fragments due at the same time: 64 transformer blocks of 3.1 M parameters
+    (6 tensors each), one fragment per block; M=4 bf16 learners, per-fragment seeded quorum
+    of 3 or 4.  The case for the multi-fragment launch: one kernel covers up to eight
+    fragments, so small fragments need not each pay a launch."""
+    M = 4
+    frags: List[FragmentSpec] = []
+    for b in range(blocks):
+        rng = np.random.default_rng(seed_for("small_fragments", b, "meta"))
+        k = int(rng.integers(3, M + 1))
+        frags.append(FragmentSpec(b, _dense_block(d_model, d_ff, False, f"blk{b}."), M=M,
+                                  learner_dtype="bf16",
+                                  token_counts=_uniform_tokens(rng, M, 1 << 20),
+                                  quorum_mask=_choose_quorum(rng, M, k), drift=[1e-3] * M))
+    order = np.random.default_rng(seed_for("small_fragments", "arrival")).permutation(
+        blocks).tolist()
+    return Workload("small_fragments", frags, order)
+
+
 def regroup(wl: Workload, fragment_of: Sequence[int], num_fragments: int) -> Workload:
     """The same tensors regrouped into ``num_fragments`` fragments: tensor i (numbered across
     the fragments of ``wl`` in order) goes to fragment ``fragment_of[i]``.  The partition is an
@@ -229,6 +248,7 @@ WORKLOADS = {
     "moe": moe,
     "moe_stacked": lambda: moe(stacked=True),
     "streaming_model": streaming_model,
+    "small_fragments": small_fragments,
 }
 
 
@@ -245,6 +265,8 @@ def reduced(name: str) -> Workload:
         return moe(d_model=64, d_ff=45, experts=64)
     if name == "moe_stacked":
         return moe(d_model=64, d_ff=45, experts=64, stacked=True)
+    if name == "small_fragments":
+        return small_fragments(d_model=40, d_ff=131, blocks=64)
     if name == "streaming_model":
         return streaming_model(d_model=48, d_ff=163, blocks=32, vocab=1003)
     raise KeyError(name)

@@ -11,7 +11,8 @@ from ddl_testutil import check_segment, oracle_segment, random_problem
 pytestmark = pytest.mark.gpu
 
 DEV = "cuda:0"
-NAMES = ["tiny", "dense_block", "large_dense", "moe", "moe_stacked", "streaming_model"]
+NAMES = ["tiny", "dense_block", "large_dense", "moe", "moe_stacked", "streaming_model",
+         "small_fragments"]
 
 
 @pytest.fixture(scope="module")

@@ -21,6 +21,9 @@ def test_workload_sizes():
     assert ms.numel == m.numel and ms.num_segments == 4 and ms.name == "moe_stacked"
     assert ms.fragments[0].token_counts == m.fragments[0].token_counts
     assert ms.fragments[0].quorum_mask == m.fragments[0].quorum_mask
+    sf = ddl_synth.small_fragments()
+    assert sf.numel == 64 * 3_145_728 and len(sf.fragments) == 64 and sf.num_segments == 384
+    assert {f.Mq for f in sf.fragments} == {3, 4} and sorted(sf.arrival_order) == list(range(64))
     s = ddl_synth.streaming_model()
     assert s.numel == 8_309_964_800 and len(s.fragments) == 33
     assert sorted(s.arrival_order) == list(range(33)) and s.arrival_order != list(range(33))
