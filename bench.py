@@ -75,6 +75,9 @@ def parse_args():
     ap.add_argument("--bcast", action="store_true",
                     help="also write the new Theta as bf16 in the same pass (+2 B/param)")
     ap.add_argument("--tile-rotate", type=int, default=None)
+    ap.add_argument("--streams", type=int, default=1,
+                    help="issue the calls of a step round-robin on this many HIP streams "
+                         "(fragments are independent; call i of every step uses stream i mod N)")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph and time replays (plan API, avg merge)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -345,10 +348,27 @@ def main():
 
     launch_lists = [launch_list(c) for c in copies]
 
+    streams = [torch.cuda.Stream() for _ in range(args.streams)] if args.streams > 1 else None
+
     def step():
-        for _, _, fn in launch_lists[counter[0] % replicas]:
-            fn()
+        if streams is None:
+            for _, _, fn in launch_lists[counter[0] % replicas]:
+                fn()
+        else:
+            for i, (_, _, fn) in enumerate(launch_lists[counter[0] % replicas]):
+                with torch.cuda.stream(streams[i % len(streams)]):
+                    fn()
         counter[0] += 1
+
+    def fork():     # the side streams start after what the main stream has done so far
+        if streams is not None:
+            for st in streams:
+                st.wait_stream(torch.cuda.current_stream())
+
+    def join():     # ... and the main stream continues after all of them
+        if streams is not None:
+            for st in streams:
+                torch.cuda.current_stream().wait_stream(st)
 
     if args.graph:
         if args.api != "plan" or args.merge != "avg":
@@ -387,21 +407,25 @@ def main():
     torch.cuda.synchronize()
 
     # ---- timed region ---------------------------------------------------------------------
+    fork()
     for _ in range(warmup):
         step()
+    join()
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record()          # on torch's current stream: the stream the kernels are launched on
+    fork()
     for _ in range(steps):
         step()
+    join()
     ev1.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     wall_ms = (t1 - t0) * 1e3 / steps
     gpu_ms = ev0.elapsed_time(ev1) / steps
 
-    detail = None if args.graph else detail_pass(torch, launch_lists, counter, replicas,
+    detail = None if args.graph or streams is not None else detail_pass(torch, launch_lists, counter, replicas,
                                                  min(steps, 40), 2 * wl.numel if args.bcast else 0)
 
     params_per_s = wl.numel / (wall_ms * 1e-3)
@@ -459,6 +483,7 @@ def main():
                       f"rda/{args.rda_group}"),
             "launches_per_step": launches_per_step,
             "syncs_per_call": args.syncs_per_call,
+            "streams": args.streams,
             "replicas": replicas,
             "bf16_broadcast_copy": bool(args.bcast),
             "hip_graph": bool(args.graph),
