@@ -54,7 +54,7 @@ def parse_args():
                              "streaming_model", "small_fragments"])
     ap.add_argument("--syncs-per-call", type=int, default=1,
                     help="fragments handed to one ddl_plan_merge call (plan API, avg merge): "
-                         "the library covers up to eight fragments with one launch")
+                         "the library covers up to sixteen fragments with one launch")
     ap.add_argument("--api", default="plan", choices=["plan", "batch", "tensor"],
                     help="resident plan (default); the one-shot ddl_merge_batch per fragment; "
                          "or, for --merge rda, one ddl_rda_merge_fragment call per tensor")

@@ -201,7 +201,7 @@ def streaming_model(d_model: int = 4096, d_ff: int = 14336, blocks: int = 32,
 def small_fragments(d_model: int = 512, d_ff: int = 2048, blocks: int = 64) -> Workload:
     """Many small fragments due at the same time: 64 transformer blocks of 3.1 M parameters
     (6 tensors each), one fragment per block; M=4 bf16 learners, per-fragment seeded quorum
-    of 3 or 4.  The case for the multi-fragment launch: one kernel covers up to eight
+    of 3 or 4.  The case for the multi-fragment launch: one kernel covers up to sixteen
     fragments, so small fragments need not each pay a launch."""
     M = 4
     frags: List[FragmentSpec] = []

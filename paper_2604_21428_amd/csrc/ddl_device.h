@@ -11,7 +11,7 @@
 #include <stdint.h>
 
 #define DDL_MAXL 16         // learners per fragment, = DDL_MAX_LEARNERS of the public header
-#define DDL_MAX_ITEMS 8     // fragments per launch
+#define DDL_MAX_ITEMS 16    // fragments per launch
 #define DDL_BLOCK 256       // threads per workgroup: 4 wavefronts of 64
 #define DDL_TILE (DDL_BLOCK * 4)  // elements per tile: one group of four per lane
 #define DDL_LDS_PER_CU (160 * 1024)  // bytes of LDS per compute unit on gfx950
