@@ -139,9 +139,14 @@ def _u8(xs, M: Optional[int] = None):
     return (ctypes.c_uint8 * len(xs))(*xs)
 
 
+_raw_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+
+
 def _stream_handle(stream) -> Optional[int]:
-    """hipStream_t of a torch stream (None: torch's current stream)."""
+    """hipStream_t of a torch stream (None: torch's current stream on the current device)."""
     if stream is None:
+        if _raw_stream is not None:
+            return ctypes.c_void_p(_raw_stream(torch.cuda.current_device()))
         stream = torch.cuda.current_stream()
     return ctypes.c_void_p(stream.cuda_stream)
 
