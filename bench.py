@@ -105,10 +105,16 @@ def time_copy_probe(ddl, torch, nbytes=1 << 30, reps=20):
     return 2 * nbytes / (ms * 1e-3) / 1e9
 
 
-def cpu_baseline(torch, ddl_synth, wl, data, budget_s=20.0):
+def cpu_baseline(torch, ddl_synth, wl, data, budget_s=20.0, gpu_merge=None):
     """The oracle as it stands, timed on the host: the plain scalar fp64 loop on one core and
     the same loop chunked over all cores.  Sample: whole tensors of the workload, in order,
-    until about ``budget_s`` seconds of single-core work have been spent."""
+    until about ``budget_s`` seconds of single-core work have been spent.
+
+    The oracle's results are not thrown away: if ``gpu_merge(fragment_index)`` is given, every
+    fragment whose tensors were all run through the oracle is then synced once more on the GPU
+    from that same state, and the two are compared on windows of every tensor (first, middle
+    and last 4096 elements of what the oracle saw): ``max_abs_err_vs_oracle``."""
+    import numpy as np
     import oracle
     cores = len(os.sched_getaffinity(0))
     cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)) or cores)
@@ -116,8 +122,10 @@ def cpu_baseline(torch, ddl_synth, wl, data, budget_s=20.0):
     t_single = 0.0
     t_multi = 0.0
     tensors = 0
+    worst_err, worst_rel, checked = 0.0, 0.0, 0
     for fi in wl.arrival_order:
         f = wl.fragments[fi]
+        kept = []                       # (segment, lo, hi, theta_ref, v_ref) of this fragment
         for s in data[fi]:
             n = s.theta.numel()
             cap = 1 << 26               # at most 64 Mi elements of a tensor: bounds host memory
@@ -128,15 +136,30 @@ def cpu_baseline(torch, ddl_synth, wl, data, budget_s=20.0):
             t0 = time.perf_counter()
             oracle.merge_fragment(th, v, ls, f.token_counts, f.quorum_mask, f.lr, f.mu)
             t1 = time.perf_counter()
-            oracle.merge_fragment(th, v, ls, f.token_counts, f.quorum_mask, f.lr, f.mu,
-                                  nthreads=cores)
+            ref = oracle.merge_fragment(th, v, ls, f.token_counts, f.quorum_mask, f.lr, f.mu,
+                                        nthreads=cores)
             t2 = time.perf_counter()
             t_single += t1 - t0
             t_multi += t2 - t1
-            done_params += min(n, cap)
+            m = min(n, cap)
+            done_params += m
             tensors += 1
+            for lo in sorted({0, max(0, m // 2 - 2048), max(0, m - 4096)}):
+                hi = min(m, lo + 4096)
+                kept.append((s, lo, hi, ref[0][lo:hi].copy(), ref[1][lo:hi].copy()))
+            del ref, th, v, ls
             if t_single >= budget_s:
                 break
+        whole_fragment = len({id(k[0]) for k in kept}) == len(data[fi])
+        if gpu_merge is not None and whole_fragment and kept:
+            gpu_merge(fi)
+            torch.cuda.synchronize()
+            for s, lo, hi, th_ref, v_ref in kept:
+                for got, want in ((s.theta[lo:hi], th_ref), (s.v[lo:hi], v_ref)):
+                    err = np.abs(got.cpu().numpy().astype(np.float64) - want)
+                    worst_err = max(worst_err, float(err.max()))
+                    worst_rel = max(worst_rel, float((err / (1.0 + np.abs(want))).max()))
+                    checked += err.size
         if t_single >= budget_s:
             break
     model = ""
@@ -160,6 +183,10 @@ def cpu_baseline(torch, ddl_synth, wl, data, budget_s=20.0):
         "value_1core": done_params / t_single,
         "seconds_1core": round(t_single, 3),
         "seconds_allcores": round(t_multi, 3),
+        # one more sync of the same state on the GPU against the oracle's result just timed
+        "max_abs_err_vs_oracle": worst_err if checked else None,
+        "max_err_over_bound": (worst_rel / 1e-6) if checked else None,   # bound 1e-6 (1 + |ref|)
+        "elements_compared": checked,
     }
 
 
@@ -513,7 +540,12 @@ def main():
     if detail is not None:
         out["detail"] = detail
     if not args.no_cpu_baseline and args.merge != "q4":   # the oracle leg times the bf16 path
-        out["cpu_baseline"] = cpu_baseline(torch, ddl_synth, wl, data)
+        gpu_merge = None
+        if (args.api == "plan" and args.merge == "avg" and args.syncs_per_call == 1 and
+                not args.graph and streams is None):
+            fns = {fi: fn for fi, _, fn in launch_lists[0]}
+            gpu_merge = lambda fi: fns[fi]()
+        out["cpu_baseline"] = cpu_baseline(torch, ddl_synth, wl, data, gpu_merge=gpu_merge)
     print(json.dumps(out))
 
 
