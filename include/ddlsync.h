@@ -338,12 +338,12 @@ DDL_API ddl_status ddl_copy_probe(void* dst, const void* src, size_t bytes, void
 /*
  * Launch-shape knobs, for measurement.  Names: "tiles_per_block" (how many consecutive
  * 1024-element tiles one workgroup walks, 1..1024; default 1), "max_blocks_per_cu" (0: no cap;
- * k in 3..64: at most k workgroups resident per compute unit; default 4), "tile_rotate" (0:
- * workgroup b takes run-of-tiles b; k in 2..4096: the index is rotated within groups of k by
- * the group's number, which spreads every XCD's accesses over all memory channels; default
- * 64), "rda_blocks_per_cu" (the residency cap of the RDA one-kernel
- * shapes; default 0).  Affects later calls.  Unknown name or bad value: INVALID_ARG.
- * ddl_get_option writes the current value.
+ * k in 3..64: at most k workgroups resident per compute unit; -1, the default: chosen by
+ * learner type and count, 3 to 6), "tile_rotate" (0: workgroup b takes run-of-tiles b; k in
+ * 2..4096: the index is rotated within groups of k by the group's number, which spreads every
+ * XCD's accesses over all memory channels; default 64), "rda_blocks_per_cu" (the residency cap
+ * of the RDA one-kernel shapes; default 0).  Affects later calls.  Unknown name or bad value:
+ * INVALID_ARG.  ddl_get_option writes the current value.
  */
 DDL_API ddl_status ddl_set_option(const char* name, long value);
 DDL_API ddl_status ddl_get_option(const char* name, long* value_out);

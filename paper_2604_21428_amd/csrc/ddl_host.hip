@@ -47,7 +47,8 @@ namespace {
 std::mutex g_mu;  // guards options, device state and the staging ring
 long g_tiles_per_block = 1;    // consecutive tiles a workgroup walks
 long g_tile_rotate = 64;       // group size of the tile rotation (0: off); see rotate_tile()
-long g_max_blocks_per_cu = 4;  // 0: no cap; k: at most k resident workgroups per compute unit
+long g_max_blocks_per_cu = -1;  // -1: by learner type and count; 0: no cap; k: at most k
+                                // resident workgroups per compute unit
 
 constexpr int kMaxDevices = 16;
 constexpr int kSlots = 4;
@@ -86,16 +87,29 @@ uint32_t grid_for(uint32_t total_tiles)
 
 // Dynamic LDS requested per workgroup purely to cap residency: floor(LDS per CU / k), kept
 // within the 64 KiB a kernel may ask for without opting in.
-uint32_t lds_cap_bytes()
+// The cap itself, when left to the library (measured on MI355X; what matters is roughly the
+// bytes one compute unit has in flight): few bf16 learners leave room for six workgroups, many
+// want four; fp32 learners, twice the bytes per tile, want four and from four learners on
+// three; 4-bit codes are so few bytes that six is best throughout.
+// elem_bytes: 4 fp32 learners, 2 bf16, 0 the 4-bit codes.
+long auto_blocks_per_cu(int elem_bytes, int Mq)
 {
-    if (g_max_blocks_per_cu <= 0) return 0;
-    uint32_t b = (uint32_t)(DDL_LDS_PER_CU / g_max_blocks_per_cu) & ~511u;
+    if (elem_bytes == 4) return Mq >= 4 ? 3 : 4;
+    if (elem_bytes == 2) return Mq <= 5 ? 6 : 4;
+    return 6;
+}
+
+uint32_t lds_cap_bytes(int elem_bytes, int Mq)
+{
+    const long k = g_max_blocks_per_cu < 0 ? auto_blocks_per_cu(elem_bytes, Mq) : g_max_blocks_per_cu;
+    if (k <= 0) return 0;
+    uint32_t b = (uint32_t)(DDL_LDS_PER_CU / k) & ~511u;
     return b > 64 * 1024 ? 64 * 1024 : b;
 }
 
 }  // namespace
 
-uint32_t ddlh::merge_lds_cap_bytes() { return lds_cap_bytes(); }
+uint32_t ddlh::merge_lds_cap_bytes(int elem_bytes, int Mq) { return lds_cap_bytes(elem_bytes, Mq); }
 uint32_t ddlh::tile_rotate() { return (uint32_t)g_tile_rotate; }
 
 // ------------------------------------------------------------------------------------------
@@ -387,7 +401,9 @@ ddl_status launch_work(const Table& T, const void* d_table, std::vector<Work>& w
             a.num_items = items;
             a.total_tiles = (uint32_t)tiles;
             const int e = ddl_launch_merge((int)f0.dt, work[i].q.Mq, false,
-                                           grid_for(a.total_tiles), lds_cap_bytes(), stream, a);
+                                           grid_for(a.total_tiles),
+                                           lds_cap_bytes((int)elem_size(f0.dt), work[i].q.Mq),
+                                           stream, a);
             if (e != (int)hipSuccess) return runtime_error((hipError_t)e, "merge kernel launch");
         }
         if (j == i) return DDL_ERR_INVALID_ARG;  // cannot happen: a lone fragment always fits
@@ -424,8 +440,8 @@ ddl_status merge_flat(float* theta, float* v, void* theta_bf16, const void* cons
     a.num_items = 1;
     fill_desc(a.flat, theta, v, theta_bf16, lp, M, n, 0);
     fill_item(a.item[0], q, lr, mu, 0, 1, 0);
-    const int e = ddl_launch_merge((int)dt, q.Mq, true, grid_for(a.total_tiles), lds_cap_bytes(),
-                                   stream, a);
+    const int e = ddl_launch_merge((int)dt, q.Mq, true, grid_for(a.total_tiles),
+                                   lds_cap_bytes((int)elem_size(dt), q.Mq), stream, a);
     if (e != (int)hipSuccess) return runtime_error((hipError_t)e, "merge kernel launch");
     return DDL_OK;
 }
@@ -673,7 +689,7 @@ ddl_status ddl_set_option(const char* name, long value)
         return DDL_OK;
     }
     if (!std::strcmp(name, "max_blocks_per_cu")) {
-        if (value != 0 && (value < 3 || value > 64)) return DDL_ERR_INVALID_ARG;
+        if (value != 0 && value != -1 && (value < 3 || value > 64)) return DDL_ERR_INVALID_ARG;
         g_max_blocks_per_cu = value;
         return DDL_OK;
     }

@@ -54,8 +54,8 @@ ddl_status weights_tokens(const uint64_t* t, const uint8_t* q, int M, double* w)
 void compact(const double* w, int M, Quorum& out);
 bool finite_nonneg(float x);
 // Unused dynamic LDS per workgroup that enforces the max_blocks_per_cu option on the
-// streaming merge kernels (0: no cap).
-uint32_t merge_lds_cap_bytes();
+// streaming merge kernels (0: no cap).  elem_bytes: bytes per learner element (0: 4-bit codes).
+uint32_t merge_lds_cap_bytes(int elem_bytes, int Mq);
 // Group size of the tile rotation (option tile_rotate; 0: off).
 uint32_t tile_rotate();
 // Records the message for ddl_last_error_message and returns DDL_ERR_RUNTIME.

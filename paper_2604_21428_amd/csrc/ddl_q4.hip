@@ -314,7 +314,7 @@ extern "C" ddl_status ddl_q4_merge_fragment(float* theta, float* v, const uint8_
     a.rotate = ddlh::tile_rotate();
     const q4_fn fn = pick_q4(q.Mq);
     if (!fn) return DDL_ERR_INVALID_ARG;
-    hipLaunchKernelGGL(fn, dim3((uint32_t)tiles), dim3(DDL_BLOCK), ddlh::merge_lds_cap_bytes(),
+    hipLaunchKernelGGL(fn, dim3((uint32_t)tiles), dim3(DDL_BLOCK), ddlh::merge_lds_cap_bytes(0, q.Mq),
                        static_cast<hipStream_t>(hip_stream), a);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? DDL_OK : ddlh::runtime_error(e, "q4 merge kernel launch");

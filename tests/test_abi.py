@@ -238,11 +238,14 @@ int main(void) {
 
 def test_options(ddl):
     assert ddl.get_option("tiles_per_block") >= 1
-    assert ddl.get_option("max_blocks_per_cu") >= 0
+    assert ddl.get_option("max_blocks_per_cu") == -1          # chosen by the library
+    assert ddl.get_option("tile_rotate") == 64
     with pytest.raises(ddl.DdlError):
         ddl.set_option("tiles_per_block", 0)
-    with pytest.raises(ddl.DdlError):
-        ddl.set_option("max_blocks_per_cu", 2)
-    with pytest.raises(ddl.DdlError):
-        ddl.set_option("max_blocks_per_cu", -1)
+    for bad in (2, -2, 65):
+        with pytest.raises(ddl.DdlError):
+            ddl.set_option("max_blocks_per_cu", bad)
+    ddl.set_option("max_blocks_per_cu", 5)
+    assert ddl.get_option("max_blocks_per_cu") == 5
+    ddl.set_option("max_blocks_per_cu", -1)
 
