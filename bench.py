@@ -30,12 +30,12 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published peak
 # scaled by what the same counter reads for ddl_copy_probe of known size); the runs are
 # summarised under profiles/.  None where no counter run exists for the workload.
 MEASURED_TRAFFIC_BYTES = {
-    "dense_block": 1107108047,   # profiles/ddl_merge_kernel_dense_block.txt
-    "large_dense": 27240128247,  # profiles/ddl_merge_kernel_large_workloads.txt
+    "dense_block": 1107103355,   # profiles/ddl_merge_kernel_dense_block.txt
+    "large_dense": 27240647788,  # profiles/ddl_merge_kernel_large_workloads.txt
 }
 # The same for one sync with the RDA merge through the plan, one norm per row.
 MEASURED_TRAFFIC_BYTES_Q4_BLOCK128 = {
-    "dense_block": 899419746,    # profiles/ddl_q4_kernels.txt
+    "dense_block": 899423517,    # profiles/ddl_q4_kernels.txt
 }
 MEASURED_TRAFFIC_BYTES_RDA_ROWS = {
     "dense_block": 1107403362,   # profiles/ddl_rda_kernels.txt
