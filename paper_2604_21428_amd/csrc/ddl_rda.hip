@@ -640,30 +640,37 @@ __global__ void __launch_bounds__(NTH) rda_rows_kernel(const DdlRdaRowsArgs a)
 
 // Registers the row kernel keeps per lane: K groups of (packed learners + Theta + v), plus
 // about six per learner while a sweep runs (the four differences of a group, a sum, a
-// coefficient); a 1024-thread workgroup leaves each lane 128 registers, smaller ones 256 and
-// more.
+// coefficient).  A 1024-thread workgroup leaves each lane 128 registers: the learners' packed
+// words per group-of-four slot may then take 12 (K = 4), 16 (K = 2) or 24 (K = 1) registers --
+// limits found by building (the build fails on any spill); smaller workgroups have 256 and more.
 template <typename L, int MQ, int K, int NTH>
 constexpr bool row_kernel_fits()
 {
-    const int data = K * ((int)(sizeof(typename L::raw) / 4) * MQ + 8);
-    return NTH > 512 ? data + 6 * MQ <= 116 : data <= 192;
+    const int words = (int)(sizeof(typename L::raw) / 4) * MQ;  // packed learner words per slot
+    if (NTH > 512) return words <= (K >= 4 ? 12 : K == 2 ? 16 : 24);
+    return K * (words + 8) <= 192;
 }
 
 typedef void (*rda_fn)(const DdlRdaArgs);
 typedef void (*rda_rows_fn)(const DdlRdaRowsArgs);
 
 // The register-resident shapes, smallest first: X(class, K groups of four per lane, workgroup
-// size); a class holds groups of up to K * 4 * threads elements.
+// size, K and workgroup size of the second choice); a class holds groups of up to
+// K * 4 * threads elements.  The second choice, of the same capacity, is taken when the first
+// does not fit the registers for this many learners (it keeps fewer groups per lane).
 #ifndef DDL_RDA_ROW_CLASSES
-#define DDL_RDA_ROW_CLASSES(X) X(0, 1, 256) X(1, 2, 256) X(2, 4, 256) X(3, 8, 256) X(4, 4, 1024)
+#define DDL_RDA_ROW_CLASSES(X) \
+    X(0, 1, 256, 1, 256) X(1, 2, 256, 1, 512) X(2, 4, 256, 2, 512) X(3, 8, 256, 4, 512) \
+    X(4, 4, 1024, 8, 512)
 #endif
 struct RowClass {
-    int K;
-    uint32_t threads;
     uint32_t max_len;
 };
-#define DDL_X(c, k, nth) {k, nth, k * 4 * nth},
+#define DDL_X(c, k, nth, k2, nth2) {k * 4 * nth},
 constexpr RowClass kRowClass[] = {DDL_RDA_ROW_CLASSES(DDL_X)};
+#undef DDL_X
+#define DDL_X(c, k, nth, k2, nth2) static_assert(k * nth == k2 * nth2, "same capacity");
+DDL_RDA_ROW_CLASSES(DDL_X)
 #undef DDL_X
 constexpr int kNumRowClasses = (int)(sizeof(kRowClass) / sizeof(kRowClass[0]));
 
@@ -675,28 +682,34 @@ int row_class_for(uint64_t len)
     return kNumRowClasses;
 }
 
-template <typename L, int MQ, int K, int NTH>
-void row_kernels_or_null(rda_fn& one, rda_rows_fn& many)
-{
-    if constexpr (row_kernel_fits<L, MQ, K, NTH>()) {
-        one = rda_row_kernel<L, MQ, K, NTH>;
-        many = rda_rows_kernel<L, MQ, K, NTH>;
-    } else {
-        one = nullptr;
-        many = nullptr;
-    }
-}
-
-// The row kernels of class `cls` (one tensor / many tensors), or null if their registers do
-// not fit for this learner type and count.
-template <typename L, int MQ>
-void pick_row(int cls, rda_fn& one, rda_rows_fn& many)
+template <typename L, int MQ, int K, int NTH, int K2, int NTH2>
+void row_kernels_or_null(rda_fn& one, rda_rows_fn& many, uint32_t& threads)
 {
     one = nullptr;
     many = nullptr;
+    threads = 0;
+    if constexpr (row_kernel_fits<L, MQ, K, NTH>()) {
+        one = rda_row_kernel<L, MQ, K, NTH>;
+        many = rda_rows_kernel<L, MQ, K, NTH>;
+        threads = NTH;
+    } else if constexpr (row_kernel_fits<L, MQ, K2, NTH2>()) {
+        one = rda_row_kernel<L, MQ, K2, NTH2>;
+        many = rda_rows_kernel<L, MQ, K2, NTH2>;
+        threads = NTH2;
+    }
+}
+
+// The row kernels of class `cls` (one tensor / many tensors) and their workgroup size, or null
+// if neither choice fits the registers for this learner type and count.
+template <typename L, int MQ>
+void pick_row(int cls, rda_fn& one, rda_rows_fn& many, uint32_t& threads)
+{
+    one = nullptr;
+    many = nullptr;
+    threads = 0;
     switch (cls) {
-#define DDL_X(c, k, nth) \
-    case c: row_kernels_or_null<L, MQ, k, nth>(one, many); break;
+#define DDL_X(c, k, nth, k2, nth2) \
+    case c: row_kernels_or_null<L, MQ, k, nth, k2, nth2>(one, many, threads); break;
         DDL_RDA_ROW_CLASSES(DDL_X)
 #undef DDL_X
         default: break;
@@ -706,6 +719,7 @@ void pick_row(int cls, rda_fn& one, rda_rows_fn& many)
 struct Kernels {
     rda_fn sumsq = nullptr, dirsq = nullptr, apply = nullptr, group = nullptr, row = nullptr;
     rda_rows_fn rows = nullptr;
+    uint32_t row_threads = 0;  // workgroup size of row / rows
 };
 
 template <typename L>
@@ -718,7 +732,7 @@ void pick(int Mq, int cls, Kernels& k)
         k.dirsq = rda_dirsq_kernel<L, q>;        \
         k.apply = rda_apply_kernel<L, q>;        \
         k.group = rda_group_kernel<L, q>;        \
-        pick_row<L, q>(cls, k.row, k.rows);      \
+        pick_row<L, q>(cls, k.row, k.rows, k.row_threads); \
         break;
         DDL_CASE(1) DDL_CASE(2) DDL_CASE(3) DDL_CASE(4) DDL_CASE(5) DDL_CASE(6) DDL_CASE(7)
         DDL_CASE(8) DDL_CASE(9) DDL_CASE(10) DDL_CASE(11) DDL_CASE(12) DDL_CASE(13)
@@ -802,7 +816,7 @@ ddl_status launch_one(ddl_dtype dt, int Mq, DdlRdaArgs& a, const Geometry& g, vo
     const dim3 block(DDL_BLOCK);
     const uint32_t groups = (uint32_t)g.groups;
     if (k.row && a.vec_ok && a.n % 4 == 0 && groups >= kGroupKernelMinGroups) {
-        hipLaunchKernelGGL(k.row, dim3(groups), dim3(kRowClass[cls].threads), row_lds_cap(), stream,
+        hipLaunchKernelGGL(k.row, dim3(groups), dim3(k.row_threads), row_lds_cap(), stream,
                            a);
     } else if (a.group_len <= kGroupKernelMaxLen && groups >= kGroupKernelMinGroups) {
         hipLaunchKernelGGL(k.group, dim3(groups), block, row_lds_cap(), stream, a);
@@ -1117,7 +1131,7 @@ extern "C" ddl_status ddl_plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, 
                 a.mu = wk.mu;
                 std::memcpy(a.w, wk.q.w, sizeof a.w);
                 std::memcpy(a.idx, wk.q.idx, sizeof a.idx);
-                hipLaunchKernelGGL(fn.rows, dim3(k.rows), dim3(kRowClass[c].threads), row_lds_cap(),
+                hipLaunchKernelGGL(fn.rows, dim3(k.rows), dim3(fn.row_threads), row_lds_cap(),
                                    stream, a);
                 const hipError_t e = hipGetLastError();
                 if (e != hipSuccess) return ddlh::runtime_error(e, "RDA rows kernel launch");

@@ -86,6 +86,37 @@ def test_quorum_sizes(ddl, Mq, g):
     _run(ddl, theta, v, learners, tokens, mask.tolist(), g, 0.7, 0.9, f"Mq={Mq} g={g}")
 
 
+# (learner type, contributing learners, group length): one-pass row kernels in their first and
+# second register layouts, and combinations that fit neither (many learners, long rows)
+ROW_LAYOUTS = [(torch.bfloat16, 8, 8192), (torch.bfloat16, 11, 8192), (torch.bfloat16, 16, 6000),
+               (torch.bfloat16, 6, 14336), (torch.bfloat16, 8, 16384), (torch.bfloat16, 9, 16384),
+               (torch.bfloat16, 16, 4096), (torch.bfloat16, 16, 2048),
+               (torch.float32, 3, 16000), (torch.float32, 4, 16000), (torch.float32, 5, 12000),
+               (torch.float32, 8, 8192), (torch.float32, 10, 5000), (torch.float32, 11, 5000),
+               (torch.float32, 16, 4096), (torch.float32, 16, 1024)]
+
+
+@pytest.mark.parametrize("dtype,Mq,g", ROW_LAYOUTS,
+                         ids=[f"{str(d)[6:]}-Mq{m}-g{g}" for d, m, g in ROW_LAYOUTS])
+def test_row_kernel_register_layouts(ddl, dtype, Mq, g):
+    n = 516 * g                               # enough groups for the one-kernel shapes
+    theta, v, learners, tokens, mask = random_problem(650 + Mq + g, n, Mq, dtype, DEV)
+    idx = np.sort(np.random.default_rng(g).choice(516, size=4, replace=False))
+    ws = _workspace(ddl, n, g, Mq)
+    refs = []
+    for r in idx:                             # groups are independent: check four of them
+        lo, hi = int(r) * g, (int(r) + 1) * g
+        refs.append((lo, hi, oracle.rda_merge_fragment(
+            ddl_synth.to_host_array(theta[lo:hi]), ddl_synth.to_host_array(v[lo:hi]),
+            host_learners(learners, lo, hi), tokens, mask, g, 0.7, 0.9)))
+    print(f"row layout {dtype} Mq={Mq} g={g}", flush=True)
+    ddl.rda_merge_fragment(theta, v, learners, tokens, mask, g, 0.7, 0.9, ws)
+    torch.cuda.synchronize()
+    for lo, hi, ref in refs:
+        assert_parity(ddl_synth.to_host_array(theta[lo:hi]), ref[0], f"Mq={Mq} g={g} [{lo}] theta")
+        assert_parity(ddl_synth.to_host_array(v[lo:hi]), ref[1], f"Mq={Mq} g={g} [{lo}] v")
+
+
 @pytest.mark.parametrize("g", [2000, 20])
 @pytest.mark.parametrize("offset", [1, 2, 3])
 def test_misaligned(ddl, offset, g):
