@@ -291,7 +291,9 @@ DDL_API size_t ddl_plan_num_elements(const ddl_plan* plan);
  * ddl_plan_set_rda_groups   group_len[s] for every segment the plan was created with, empty
  *                           ones included, fragment by fragment in creation order
  *                           (num_segments = their total); 0 or a value above the segment's n
- *                           means one group for the whole tensor.  Uploads a small device
+ *                           means one group for the whole tensor; (size_t)-1 means that this
+ *                           tensor is merged by direct averaging, not RDA (the paper uses RDA
+ *                           for the non-embedding parameters only, Section 5.1).  Uploads a small device
  *                           table (allocates; not for capture); may be called again to change
  *                           the grouping once no merge of the plan is running.
  * ddl_plan_rda_workspace_bytes   size of the scratch the merges of this plan need (0 before

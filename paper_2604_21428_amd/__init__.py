@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libddlsync.so")
 DDL_OK, DDL_ERR_INVALID_ARG, DDL_ERR_EMPTY_QUORUM, DDL_ERR_ALIAS, DDL_ERR_RUNTIME = range(5)
 DDL_F32, DDL_BF16 = 0, 1
 DDL_MAX_LEARNERS = 16
+RDA_DIRECT = (1 << (8 * ctypes.sizeof(ctypes.c_size_t))) - 1   # (size_t)-1
 
 
 class DdlError(RuntimeError):
@@ -443,9 +444,11 @@ class Plan:
 
     def set_rda_groups(self, group_len: Sequence[int]) -> None:
         """ddl_plan_set_rda_groups: the RDA group length of every segment of the plan, fragment
-        by fragment in creation order (0: one group per tensor)."""
+        by fragment in creation order (0: one group per tensor; RDA_DIRECT or -1: this tensor
+        is merged by direct averaging)."""
         n = len(group_len)
-        arr = (ctypes.c_size_t * max(1, n))(*[int(g) for g in group_len])
+        arr = (ctypes.c_size_t * max(1, n))(*[RDA_DIRECT if int(g) < 0 else int(g)
+                                              for g in group_len])
         _check(_lib.ddl_plan_set_rda_groups(self._h, arr, n), "ddl_plan_set_rda_groups")
 
     @property

@@ -448,6 +448,31 @@ ddl_status merge_flat(float* theta, float* v, void* theta_bf16, const void* cons
 
 }  // namespace
 
+// Direct averaging of ONE tensor whose descriptor already exists (a tensor of a plan): the
+// descriptor travels in the kernel-argument block.  Used by the RDA plan call for tensors
+// that are to be merged by direct averaging.
+ddl_status ddlh::launch_one_direct(const DdlSegDesc& desc, ddl_dtype dt, const Quorum& q, float lr,
+                                   float mu, void* stream)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    const uint64_t tiles = (desc.n + DDL_TILE - 1) / DDL_TILE;
+    if (tiles == 0) return DDL_OK;
+    if (tiles > 0x7fffffffull) return DDL_ERR_INVALID_ARG;
+    DdlLaunchArgs a;
+    std::memset(&a, 0, sizeof a);
+    a.tiles_per_block = (uint32_t)g_tiles_per_block;
+    a.rotate = (int32_t)g_tile_rotate;
+    a.total_tiles = (uint32_t)tiles;
+    a.num_items = 1;
+    a.flat = desc;
+    a.flat.tile_begin = 0;
+    fill_item(a.item[0], q, lr, mu, 0, 1, 0);
+    const int e = ddl_launch_merge((int)dt, q.Mq, true, grid_for(a.total_tiles),
+                                   lds_cap_bytes((int)elem_size(dt), q.Mq), stream, a);
+    if (e != (int)hipSuccess) return runtime_error((hipError_t)e, "merge kernel launch");
+    return DDL_OK;
+}
+
 extern "C" {
 
 int ddl_version(void) { return 100; }

@@ -58,6 +58,9 @@ bool finite_nonneg(float x);
 uint32_t merge_lds_cap_bytes(int elem_bytes, int Mq);
 // Group size of the tile rotation (option tile_rotate; 0: off).
 uint32_t tile_rotate();
+// Enqueues the direct-averaging merge + outer step of one tensor given by its descriptor.
+ddl_status launch_one_direct(const DdlSegDesc& desc, ddl_dtype dt, const Quorum& q, float lr,
+                             float mu, void* stream);
 // Records the message for ddl_last_error_message and returns DDL_ERR_RUNTIME.
 ddl_status runtime_error(hipError_t e, const char* what);
 

@@ -911,7 +911,8 @@ struct DdlRdaPlan {
     };
     struct Frag {
         Class cls[kNumRowClasses];
-        std::vector<uint32_t> other;  // descriptors that always take the one-tensor path
+        std::vector<uint32_t> other;   // descriptors that always take the one-tensor path
+        std::vector<uint32_t> direct;  // descriptors merged by direct averaging instead
     };
     std::vector<uint64_t> group_len;  // per descriptor, clamped to its n
     std::vector<Frag> frags;
@@ -963,6 +964,11 @@ extern "C" ddl_status ddl_plan_set_rda_groups(ddl_plan* plan, const size_t* grou
         for (uint32_t d = fi.seg_begin; d < fi.seg_begin + fi.num_segs; ++d) {
             const DdlSegDesc& sd = T.segs[d];
             uint64_t g = group_len[T.origin[d]];
+            if (g == (size_t)-1) {  // this tensor takes direct averaging
+                R->group_len[d] = 0;
+                rf.direct.push_back(d);
+                continue;
+            }
             if (g == 0 || g > sd.n) g = sd.n;
             R->group_len[d] = g;
             Geometry geo;
@@ -1144,6 +1150,11 @@ extern "C" ddl_status ddl_plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, 
         }
         for (uint32_t d : rf.other) {
             const ddl_status st = one_tensor(f, wk, d);
+            if (st != DDL_OK) return st;
+        }
+        for (uint32_t d : rf.direct) {
+            const ddl_status st =
+                ddlh::launch_one_direct(T.segs[d], f.dt, wk.q, wk.lr, wk.mu, hip_stream);
             if (st != DDL_OK) return st;
         }
     }

@@ -159,6 +159,39 @@ def test_several_fragments_in_one_call_and_regrouping(ddl):
     plan.destroy()
 
 
+def test_direct_averaging_for_chosen_tensors(ddl):
+    """The paper merges the non-embedding parameters by RDA and the rest by direct averaging:
+    a tensor whose group length is RDA_DIRECT takes the direct merge inside the same call."""
+    M, mask = 4, [1, 1, 0, 1]
+    shapes = [(1003, 64), (600, 1024), (40, 4096), (5000, 16)]     # first and last: direct
+    direct = [True, False, False, True]
+    segs, refs, groups, tokens = [], [], [], None
+    for k, (rows, g) in enumerate(shapes):
+        n = rows * g
+        theta, v, learners, tok, _ = random_problem(9000 + k, n, M, torch.bfloat16, DEV)
+        tokens = tokens or tok
+        host = (ddl_synth.to_host_array(theta), ddl_synth.to_host_array(v), host_learners(learners))
+        if direct[k]:
+            refs.append(oracle.merge_fragment(*host, tokens, mask, 0.7, 0.9))
+        else:
+            refs.append(oracle.rda_merge_fragment(*host, tokens, mask, g, 0.7, 0.9))
+        bf = torch.zeros(n, dtype=torch.bfloat16, device=DEV)
+        segs.append((theta, v, learners, bf))
+        groups.append(ddl.RDA_DIRECT if direct[k] else g)
+    groups[-1] = -1                                      # the binding takes -1 as well
+    plan = ddl.Plan([ddl.Fragment(segs, M=M, learner_dtype=torch.bfloat16)])
+    plan.set_rda_groups(groups)
+    ws = torch.empty(max(256, plan.rda_workspace_bytes), dtype=torch.uint8, device=DEV)
+    plan.rda_merge([(0, tokens, mask, 0.7, 0.9)], ws)
+    torch.cuda.synchronize()
+    for k, ((theta, v, _, bf), ref) in enumerate(zip(segs, refs)):
+        assert_parity(ddl_synth.to_host_array(theta), ref[0], f"tensor {k} theta")
+        assert_parity(ddl_synth.to_host_array(v), ref[1], f"tensor {k} v")
+        assert np.array_equal(ddl_synth.to_host_array(bf),
+                              oracle.round_bf16(ddl_synth.to_host_array(theta))), f"tensor {k} bf16"
+    plan.destroy()
+
+
 def test_errors_leave_state_untouched(ddl):
     wl = ddl_synth.reduced("dense_block")
     data = [ddl_synth.make_fragment(wl, f, DEV) for f in wl.fragments]
