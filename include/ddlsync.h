@@ -238,9 +238,11 @@ typedef struct ddl_fragment {
  * every segment of every fragment; fragments of one call must be distinct (no Theta or v
  * range may appear twice: DDL_ERR_ALIAS).
  *
- * The segment descriptors are staged through a small library-owned, lazily grown pinned-host
- * and device buffer ring; a call may therefore allocate (first calls, or growth) and may wait
- * for a previous call that still uses the ring slot it needs.  Not capturable in a HIP graph.
+ * The segment descriptors are staged through library-owned, lazily grown pinned-host and
+ * device buffers, and the last 64 distinct tables stay there: a call that names the same
+ * fragments (same pointers and sizes) as an earlier one reuses its table without any copy.
+ * A call may allocate (new table, or growth) and may wait for an earlier call that still uses
+ * the buffer it takes over.  Not capturable in a HIP graph (use a plan for that).
  */
 DDL_API ddl_status ddl_merge_batch(const ddl_fragment* frags, int num_frags, void* hip_stream);
 

@@ -51,13 +51,19 @@ long g_max_blocks_per_cu = -1;  // -1: by learner type and count; 0: no cap; k: 
                                 // resident workgroups per compute unit
 
 constexpr int kMaxDevices = 16;
-constexpr int kSlots = 4;
+constexpr int kSlots = 64;
 
+// One staged descriptor table.  The pinned host copy doubles as the key of a small cache: a
+// later call that builds the very same table (the same fragments, i.e. the same pointers and
+// sizes) finds it here and needs no copy at all.
 struct Slot {
-    void* host = nullptr;  // pinned
+    void* host = nullptr;  // pinned; holds the image that `dev` holds (first `bytes` bytes)
     void* dev = nullptr;
     size_t cap = 0;
-    hipEvent_t done = nullptr;
+    size_t bytes = 0;      // 0: nothing valid staged
+    uint64_t hash = 0;
+    hipEvent_t done = nullptr;       // recorded after the last work that read `dev`
+    hipStream_t last_stream = nullptr;
     bool pending = false;
 };
 
@@ -572,31 +578,53 @@ ddl_status ddl_merge_batch(const ddl_fragment* frags, int num_frags, void* hip_s
     if (st != DDL_OK) return st;
     if (T.segs.empty()) return DDL_OK;
 
-    // Stage the descriptors: pinned host copy -> device, on the caller's stream.
-    Slot& sl = ds->slot[ds->next];
-    ds->next = (ds->next + 1) % kSlots;
-    if (sl.pending) {
-        DDL_HIP(hipEventSynchronize(sl.done));
-        sl.pending = false;
-    }
-    const size_t bytes = T.bytes();
-    if (bytes > sl.cap) {
-        if (sl.host) DDL_HIP(hipHostFree(sl.host));
-        if (sl.dev) DDL_HIP(hipFree(sl.dev));
-        sl.host = sl.dev = nullptr;
-        sl.cap = 0;
-        const size_t cap = std::max<size_t>(bytes * 2, 64 * 1024);
-        DDL_HIP(hipHostMalloc(&sl.host, cap, hipHostMallocDefault));
-        DDL_HIP(hipMalloc(&sl.dev, cap));
-        sl.cap = cap;
-    }
-    if (!sl.done) DDL_HIP(hipEventCreateWithFlags(&sl.done, hipEventDisableTiming));
-    T.copy_to(sl.host);
+    // The descriptors go to the device through a pinned host copy, on the caller's stream --
+    // unless an earlier call staged exactly this table, which is then used as it is.
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    DDL_HIP(hipMemcpyAsync(sl.dev, sl.host, bytes, hipMemcpyHostToDevice, stream));
-    st = launch_work(T, sl.dev, work, hip_stream);
+    const size_t bytes = T.bytes();
+    std::vector<char> image(bytes);
+    T.copy_to(image.data());
+    uint64_t hash = 1469598103934665603ull;  // FNV-1a
+    for (size_t i = 0; i < bytes; ++i) hash = (hash ^ (unsigned char)image[i]) * 1099511628211ull;
+    Slot* sl = nullptr;
+    for (Slot& c : ds->slot)
+        if (c.bytes == bytes && c.hash == hash && std::memcmp(c.host, image.data(), bytes) == 0) {
+            sl = &c;
+            break;
+        }
+    if (sl) {
+        // Staged on another stream and possibly not there yet: order this stream after it.
+        if (sl->pending && sl->last_stream != stream) DDL_HIP(hipStreamWaitEvent(stream, sl->done, 0));
+    } else {
+        sl = &ds->slot[ds->next];
+        ds->next = (ds->next + 1) % kSlots;
+        sl->bytes = 0;
+        if (sl->pending) {
+            DDL_HIP(hipEventSynchronize(sl->done));
+            sl->pending = false;
+        }
+        if (bytes > sl->cap) {
+            if (sl->host) DDL_HIP(hipHostFree(sl->host));
+            if (sl->dev) DDL_HIP(hipFree(sl->dev));
+            sl->host = sl->dev = nullptr;
+            sl->cap = 0;
+            const size_t cap = std::max<size_t>(bytes * 2, 16 * 1024);
+            DDL_HIP(hipHostMalloc(&sl->host, cap, hipHostMallocDefault));
+            DDL_HIP(hipMalloc(&sl->dev, cap));
+            sl->cap = cap;
+        }
+        if (!sl->done) DDL_HIP(hipEventCreateWithFlags(&sl->done, hipEventDisableTiming));
+        std::memcpy(sl->host, image.data(), bytes);
+        DDL_HIP(hipMemcpyAsync(sl->dev, sl->host, bytes, hipMemcpyHostToDevice, stream));
+        sl->bytes = bytes;
+        sl->hash = hash;
+    }
+    st = launch_work(T, sl->dev, work, hip_stream);
     // Record even after a failed launch: the copy above may still be in flight.
-    if (hipEventRecord(sl.done, stream) == hipSuccess) sl.pending = true;
+    if (hipEventRecord(sl->done, stream) == hipSuccess) {
+        sl->pending = true;
+        sl->last_stream = stream;
+    }
     return st;
 }
 

@@ -205,6 +205,53 @@ def test_many_batches_reuse_the_staging_ring(ddl):
             check_segment(s, refs[si], f"run {k} seg {si}")
 
 
+def test_staged_tables_are_cached_and_evicted(ddl):
+    """ddl_merge_batch keeps the descriptor tables it staged and reuses one when the same
+    fragments come again (no copy), also from another stream; with more distinct fragments
+    than it keeps, old tables are evicted and staged anew.  Two rounds over 80 fragments, the
+    calls alternating between two streams; every tensor must show exactly two syncs."""
+    n, M = 5000, 3
+    tok, mask = [5, 6, 7], [1, 1, 1]
+    frags = []
+    for k in range(80):
+        th, v, ls, _, _ = random_problem(4000 + k, n + k, M, torch.bfloat16, DEV)
+        h = (ddl_synth.to_host_array(th), ddl_synth.to_host_array(v),
+             [ddl_synth.to_host_array(x) for x in ls])
+        r1 = oracle.merge_fragment(h[0], h[1], h[2], tok, mask, 0.7, 0.9)
+        # the second sync starts from the fp32 state the GPU holds after the first; feed the
+        # oracle its own first result rounded to fp32 (the two differ by far less than the bar)
+        r2 = oracle.merge_fragment(r1[0].astype(np.float32), r1[1].astype(np.float32), h[2], tok,
+                                   mask, 0.7, 0.9)
+        frags.append((ddl.Fragment([(th, v, ls)], tok, mask, 0.7, 0.9, M=M,
+                                   learner_dtype=torch.bfloat16), th, v, ls, r2))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for rnd in range(2):
+        for k, (fr, *_rest) in enumerate(frags):
+            # fragment k always on the same stream within a round, the other one next round,
+            # and rounds are separated by a full synchronisation: syncs of one fragment stay
+            # ordered
+            with torch.cuda.stream(streams[(k + rnd) % 2]):
+                ddl.merge_batch([fr])
+        torch.cuda.synchronize()
+    for k, (_, th, v, ls, r2) in enumerate(frags):
+        check_segment(ddl_synth.SegmentData(th, v, ls), r2, f"fragment {k}")
+    # the same fragment many times in a row on alternating streams, ordered by events
+    fr, th, v, ls, _ = frags[0]
+    ref = (ddl_synth.to_host_array(th), ddl_synth.to_host_array(v))
+    h_ls = [ddl_synth.to_host_array(x) for x in ls]
+    for i in range(6):
+        ref = oracle.merge_fragment(ref[0].astype(np.float32), ref[1].astype(np.float32), h_ls, tok,
+                                    mask, 0.7, 0.9)
+        cur, prev = streams[i % 2], streams[(i + 1) % 2]
+        cur.wait_stream(prev)
+        with torch.cuda.stream(cur):
+            ddl.merge_batch([fr])
+    torch.cuda.synchronize()
+    err_t = np.abs(ddl_synth.to_host_array(th) - ref[0]).max()
+    assert err_t < 5e-6, err_t      # six fp32 roundings of the carried state against fp64
+
+
 @pytest.mark.parametrize("tpb,cap", [(1, 0), (2, 0), (3, 4), (7, 0), (64, 8), (1024, 3)])
 def test_launch_shape_options(ddl, tpb, cap):
     """Workgroups that walk several tiles (across tensor and fragment boundaries) and capped
