@@ -33,7 +33,14 @@
  *   - Theta and v ranges must not overlap each other nor any contributing learner range
  *     (DDL_ERR_ALIAS); learner ranges may overlap one another.
  *   - Entry points may be called from several host threads; calls that touch the same Theta
- *     or v must be ordered by the caller (same stream, or events).
+ *     or v must be ordered by the caller (same stream, or events).  No launch path takes a
+ *     lock.
+ *   - Process-wide state, all of it: (1) the launch-shape options of ddl_set_option, atomics
+ *     that every later call on any thread reads -- a measurement aid, results never depend on
+ *     them; (2) the staging cache of ddl_merge_batch (per device, up to 64 descriptor tables in
+ *     library-owned pinned-host and device buffers, behind one mutex that is held while that
+ *     call enqueues, never while it waits for the GPU; freed when the process ends).  Plans
+ *     hold everything else.
  *   - lr and mu must be finite and >= 0.
  */
 #ifndef DDLSYNC_H
@@ -64,6 +71,12 @@ typedef enum { DDL_F32 = 0, DDL_BF16 = 1 } ddl_dtype;
 
 /* Library version, major * 10000 + minor * 100 + patch. */
 DDL_API int ddl_version(void);
+
+/* Static string naming the sources this library was built from: twelve hex digits of a hash
+ * over the kernel and host sources and this header ("unknown" if the build did not set it).
+ * Profile summaries record it next to counter figures, so that a figure taken on other
+ * kernels is not mistaken for a current one. */
+DDL_API const char* ddl_build_id(void);
 
 /* Static string for a status code. */
 DDL_API const char* ddl_status_string(ddl_status s);
@@ -242,7 +255,8 @@ typedef struct ddl_fragment {
  * device buffers, and the last 64 distinct tables stay there: a call that names the same
  * fragments (same pointers and sizes) as an earlier one reuses its table without any copy.
  * A call may allocate (new table, or growth) and may wait for an earlier call that still uses
- * the buffer it takes over.  Not capturable in a HIP graph (use a plan for that).
+ * the buffer it takes over.  Not capturable in a HIP graph: on a stream that is being captured
+ * the call returns DDL_ERR_INVALID_ARG and enqueues nothing (use a plan for that).
  */
 DDL_API ddl_status ddl_merge_batch(const ddl_fragment* frags, int num_frags, void* hip_stream);
 

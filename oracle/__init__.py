@@ -294,19 +294,3 @@ def q4_merge_fragment(theta: np.ndarray, v: np.ndarray, codes: Sequence[np.ndarr
     if rc != OK:
         raise OracleError(rc)
     return theta_out, v_out
-
-
-def merge_batch(fragments) -> list:
-    """A batch is, by definition, its fragments merged one after another, each segment of a
-    fragment with that fragment's own weights, lr and mu (a fragment is a set of whole
-    tensors, Section 5.1).  ``fragments`` is a list of dicts with keys ``segments`` (list of
-    (theta, v, learners) host-array triples), ``token_counts``, ``quorum_mask``, ``lr``,
-    ``mu``.  Returns a list (per fragment) of lists (per segment) of (theta_new, v_new)."""
-    out = []
-    for f in fragments:
-        res = []
-        for theta, v, learners in f["segments"]:
-            res.append(merge_fragment(theta, v, learners, f["token_counts"], f["quorum_mask"],
-                                      f["lr"], f["mu"]))
-        out.append(res)
-    return out

@@ -60,6 +60,7 @@ def _load() -> ctypes.CDLL:
     u64p, u8p = ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint8)
     f64p, vpp = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_void_p)
     lib.ddl_version.restype = ctypes.c_int
+    lib.ddl_build_id.restype = ctypes.c_char_p
     lib.ddl_status_string.argtypes = [ctypes.c_int]
     lib.ddl_status_string.restype = ctypes.c_char_p
     lib.ddl_last_error_message.restype = ctypes.c_char_p
@@ -186,6 +187,11 @@ def _learner_table(learners: Sequence[Optional[torch.Tensor]], n: int, dtype_cod
 
 def version() -> int:
     return _lib.ddl_version()
+
+
+def build_id() -> str:
+    """ddl_build_id: hash of the sources the loaded library was built from."""
+    return _lib.ddl_build_id().decode()
 
 
 def compute_weights(token_counts, quorum_mask) -> List[float]:

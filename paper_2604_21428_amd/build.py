@@ -5,6 +5,7 @@ library lands next to this file so that it travels with the source tree.
 """
 from __future__ import annotations
 
+import hashlib
 import os
 import re
 import subprocess
@@ -23,6 +24,22 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
          "-Wno-unused-const-variable", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+def source_id() -> str:
+    """Twelve hex digits identifying the kernel and host sources the library is built from
+    (every file under csrc/ plus the public header): what ``ddl_build_id()`` returns, and
+    what a profile summary records so that a stale counter figure can be told from a current
+    one."""
+    h = hashlib.sha256()
+    files = sorted(os.listdir(CSRC))
+    for name in files:
+        if name.endswith((".hip", ".h")):
+            with open(os.path.join(CSRC, name), "rb") as fh:
+                h.update(name.encode() + b"\0" + fh.read())
+    with open(os.path.join(HERE, "..", "include", "ddlsync.h"), "rb") as fh:
+        h.update(b"ddlsync.h\0" + fh.read())
+    return h.hexdigest()[:12]
 
 
 def _compile(src: str, extra) -> str:
@@ -45,8 +62,9 @@ def _compile(src: str, extra) -> str:
 def build(extra_flags=(), out: str = LIB_PATH, verbose: bool = False) -> str:
     """Compile every HIP source and link the shared library.  Always recompiles."""
     os.makedirs(BUILD_DIR, exist_ok=True)
+    extra = list(extra_flags) + [f'-DDDL_BUILD_ID="{source_id()}"']
     with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
-        objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
+        objs = list(ex.map(lambda s: _compile(s, extra), SOURCES))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", out]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:

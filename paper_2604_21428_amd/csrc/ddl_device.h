@@ -10,6 +10,8 @@
 #pragma once
 #include <stdint.h>
 
+#include <atomic>
+
 #define DDL_MAXL 16         // learners per fragment, = DDL_MAX_LEARNERS of the public header
 #define DDL_MAX_ITEMS 16    // fragments per launch
 #define DDL_BLOCK 256       // threads per workgroup: 4 wavefronts of 64
@@ -68,4 +70,4 @@ int ddl_launch_copy(void* dst, const void* src, uint64_t n16, uint32_t grid, voi
 
 // Launch-shape knob of the one-kernel RDA shape (set through ddl_set_option): at most this
 // many workgroups resident per compute unit (0: no cap), enforced with unused dynamic LDS.
-extern long ddl_opt_rda_blocks_per_cu;
+extern std::atomic<long> ddl_opt_rda_blocks_per_cu;

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <mutex>
@@ -19,7 +20,7 @@ using namespace ddlh;
 
 static_assert(DDL_MAXL == DDL_MAX_LEARNERS, "device and public learner limits differ");
 
-long ddl_opt_rda_blocks_per_cu = 0;
+std::atomic<long> ddl_opt_rda_blocks_per_cu{0};
 
 namespace {
 
@@ -44,11 +45,14 @@ namespace {
 // ------------------------------------------------------------------------------------------
 // options and per-device state
 // ------------------------------------------------------------------------------------------
-std::mutex g_mu;  // guards options, device state and the staging ring
-long g_tiles_per_block = 1;    // consecutive tiles a workgroup walks
-long g_tile_rotate = 64;       // group size of the tile rotation (0: off); see rotate_tile()
-long g_max_blocks_per_cu = -1;  // -1: by learner type and count; 0: no cap; k: at most k
-                                // resident workgroups per compute unit
+// The launch-shape options are process-wide atomics: a launch reads each one once, so a call
+// racing with ddl_set_option sees either the old or the new value, never a torn one.  No
+// lock is taken on any launch path; the only lock guards the staging cache of ddl_merge_batch.
+std::atomic<long> g_tiles_per_block{1};     // consecutive tiles a workgroup walks
+std::atomic<long> g_tile_rotate{64};        // group size of the tile rotation (0: off)
+std::atomic<long> g_max_blocks_per_cu{-1};  // -1: by learner type and count; 0: no cap; k: at
+                                            // most k resident workgroups per compute unit
+std::mutex g_stage_mu;                      // guards g_dev (the staging cache) only
 
 constexpr int kMaxDevices = 16;
 constexpr int kSlots = 64;
@@ -85,10 +89,9 @@ ddl_status device_state(DeviceState** out)
     return DDL_OK;
 }
 
-uint32_t grid_for(uint32_t total_tiles)
+uint32_t grid_for(uint32_t total_tiles, uint32_t tiles_per_block)
 {
-    const uint64_t g = (uint64_t)g_tiles_per_block;
-    return (uint32_t)(((uint64_t)total_tiles + g - 1) / g);
+    return (uint32_t)(((uint64_t)total_tiles + tiles_per_block - 1) / tiles_per_block);
 }
 
 // Dynamic LDS requested per workgroup purely to cap residency: floor(LDS per CU / k), kept
@@ -107,7 +110,8 @@ long auto_blocks_per_cu(int elem_bytes, int Mq)
 
 uint32_t lds_cap_bytes(int elem_bytes, int Mq)
 {
-    const long k = g_max_blocks_per_cu < 0 ? auto_blocks_per_cu(elem_bytes, Mq) : g_max_blocks_per_cu;
+    const long opt = g_max_blocks_per_cu.load(std::memory_order_relaxed);
+    const long k = opt < 0 ? auto_blocks_per_cu(elem_bytes, Mq) : opt;
     if (k <= 0) return 0;
     uint32_t b = (uint32_t)(DDL_LDS_PER_CU / k) & ~511u;
     return b > 64 * 1024 ? 64 * 1024 : b;
@@ -116,7 +120,7 @@ uint32_t lds_cap_bytes(int elem_bytes, int Mq)
 }  // namespace
 
 uint32_t ddlh::merge_lds_cap_bytes(int elem_bytes, int Mq) { return lds_cap_bytes(elem_bytes, Mq); }
-uint32_t ddlh::tile_rotate() { return (uint32_t)g_tile_rotate; }
+uint32_t ddlh::tile_rotate() { return (uint32_t)g_tile_rotate.load(std::memory_order_relaxed); }
 
 // ------------------------------------------------------------------------------------------
 // weights
@@ -222,23 +226,34 @@ inline size_t elem_size(ddl_dtype d) { return d == DDL_BF16 ? 2 : 4; }
 
 inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
+// Appends [p, p + elem * n); false if the end is not representable (the range would wrap
+// around the address space: no such array exists, and a wrapped end would hide an overlap).
+bool add_range(const void* p, size_t elem, size_t n, bool out, std::vector<Range>& r)
+{
+    size_t bytes = 0;
+    uintptr_t hi = 0;
+    if (__builtin_mul_overflow(elem, n, &bytes) ||
+        __builtin_add_overflow((uintptr_t)p, bytes, &hi))
+        return false;
+    r.push_back({(uintptr_t)p, hi, out});
+    return true;
+}
+
 // Appends the ranges of one segment; false if a needed pointer is NULL or misaligned for its
-// element type.  `learner_bits` selects which learners' ranges count.
+// element type, or a range wraps.  `learner_bits` selects which learners' ranges count.
 bool add_segment_ranges(const float* theta, const float* v, const void* theta_bf16,
                         const void* const* learners, uint32_t learner_bits, ddl_dtype dt, size_t n,
                         std::vector<Range>& r)
 {
     if (!theta || !v || !aligned(theta, 4) || !aligned(v, 4) || !aligned(theta_bf16, 2))
         return false;
-    r.push_back({(uintptr_t)theta, (uintptr_t)theta + 4 * n, true});
-    r.push_back({(uintptr_t)v, (uintptr_t)v + 4 * n, true});
-    if (theta_bf16) r.push_back({(uintptr_t)theta_bf16, (uintptr_t)theta_bf16 + 2 * n, true});
+    if (!add_range(theta, 4, n, true, r) || !add_range(v, 4, n, true, r)) return false;
+    if (theta_bf16 && !add_range(theta_bf16, 2, n, true, r)) return false;
     const size_t b = elem_size(dt);
     for (int m = 0; m < DDL_MAXL; ++m) {
         if (!(learner_bits >> m & 1)) continue;
         const void* p = learners[m];
-        if (!p || !aligned(p, b)) return false;
-        r.push_back({(uintptr_t)p, (uintptr_t)p + b * n, false});
+        if (!p || !aligned(p, b) || !add_range(p, b, n, false, r)) return false;
     }
     return true;
 }
@@ -388,8 +403,8 @@ ddl_status launch_work(const Table& T, const void* d_table, std::vector<Work>& w
         a.segs = static_cast<const DdlSegDesc*>(d_table);
         a.coarse = reinterpret_cast<const uint32_t*>(static_cast<const char*>(d_table) +
                                                      T.seg_bytes());
-        a.tiles_per_block = (uint32_t)g_tiles_per_block;
-        a.rotate = (int32_t)g_tile_rotate;
+        a.tiles_per_block = (uint32_t)g_tiles_per_block.load(std::memory_order_relaxed);
+        a.rotate = (int32_t)tile_rotate();
         uint64_t tiles = 0;
         int items = 0;
         size_t j = i;
@@ -407,7 +422,7 @@ ddl_status launch_work(const Table& T, const void* d_table, std::vector<Work>& w
             a.num_items = items;
             a.total_tiles = (uint32_t)tiles;
             const int e = ddl_launch_merge((int)f0.dt, work[i].q.Mq, false,
-                                           grid_for(a.total_tiles),
+                                           grid_for(a.total_tiles, a.tiles_per_block),
                                            lds_cap_bytes((int)elem_size(f0.dt), work[i].q.Mq),
                                            stream, a);
             if (e != (int)hipSuccess) return runtime_error((hipError_t)e, "merge kernel launch");
@@ -435,18 +450,17 @@ ddl_status merge_flat(float* theta, float* v, void* theta_bf16, const void* cons
         return DDL_ERR_INVALID_ARG;
     if (ranges_alias(ranges)) return DDL_ERR_ALIAS;
 
-    std::lock_guard<std::mutex> lock(g_mu);
     const uint64_t tiles = (n + DDL_TILE - 1) / DDL_TILE;
     if (tiles > 0x7fffffffull) return DDL_ERR_INVALID_ARG;
     DdlLaunchArgs a;
     std::memset(&a, 0, sizeof a);
-    a.tiles_per_block = (uint32_t)g_tiles_per_block;
-    a.rotate = (int32_t)g_tile_rotate;
+    a.tiles_per_block = (uint32_t)g_tiles_per_block.load(std::memory_order_relaxed);
+    a.rotate = (int32_t)tile_rotate();
     a.total_tiles = (uint32_t)tiles;
     a.num_items = 1;
     fill_desc(a.flat, theta, v, theta_bf16, lp, M, n, 0);
     fill_item(a.item[0], q, lr, mu, 0, 1, 0);
-    const int e = ddl_launch_merge((int)dt, q.Mq, true, grid_for(a.total_tiles),
+    const int e = ddl_launch_merge((int)dt, q.Mq, true, grid_for(a.total_tiles, a.tiles_per_block),
                                    lds_cap_bytes((int)elem_size(dt), q.Mq), stream, a);
     if (e != (int)hipSuccess) return runtime_error((hipError_t)e, "merge kernel launch");
     return DDL_OK;
@@ -460,20 +474,19 @@ ddl_status merge_flat(float* theta, float* v, void* theta_bf16, const void* cons
 ddl_status ddlh::launch_one_direct(const DdlSegDesc& desc, ddl_dtype dt, const Quorum& q, float lr,
                                    float mu, void* stream)
 {
-    std::lock_guard<std::mutex> lock(g_mu);
     const uint64_t tiles = (desc.n + DDL_TILE - 1) / DDL_TILE;
     if (tiles == 0) return DDL_OK;
     if (tiles > 0x7fffffffull) return DDL_ERR_INVALID_ARG;
     DdlLaunchArgs a;
     std::memset(&a, 0, sizeof a);
-    a.tiles_per_block = (uint32_t)g_tiles_per_block;
-    a.rotate = (int32_t)g_tile_rotate;
+    a.tiles_per_block = (uint32_t)g_tiles_per_block.load(std::memory_order_relaxed);
+    a.rotate = (int32_t)tile_rotate();
     a.total_tiles = (uint32_t)tiles;
     a.num_items = 1;
     a.flat = desc;
     a.flat.tile_begin = 0;
     fill_item(a.item[0], q, lr, mu, 0, 1, 0);
-    const int e = ddl_launch_merge((int)dt, q.Mq, true, grid_for(a.total_tiles),
+    const int e = ddl_launch_merge((int)dt, q.Mq, true, grid_for(a.total_tiles, a.tiles_per_block),
                                    lds_cap_bytes((int)elem_size(dt), q.Mq), stream, a);
     if (e != (int)hipSuccess) return runtime_error((hipError_t)e, "merge kernel launch");
     return DDL_OK;
@@ -481,7 +494,12 @@ ddl_status ddlh::launch_one_direct(const DdlSegDesc& desc, ddl_dtype dt, const Q
 
 extern "C" {
 
-int ddl_version(void) { return 100; }
+int ddl_version(void) { return 200; }
+
+#ifndef DDL_BUILD_ID
+#define DDL_BUILD_ID "unknown"
+#endif
+const char* ddl_build_id(void) { return DDL_BUILD_ID; }
 
 const char* ddl_status_string(ddl_status s)
 {
@@ -569,23 +587,34 @@ ddl_status ddl_merge_batch(const ddl_fragment* frags, int num_frags, void* hip_s
         work.push_back(wk);
     }
 
-    std::lock_guard<std::mutex> lock(g_mu);
-    DeviceState* ds = nullptr;
-    ddl_status st = device_state(&ds);
-    if (st != DDL_OK) return st;
+    // The staging below copies from a reusable pinned buffer and records an event: neither
+    // may become a node of a graph under capture (a replay would read a buffer that later
+    // calls overwrite, and the event would never be seen as recorded).  A plan is the form
+    // for capture.
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    DDL_HIP(hipStreamIsCapturing(stream, &cap));
+    if (cap != hipStreamCaptureStatusNone) return DDL_ERR_INVALID_ARG;
+
     Table T;
-    st = build_table(frags, num_frags, bits.data(), T);
+    ddl_status st = build_table(frags, num_frags, bits.data(), T);
     if (st != DDL_OK) return st;
     if (T.segs.empty()) return DDL_OK;
-
-    // The descriptors go to the device through a pinned host copy, on the caller's stream --
-    // unless an earlier call staged exactly this table, which is then used as it is.
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const size_t bytes = T.bytes();
     std::vector<char> image(bytes);
     T.copy_to(image.data());
     uint64_t hash = 1469598103934665603ull;  // FNV-1a
     for (size_t i = 0; i < bytes; ++i) hash = (hash ^ (unsigned char)image[i]) * 1099511628211ull;
+
+    // The descriptors go to the device through a pinned host copy, on the caller's stream --
+    // unless an earlier call staged exactly this table, which is then used as it is.  The lock
+    // covers the cache bookkeeping and this call's enqueues, never a wait for the GPU: a slot
+    // whose last use has not finished is passed over, and if every slot is busy the lock is
+    // dropped while waiting for one.
+    std::unique_lock<std::mutex> lock(g_stage_mu);
+    DeviceState* ds = nullptr;
+    st = device_state(&ds);
+    if (st != DDL_OK) return st;
     Slot* sl = nullptr;
     for (Slot& c : ds->slot)
         if (c.bytes == bytes && c.hash == hash && std::memcmp(c.host, image.data(), bytes) == 0) {
@@ -596,22 +625,36 @@ ddl_status ddl_merge_batch(const ddl_fragment* frags, int num_frags, void* hip_s
         // Staged on another stream and possibly not there yet: order this stream after it.
         if (sl->pending && sl->last_stream != stream) DDL_HIP(hipStreamWaitEvent(stream, sl->done, 0));
     } else {
-        sl = &ds->slot[ds->next];
-        ds->next = (ds->next + 1) % kSlots;
-        sl->bytes = 0;
-        if (sl->pending) {
-            DDL_HIP(hipEventSynchronize(sl->done));
-            sl->pending = false;
+        for (;;) {
+            for (int tries = 0; tries < kSlots && !sl; ++tries) {
+                Slot& c = ds->slot[ds->next];
+                ds->next = (ds->next + 1) % kSlots;
+                if (c.pending) {
+                    const hipError_t q = hipEventQuery(c.done);
+                    if (q == hipErrorNotReady) continue;
+                    if (q != hipSuccess) return runtime_error(q, "hipEventQuery");
+                    c.pending = false;
+                }
+                sl = &c;
+            }
+            if (sl) break;
+            // Every slot is still in use by enqueued work: wait for the oldest one without
+            // holding the lock (events are never destroyed), then look again.
+            hipEvent_t oldest = ds->slot[ds->next].done;
+            lock.unlock();
+            DDL_HIP(hipEventSynchronize(oldest));
+            lock.lock();
         }
+        sl->bytes = 0;
         if (bytes > sl->cap) {
             if (sl->host) DDL_HIP(hipHostFree(sl->host));
             if (sl->dev) DDL_HIP(hipFree(sl->dev));
             sl->host = sl->dev = nullptr;
             sl->cap = 0;
-            const size_t cap = std::max<size_t>(bytes * 2, 16 * 1024);
-            DDL_HIP(hipHostMalloc(&sl->host, cap, hipHostMallocDefault));
-            DDL_HIP(hipMalloc(&sl->dev, cap));
-            sl->cap = cap;
+            const size_t cap_bytes = std::max<size_t>(bytes * 2, 16 * 1024);
+            DDL_HIP(hipHostMalloc(&sl->host, cap_bytes, hipHostMallocDefault));
+            DDL_HIP(hipMalloc(&sl->dev, cap_bytes));
+            sl->cap = cap_bytes;
         }
         if (!sl->done) DDL_HIP(hipEventCreateWithFlags(&sl->done, hipEventDisableTiming));
         std::memcpy(sl->host, image.data(), bytes);
@@ -640,11 +683,7 @@ ddl_status ddl_plan_create(const ddl_fragment* frags, int num_frags, ddl_plan** 
     ddl_plan* p = new (std::nothrow) ddl_plan();
     if (!p) return DDL_ERR_RUNTIME;
     std::vector<uint32_t> bits((size_t)num_frags, 0xffffffffu);
-    ddl_status st;
-    {
-        std::lock_guard<std::mutex> lock(g_mu);
-        st = build_table(frags, num_frags, bits.data(), p->table);
-    }
+    const ddl_status st = build_table(frags, num_frags, bits.data(), p->table);
     if (st != DDL_OK) {
         delete p;
         return st;
@@ -692,7 +731,6 @@ ddl_status ddl_plan_merge(ddl_plan* plan, const ddl_sync* syncs, int count, void
         if (f.num_segs > 0 && (wk.q.present_bits & ~f.nonnull_bits)) return DDL_ERR_INVALID_ARG;
         work.push_back(wk);
     }
-    std::lock_guard<std::mutex> lock(g_mu);
     return launch_work(T, plan->d_table, work, hip_stream);
 }
 
@@ -735,7 +773,6 @@ ddl_status ddl_copy_probe(void* dst, const void* src, size_t bytes, void* hip_st
 ddl_status ddl_set_option(const char* name, long value)
 {
     if (!name) return DDL_ERR_INVALID_ARG;
-    std::lock_guard<std::mutex> lock(g_mu);
     if (!std::strcmp(name, "tiles_per_block")) {
         if (value < 1 || value > 1024) return DDL_ERR_INVALID_ARG;
         g_tiles_per_block = value;
@@ -762,7 +799,6 @@ ddl_status ddl_set_option(const char* name, long value)
 ddl_status ddl_get_option(const char* name, long* value_out)
 {
     if (!name || !value_out) return DDL_ERR_INVALID_ARG;
-    std::lock_guard<std::mutex> lock(g_mu);
     if (!std::strcmp(name, "tiles_per_block")) {
         *value_out = g_tiles_per_block;
         return DDL_OK;

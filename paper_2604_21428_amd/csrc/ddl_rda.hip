@@ -790,7 +790,7 @@ inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) =
 // rda_blocks_per_cu; 0: no cap).
 uint32_t row_lds_cap()
 {
-    const long cap = ddl_opt_rda_blocks_per_cu;
+    const long cap = ddl_opt_rda_blocks_per_cu.load(std::memory_order_relaxed);
     uint32_t lds = cap > 0 ? (uint32_t)(DDL_LDS_PER_CU / cap) & ~511u : 0u;
     return lds > 60 * 1024 ? 60 * 1024 : lds;  // static LDS of the kernel comes on top
 }

@@ -53,6 +53,39 @@ def check_segment(seg: ddl_synth.SegmentData, ref, what: str, lo: int = 0,
     return max(e1, e2)
 
 
+def full_parity(seg: ddl_synth.SegmentData, theta0: torch.Tensor, v0: torch.Tensor,
+                frag: ddl_synth.FragmentSpec, what: str, chunk: int = 1 << 26,
+                nthreads: int = 16) -> Tuple[float, int]:
+    """EVERY element of a segment after its in-place GPU sync against the oracle run on the
+    state before it (``theta0``, ``v0``: copies taken before the sync; the learners are not
+    written).  Works chunk by chunk so that host memory stays bounded at any tensor size; the
+    oracle's threaded form is pinned bit-identical to its serial loop.  The fp64 subtraction
+    and the comparison with the bound run on the device (test plumbing); a chunk that fails
+    is re-checked on the host for the report.  Returns (max abs err, elements compared)."""
+    n = theta0.numel()
+    worst, count = 0.0, 0
+    # buffers of learners outside the quorum are not copied (the oracle never reads them)
+    used = [x if (q and t > 0) else None
+            for x, q, t in zip(seg.learners, frag.quorum_mask, frag.token_counts)]
+    for lo in range(0, n, chunk):
+        hi = min(n, lo + chunk)
+        ref = oracle.merge_fragment(ddl_synth.to_host_array(theta0[lo:hi]),
+                                    ddl_synth.to_host_array(v0[lo:hi]),
+                                    host_learners(used, lo, hi), frag.token_counts,
+                                    frag.quorum_mask, frag.lr, frag.mu, nthreads=nthreads)
+        for got, want, name in ((seg.theta[lo:hi], ref[0], "theta"), (seg.v[lo:hi], ref[1], "v")):
+            w = torch.from_numpy(want).to(got.device)
+            err = (got.double() - w).abs_()
+            ok = bool((err <= TOL * (1.0 + w.abs())).all())
+            if not ok:
+                assert_parity(ddl_synth.to_host_array(got), want, f"{what} {name} [{lo},{hi})")
+                raise AssertionError(f"{what} {name} [{lo},{hi}): device and host checks disagree")
+            worst = max(worst, float(err.max()))
+            del w, err
+        count += hi - lo
+    return worst, count
+
+
 def random_problem(seed: int, n: int, M: int, dtype: torch.dtype, device, mask=None,
                    offset: int = 0, v_sigma: float = 1e-4):
     """theta, v, learners (device) plus token counts and mask.  ``offset`` > 0 makes every

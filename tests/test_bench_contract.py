@@ -42,3 +42,9 @@ def test_one_json_line_with_the_agreed_keys():
     assert cpu["kind"] == "oracle" and cpu["unit"] == "params/s" and cpu["value"] > 0
     assert cpu["cores"] >= 1 and isinstance(cpu["sample"], str)
     assert cpu["max_abs_err_vs_oracle"] is not None and cpu["max_err_over_bound"] < 1.0
+    # parity is total: every element of the workload went through the oracle
+    assert cpu["elements_compared"] == d["config"]["params"] and cpu["parity_ok"] is True
+    assert cpu["fragments_covered"] == [0]
+    assert roof["traffic"] is None or isinstance(roof["traffic"], int)
+    assert isinstance(roof["traffic_source"], str)
+    assert d["config"]["library_build"]

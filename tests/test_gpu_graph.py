@@ -66,3 +66,39 @@ def test_captured_sync_replays_like_eager(ddl, name):
                 assert torch.equal(s.v, graph_data[fi][si].v), (replay, fi, si)
     gplan.destroy()
     eplan.destroy()
+
+
+def test_merge_batch_refuses_a_capturing_stream(ddl):
+    """The one-shot batch call stages descriptors through a reusable pinned buffer and records
+    an event, neither of which may become a graph node: under capture it must return an
+    argument error, enqueue nothing and leave the state untouched, while a plan merge captured
+    beside it goes through."""
+    wl = ddl_synth.reduced("dense_block")
+    f = wl.fragments[0]
+    segs = ddl_synth.make_fragment(wl, f, DEV)
+    other = ddl_synth.make_fragment(wl, f, DEV)
+    before = [(s.theta.clone(), s.v.clone()) for s in segs]
+    frag = ddl.Fragment([(s.theta, s.v, s.learners) for s in segs], f.token_counts, f.quorum_mask,
+                        f.lr, f.mu, M=f.M, learner_dtype=torch.bfloat16)
+    plan = _plan(ddl, wl, [other])
+    call = plan.prepare([(0, f.token_counts, f.quorum_mask, f.lr, f.mu)])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        plan.merge(call)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        plan.merge(call)
+        with pytest.raises(ddl.DdlError) as ei:
+            ddl.merge_batch([frag])
+    assert ei.value.status == ddl.DDL_ERR_INVALID_ARG
+    g.replay()
+    torch.cuda.synchronize()
+    for s, (th, v) in zip(segs, before):
+        assert torch.equal(s.theta, th) and torch.equal(s.v, v)
+    ddl.merge_batch([frag])                     # outside capture the same call works
+    torch.cuda.synchronize()
+    assert not torch.equal(segs[0].theta, before[0][0])
+    plan.destroy()
