@@ -81,8 +81,9 @@ DDL_API const char* ddl_build_id(void);
 /* Static string for a status code. */
 DDL_API const char* ddl_status_string(ddl_status s);
 
-/* Text of the last DDL_ERR_RUNTIME on the calling thread ("" if none). Thread-local storage
- * owned by the library, valid until the thread's next failing call. */
+/* Text of the last DDL_ERR_RUNTIME on the calling thread ("" if none); a refusal for lack of
+ * scratch space (DDL_ERR_INVALID_ARG of the RDA entry points) also leaves the sizes here.
+ * Thread-local storage owned by the library, valid until the thread's next failing call. */
 DDL_API const char* ddl_last_error_message(void);
 
 /*

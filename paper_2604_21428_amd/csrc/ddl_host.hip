@@ -34,6 +34,8 @@ ddl_status ddlh::runtime_error(hipError_t e, const char* what)
     return DDL_ERR_RUNTIME;
 }
 
+void ddlh::set_error_message(const char* text) { g_err = text ? text : ""; }
+
 namespace {
 
 #define DDL_HIP(call)                                              \

@@ -63,6 +63,8 @@ ddl_status launch_one_direct(const DdlSegDesc& desc, ddl_dtype dt, const Quorum&
                              float mu, void* stream);
 // Records the message for ddl_last_error_message and returns DDL_ERR_RUNTIME.
 ddl_status runtime_error(hipError_t e, const char* what);
+// Records a message for ddl_last_error_message (for an error that is not a HIP failure).
+void set_error_message(const char* text);
 
 }  // namespace ddlh
 

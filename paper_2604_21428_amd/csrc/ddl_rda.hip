@@ -30,6 +30,7 @@
 #include <cmath>
 #include <cstring>
 #include <new>
+#include <string>
 #include <vector>
 
 #include "../../include/ddlsync.h"
@@ -841,12 +842,14 @@ extern "C" size_t ddl_rda_workspace_bytes(size_t n, size_t group_len, int M)
     return g.bytes;
 }
 
-extern "C" ddl_status ddl_rda_merge_fragment(float* theta, float* v,
-                                             const void* const* learner_params,
-                                             ddl_dtype learner_dtype, const uint64_t* token_counts,
-                                             const uint8_t* quorum_mask, int M, size_t n,
-                                             size_t group_len, float lr, float mu, void* workspace,
-                                             size_t workspace_bytes, void* hip_stream)
+namespace {
+
+// Shared by the two one-tensor entry points.  workspace: caller's or the library's scratch.
+ddl_status rda_merge_one(float* theta, float* v, const void* const* learner_params,
+                         ddl_dtype learner_dtype, const uint64_t* token_counts,
+                         const uint8_t* quorum_mask, int M, size_t n, size_t group_len, float lr,
+                         float mu, void* workspace, size_t workspace_bytes, const char* who,
+                         void* hip_stream)
 {
     double w[DDL_MAX_LEARNERS];
     ddl_status st = ddl_compute_weights(token_counts, quorum_mask, M, w);
@@ -863,29 +866,44 @@ extern "C" ddl_status ddl_rda_merge_fragment(float* theta, float* v,
     const size_t b = learner_dtype == DDL_BF16 ? 2 : 4;
     int Mq = 0;
     bool vec_ok = aligned(theta, 16) && aligned(v, 16) && std::min(group_len, n) % 4 == 0;
-    // Overlap rules as everywhere: Theta, v and the workspace may overlap nothing.
+    // Overlap rules as everywhere: Theta, v and the workspace may overlap nothing.  (A fixed
+    // array: this path must not allocate, not even on the host.)
     struct Range { uintptr_t lo, hi; bool out; };
-    std::vector<Range> r;
-    r.push_back({(uintptr_t)theta, (uintptr_t)theta + 4 * n, true});
-    r.push_back({(uintptr_t)v, (uintptr_t)v + 4 * n, true});
+    Range r[DDL_MAX_LEARNERS + 3];
+    int nr = 0;
+    auto add = [&](const void* p, size_t elem, bool out) {
+        size_t bytes = 0;
+        uintptr_t hi = 0;
+        if (__builtin_mul_overflow(elem, n, &bytes) ||
+            __builtin_add_overflow((uintptr_t)p, bytes, &hi))
+            return false;
+        r[nr++] = {(uintptr_t)p, hi, out};
+        return true;
+    };
+    if (!add(theta, 4, true) || !add(v, 4, true)) return DDL_ERR_INVALID_ARG;
     for (int m = 0; m < M; ++m) {
         if (!(w[m] > 0.0)) continue;
         const void* p = learner_params[m];
-        if (!p || !aligned(p, b)) return DDL_ERR_INVALID_ARG;
+        if (!p || !aligned(p, b) || !add(p, b, false)) return DDL_ERR_INVALID_ARG;
         vec_ok = vec_ok && aligned(p, 16);
         a.learner[Mq] = (uint64_t)(uintptr_t)p;
         a.w[Mq] = (float)w[m];
-        r.push_back({(uintptr_t)p, (uintptr_t)p + b * n, false});
         ++Mq;
     }
     Geometry g;
     if (!geometry(n, group_len, Mq, g)) return DDL_ERR_INVALID_ARG;
-    if (!workspace || !aligned(workspace, 256) || workspace_bytes < g.bytes)
+    if (!workspace || !aligned(workspace, 256)) return DDL_ERR_INVALID_ARG;
+    if (workspace_bytes < g.bytes) {
+        ddlh::set_error_message((std::string(who) + ": this tensor and grouping need " +
+                                 std::to_string(g.bytes) + " bytes of scratch, " +
+                                 std::to_string(workspace_bytes) + " are there").c_str());
         return DDL_ERR_INVALID_ARG;
-    r.push_back({(uintptr_t)workspace, (uintptr_t)workspace + g.bytes, true});
-    std::sort(r.begin(), r.end(), [](const Range& x, const Range& y) { return x.lo < y.lo; });
+    }
+    r[nr++] = {(uintptr_t)workspace, (uintptr_t)workspace + g.bytes, true};
+    std::sort(r, r + nr, [](const Range& x, const Range& y) { return x.lo < y.lo; });
     uintptr_t hi_any = 0, hi_out = 0;
-    for (const Range& x : r) {
+    for (int i = 0; i < nr; ++i) {
+        const Range& x = r[i];
         if (x.out ? x.lo < hi_any : x.lo < hi_out) return DDL_ERR_ALIAS;
         hi_any = std::max(hi_any, x.hi);
         if (x.out) hi_out = std::max(hi_out, x.hi);
@@ -899,6 +917,20 @@ extern "C" ddl_status ddl_rda_merge_fragment(float* theta, float* v,
     a.lr = lr;
     a.mu = mu;
     return launch_one(learner_dtype, Mq, a, g, workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+}  // namespace
+
+extern "C" ddl_status ddl_rda_merge_fragment(float* theta, float* v,
+                                             const void* const* learner_params,
+                                             ddl_dtype learner_dtype, const uint64_t* token_counts,
+                                             const uint8_t* quorum_mask, int M, size_t n,
+                                             size_t group_len, float lr, float mu, void* workspace,
+                                             size_t workspace_bytes, void* hip_stream)
+{
+    return rda_merge_one(theta, v, learner_params, learner_dtype, token_counts, quorum_mask, M, n,
+                         group_len, lr, mu, workspace, workspace_bytes, "ddl_rda_merge_fragment",
+                         hip_stream);
 }
 
 // ------------------------------------------------------------------------------------------
