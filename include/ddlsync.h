@@ -39,8 +39,8 @@
  *     that every later call on any thread reads -- a measurement aid, results never depend on
  *     them; (2) the staging cache of ddl_merge_batch (per device, up to 64 descriptor tables in
  *     library-owned pinned-host and device buffers, behind one mutex that is held while that
- *     call enqueues, never while it waits for the GPU; freed when the process ends).  Plans
- *     hold everything else.
+ *     call enqueues, never while it waits for the GPU; freed when the process ends); (3) the
+ *     fixed scratch array of ddl_rda_merge_fragment_static.  Plans hold everything else.
  *   - lr and mu must be finite and >= 0.
  */
 #ifndef DDLSYNC_H
@@ -183,6 +183,33 @@ DDL_API ddl_status ddl_rda_merge_fragment(float* theta, float* v, const void* co
                                           const uint8_t* quorum_mask, int M, size_t n,
                                           size_t group_len, float lr, float mu, void* workspace,
                                           size_t workspace_bytes, void* hip_stream);
+
+/*
+ * ddl_rda_merge_fragment for callers that cannot allocate device memory and have no workspace
+ * to hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments without the workspace, same kernels, same results; the scratch
+ * is a fixed array of ddl_rda_static_scratch_bytes() = 4 MiB inside the library's device
+ * image, which every GPU the library runs on holds until the process ends.  The call
+ * allocates nothing on the device (no hipMalloc, no hipFree, no allocating library routine);
+ * its first call on a device looks the array's address up.
+ *
+ * A tensor and grouping that need more scratch than that -- ddl_rda_workspace_bytes(n,
+ * group_len, M) above 4 MiB, which takes hundreds of millions of elements in one group or
+ * hundreds of thousands of groups -- are refused with DDL_ERR_INVALID_ARG before anything is
+ * enqueued (ddl_last_error_message gives the sizes); use the workspace form for those.
+ * All calls on one GPU share the one array and it keeps the last call's contents; nothing in
+ * it has to start at zero (every kernel writes what it later reads).  Calls that may overlap
+ * in time on one GPU (different streams, different threads) race on it: keep them on one
+ * stream or order them with events.
+ */
+DDL_API size_t ddl_rda_static_scratch_bytes(void);
+DDL_API ddl_status ddl_rda_merge_fragment_static(float* theta, float* v,
+                                                 const void* const* learner_params,
+                                                 ddl_dtype learner_dtype,
+                                                 const uint64_t* token_counts,
+                                                 const uint8_t* quorum_mask, int M, size_t n,
+                                                 size_t group_len, float lr, float mu,
+                                                 void* hip_stream);
 
 /*
  * 4-bit outer gradients (Appendix D.3, "Outer gradients compression": outer gradients are

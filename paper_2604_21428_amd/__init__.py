@@ -91,6 +91,11 @@ def _load() -> ctypes.CDLL:
                                            u8p, ctypes.c_int, ctypes.c_size_t, ctypes.c_size_t,
                                            ctypes.c_float, ctypes.c_float, ctypes.c_void_p,
                                            ctypes.c_size_t, ctypes.c_void_p]
+    lib.ddl_rda_static_scratch_bytes.restype = ctypes.c_size_t
+    lib.ddl_rda_merge_fragment_static.argtypes = [ctypes.c_void_p, ctypes.c_void_p, vpp,
+                                                  ctypes.c_int, u64p, u8p, ctypes.c_int,
+                                                  ctypes.c_size_t, ctypes.c_size_t,
+                                                  ctypes.c_float, ctypes.c_float, ctypes.c_void_p]
     lib.ddl_plan_set_rda_groups.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_size_t),
                                             ctypes.c_size_t]
     lib.ddl_plan_rda_workspace_bytes.argtypes = [ctypes.c_void_p]
@@ -114,7 +119,7 @@ def _load() -> ctypes.CDLL:
                  "ddl_plan_merge", "ddl_plan_destroy", "ddl_set_option", "ddl_get_option",
                  "ddl_copy_probe", "ddl_balanced_fragments", "ddl_merge_fragment_bcast",
                  "ddl_rda_merge_fragment", "ddl_plan_set_rda_groups", "ddl_plan_rda_merge",
-                 "ddl_q4_encode", "ddl_q4_merge_fragment"):
+                 "ddl_q4_encode", "ddl_q4_merge_fragment", "ddl_rda_merge_fragment_static"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -274,6 +279,30 @@ def rda_merge_fragment(theta: torch.Tensor, v: torch.Tensor,
                                        group_len, lr, mu, workspace.data_ptr(),
                                        workspace.numel() * workspace.element_size(),
                                        _stream_handle(stream)), "ddl_rda_merge_fragment")
+
+
+def rda_static_scratch_bytes() -> int:
+    """ddl_rda_static_scratch_bytes: size of the library's fixed scratch array."""
+    return _lib.ddl_rda_static_scratch_bytes()
+
+
+def rda_merge_fragment_static(theta: torch.Tensor, v: torch.Tensor,
+                              learner_params: Sequence[Optional[torch.Tensor]], token_counts,
+                              quorum_mask, group_len: int, lr: float, mu: float, stream=None,
+                              learner_dtype=None) -> None:
+    """ddl_rda_merge_fragment_static: rda_merge_fragment on the library's own fixed scratch
+    array; allocates nothing."""
+    n = theta.numel()
+    if v.numel() != n:
+        raise ValueError("theta and v differ in size")
+    M = len(learner_params)
+    table, code = _learner_table(learner_params, n,
+                                 None if learner_dtype is None else _dtype_code(learner_dtype))
+    _check(_lib.ddl_rda_merge_fragment_static(_state_ptr(theta, "theta"), _state_ptr(v, "v"),
+                                              table, code, _u64(token_counts, M),
+                                              _u8(quorum_mask, M), M, n, group_len, lr, mu,
+                                              _stream_handle(stream)),
+           "ddl_rda_merge_fragment_static")
 
 
 def q4_encode(theta: torch.Tensor, learner: torch.Tensor, block_len: int,

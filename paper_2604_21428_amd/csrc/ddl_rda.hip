@@ -29,6 +29,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -931,6 +932,68 @@ extern "C" ddl_status ddl_rda_merge_fragment(float* theta, float* v,
     return rda_merge_one(theta, v, learner_params, learner_dtype, token_counts, quorum_mask, M, n,
                          group_len, lr, mu, workspace, workspace_bytes, "ddl_rda_merge_fragment",
                          hip_stream);
+}
+
+// ------------------------------------------------------------------------------------------
+// The same merge for callers that cannot allocate and have no workspace to pass: the scratch
+// is a fixed array in the library's device image.  Each GPU holds its own copy at its own
+// address, which is looked up once per device; host code only ever uses that looked-up
+// address, never the array's name.
+// ------------------------------------------------------------------------------------------
+#define DDL_RDA_STATIC_SCRATCH_BYTES (4u << 20)
+static __device__ __align__(256) unsigned char scratch[DDL_RDA_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxScratchDevices = 16;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxScratchDevices] = {};
+
+// Device address of `scratch` on the current device.
+ddl_status static_scratch(void** out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return ddlh::runtime_error(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxScratchDevices) {
+        ddlh::set_error_message("device index out of range");
+        return DDL_ERR_RUNTIME;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return ddlh::runtime_error(e, "hipGetSymbolAddress(scratch)");
+        if (!p) {
+            ddlh::set_error_message("hipGetSymbolAddress(scratch) returned a null address");
+            return DDL_ERR_RUNTIME;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return DDL_OK;
+}
+
+}  // namespace
+
+extern "C" size_t ddl_rda_static_scratch_bytes(void) { return DDL_RDA_STATIC_SCRATCH_BYTES; }
+
+extern "C" ddl_status ddl_rda_merge_fragment_static(float* theta, float* v,
+                                                    const void* const* learner_params,
+                                                    ddl_dtype learner_dtype,
+                                                    const uint64_t* token_counts,
+                                                    const uint8_t* quorum_mask, int M, size_t n,
+                                                    size_t group_len, float lr, float mu,
+                                                    void* hip_stream)
+{
+    void* ws = nullptr;
+    const ddl_status st = static_scratch(&ws);
+    if (st != DDL_OK) return st;
+    // Every kernel of the merge writes the part of the scratch it later reads (chunk sums,
+    // coefficients, scales), so nothing has to be cleared between calls.
+    return rda_merge_one(theta, v, learner_params, learner_dtype, token_counts, quorum_mask, M, n,
+                         group_len, lr, mu, ws, DDL_RDA_STATIC_SCRATCH_BYTES,
+                         "ddl_rda_merge_fragment_static", hip_stream);
 }
 
 // ------------------------------------------------------------------------------------------
