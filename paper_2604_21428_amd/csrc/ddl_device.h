@@ -50,10 +50,14 @@ struct DdlLaunchArgs {
     // i << shift (clamped to the last descriptor past the end), so a tile's descriptor lies
     // between entries i and i + 1 -- usually the same one, and no search is needed.
     const uint32_t* coarse;
-    uint32_t total_tiles;
+    uint32_t total_tiles;      // tiles of all fragments of the launch
+    uint32_t tile_base;        // first tile this grid covers (a long launch goes out in parts)
     uint32_t tiles_per_block;  // >= 1
     int32_t num_items;
     int32_t rotate;  // 0: workgroup b takes tile b; k > 0: tiles rotated within groups of k
+#ifdef DDL_TRACE
+    uint64_t* trace;  // diagnostic build only: per workgroup {start clock, XCD, tile}
+#endif
     DdlItem item[DDL_MAX_ITEMS];
     DdlSegDesc flat;         // the one segment of the flat variant
 };
@@ -64,6 +68,11 @@ static_assert(sizeof(DdlLaunchArgs) <= 4096, "kernel argument block limit");
 // lds_bytes of (unused) dynamic LDS per workgroup cap how many workgroups a compute unit holds.
 int ddl_launch_merge(int dtype, int Mq, bool flat, uint32_t grid, uint32_t lds_bytes, void* stream,
                      const DdlLaunchArgs& args);
+
+// The same for a launch of args.total_tiles tiles cut into parts of at most max_tiles tiles
+// (0: one part), enqueued back to back: sets args.tile_base per part.
+int ddl_launch_merge_parts(int dtype, int Mq, bool flat, uint32_t max_tiles, uint32_t lds_bytes,
+                           void* stream, DdlLaunchArgs& args);
 
 // Launches the plain 16-byte-per-lane copy of n16 * 16 bytes; grid = ceil(n16 / DDL_BLOCK).
 int ddl_launch_copy(void* dst, const void* src, uint64_t n16, uint32_t grid, void* stream);

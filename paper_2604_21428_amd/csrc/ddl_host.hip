@@ -54,6 +54,12 @@ std::atomic<long> g_tiles_per_block{1};     // consecutive tiles a workgroup wal
 std::atomic<long> g_tile_rotate{64};        // group size of the tile rotation (0: off)
 std::atomic<long> g_max_blocks_per_cu{-1};  // -1: by learner type and count; 0: no cap; k: at
                                             // most k resident workgroups per compute unit
+#ifdef DDL_TRACE
+std::atomic<long> g_trace_buffer{0};  // diagnostic build: device address of the trace records
+#endif
+std::atomic<long> g_max_tiles_per_launch{-1};  // 0: a launch is one grid; k: grids of at most
+                                               // k tiles; -1: k chosen from the bytes per tile
+std::atomic<long> g_part_megabytes{2500};      // the byte size -1 aims at
 std::mutex g_stage_mu;                      // guards g_dev (the staging cache) only
 
 constexpr int kMaxDevices = 16;
@@ -91,9 +97,22 @@ ddl_status device_state(DeviceState** out)
     return DDL_OK;
 }
 
-uint32_t grid_for(uint32_t total_tiles, uint32_t tiles_per_block)
+// A long launch goes out as several grids, back to back on the stream.  The eight XCDs each
+// work through their own share of a grid's workgroups at their own pace, and nothing
+// re-aligns them before the grid ends: over some hundred thousand workgroups their positions
+// drift apart, the window of DRAM pages in flight widens, and the achieved rate drops by
+// 3-6 %.  A grid boundary re-aligns them at the price of one drain (about 3 us).  Measured on
+// MI355X, grids of 0.3-0.5 ms (2-3 GB of traffic) are the best trade for every learner count.
+// elem_bytes: bytes per learner element (0: 4-bit codes); extra: other bytes per element.
+uint32_t max_tiles_per_launch(int elem_bytes, int Mq, int extra = 0)
 {
-    return (uint32_t)(((uint64_t)total_tiles + tiles_per_block - 1) / tiles_per_block);
+    const long opt = g_max_tiles_per_launch.load(std::memory_order_relaxed);
+    if (opt >= 0) return (uint32_t)opt;
+    const uint64_t per_tile =
+        (uint64_t)DDL_TILE * (16 + extra + (elem_bytes ? elem_bytes * Mq : (Mq + 1) / 2));
+    const uint64_t tiles =
+        (uint64_t)g_part_megabytes.load(std::memory_order_relaxed) * 1000000ull / per_tile;
+    return (uint32_t)std::max<uint64_t>(tiles, 4096);
 }
 
 // Dynamic LDS requested per workgroup purely to cap residency: floor(LDS per CU / k), kept
@@ -423,10 +442,13 @@ ddl_status launch_work(const Table& T, const void* d_table, std::vector<Work>& w
         if (items > 0) {
             a.num_items = items;
             a.total_tiles = (uint32_t)tiles;
-            const int e = ddl_launch_merge((int)f0.dt, work[i].q.Mq, false,
-                                           grid_for(a.total_tiles, a.tiles_per_block),
-                                           lds_cap_bytes((int)elem_size(f0.dt), work[i].q.Mq),
-                                           stream, a);
+#ifdef DDL_TRACE
+            a.trace = reinterpret_cast<uint64_t*>(g_trace_buffer.load());
+#endif
+            const int e = ddl_launch_merge_parts(
+                (int)f0.dt, work[i].q.Mq, false,
+                max_tiles_per_launch((int)elem_size(f0.dt), work[i].q.Mq),
+                lds_cap_bytes((int)elem_size(f0.dt), work[i].q.Mq), stream, a);
             if (e != (int)hipSuccess) return runtime_error((hipError_t)e, "merge kernel launch");
         }
         if (j == i) return DDL_ERR_INVALID_ARG;  // cannot happen: a lone fragment always fits
@@ -462,8 +484,9 @@ ddl_status merge_flat(float* theta, float* v, void* theta_bf16, const void* cons
     a.num_items = 1;
     fill_desc(a.flat, theta, v, theta_bf16, lp, M, n, 0);
     fill_item(a.item[0], q, lr, mu, 0, 1, 0);
-    const int e = ddl_launch_merge((int)dt, q.Mq, true, grid_for(a.total_tiles, a.tiles_per_block),
-                                   lds_cap_bytes((int)elem_size(dt), q.Mq), stream, a);
+    const int e = ddl_launch_merge_parts((int)dt, q.Mq, true,
+                                         max_tiles_per_launch((int)elem_size(dt), q.Mq),
+                                         lds_cap_bytes((int)elem_size(dt), q.Mq), stream, a);
     if (e != (int)hipSuccess) return runtime_error((hipError_t)e, "merge kernel launch");
     return DDL_OK;
 }
@@ -488,8 +511,9 @@ ddl_status ddlh::launch_one_direct(const DdlSegDesc& desc, ddl_dtype dt, const Q
     a.flat = desc;
     a.flat.tile_begin = 0;
     fill_item(a.item[0], q, lr, mu, 0, 1, 0);
-    const int e = ddl_launch_merge((int)dt, q.Mq, true, grid_for(a.total_tiles, a.tiles_per_block),
-                                   lds_cap_bytes((int)elem_size(dt), q.Mq), stream, a);
+    const int e = ddl_launch_merge_parts((int)dt, q.Mq, true,
+                                         max_tiles_per_launch((int)elem_size(dt), q.Mq),
+                                         lds_cap_bytes((int)elem_size(dt), q.Mq), stream, a);
     if (e != (int)hipSuccess) return runtime_error((hipError_t)e, "merge kernel launch");
     return DDL_OK;
 }
@@ -790,6 +814,22 @@ ddl_status ddl_set_option(const char* name, long value)
         g_tile_rotate = value;
         return DDL_OK;
     }
+#ifdef DDL_TRACE
+    if (!std::strcmp(name, "trace_buffer")) {
+        g_trace_buffer = value;
+        return DDL_OK;
+    }
+#endif
+    if (!std::strcmp(name, "max_tiles_per_launch")) {
+        if (value < -1 || value > 0x7fffffffl) return DDL_ERR_INVALID_ARG;
+        g_max_tiles_per_launch = value;
+        return DDL_OK;
+    }
+    if (!std::strcmp(name, "part_megabytes")) {
+        if (value < 1 || value > 1000000) return DDL_ERR_INVALID_ARG;
+        g_part_megabytes = value;
+        return DDL_OK;
+    }
     if (!std::strcmp(name, "rda_blocks_per_cu")) {
         if (value != 0 && (value < 3 || value > 64)) return DDL_ERR_INVALID_ARG;
         ddl_opt_rda_blocks_per_cu = value;
@@ -811,6 +851,14 @@ ddl_status ddl_get_option(const char* name, long* value_out)
     }
     if (!std::strcmp(name, "tile_rotate")) {
         *value_out = g_tile_rotate;
+        return DDL_OK;
+    }
+    if (!std::strcmp(name, "max_tiles_per_launch")) {
+        *value_out = g_max_tiles_per_launch;
+        return DDL_OK;
+    }
+    if (!std::strcmp(name, "part_megabytes")) {
+        *value_out = g_part_megabytes;
         return DDL_OK;
     }
     if (!std::strcmp(name, "rda_blocks_per_cu")) {

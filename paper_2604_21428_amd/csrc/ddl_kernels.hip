@@ -25,6 +25,8 @@
 //     written once.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "ddl_device.h"
 
 #ifndef DDL_PAIR
@@ -114,7 +116,17 @@ template <typename L, int MQ, bool FLAT>
 __global__ void __launch_bounds__(DDL_BLOCK) ddl_merge_kernel(const DdlLaunchArgs a)
 {
     typedef typename L::elem elem;
-    uint32_t tile = rotate_tile(blockIdx.x, gridDim.x, (uint32_t)a.rotate) * a.tiles_per_block;
+    uint32_t tile = a.tile_base +
+                    rotate_tile(blockIdx.x, gridDim.x, (uint32_t)a.rotate) * a.tiles_per_block;
+#ifdef DDL_TRACE
+    // Diagnostic build: when each workgroup started, on which XCD, with which tile.
+    if (a.trace && threadIdx.x == 0) {
+        const uint32_t xcc = __builtin_amdgcn_s_getreg((3 << 11) | 20) & 0xf;  // HW_REG_XCC_ID
+        uint64_t* rec = a.trace + 2 * (uint64_t)(a.tile_base / a.tiles_per_block + blockIdx.x);
+        rec[0] = wall_clock64();
+        rec[1] = ((uint64_t)xcc << 32) | tile;
+    }
+#endif
     const uint32_t last = min(tile + a.tiles_per_block, a.total_tiles);
 
     while (tile < last) {
@@ -238,6 +250,30 @@ int ddl_launch_merge(int dtype, int Mq, bool flat, uint32_t grid, uint32_t lds_b
     hipLaunchKernelGGL(k, dim3(grid), dim3(DDL_BLOCK), lds_bytes, static_cast<hipStream_t>(stream),
                        args);
     return (int)hipGetLastError();
+}
+
+int ddl_launch_merge_parts(int dtype, int Mq, bool flat, uint32_t max_tiles, uint32_t lds_bytes,
+                           void* stream, DdlLaunchArgs& args)
+{
+    const uint32_t tpb = args.tiles_per_block;
+    const uint64_t total = args.total_tiles;
+    // Equal parts, each a whole number of workgroups (so that they tile the range exactly)
+    // and of rotation groups (so that only the last part ends in a partial group).
+    uint64_t part = total;
+    if (max_tiles != 0 && total > max_tiles) {
+        const uint64_t parts = (total + max_tiles - 1) / max_tiles;
+        const uint64_t unit = (uint64_t)tpb * (args.rotate > 0 ? (uint32_t)args.rotate : 1u);
+        part = (total + parts - 1) / parts;
+        part = (part + unit - 1) / unit * unit;
+    }
+    for (uint64_t base = 0; base < total; base += part) {
+        const uint64_t tiles = std::min<uint64_t>(part, total - base);
+        args.tile_base = (uint32_t)base;
+        const int e = ddl_launch_merge(dtype, Mq, flat, (uint32_t)((tiles + tpb - 1) / tpb),
+                                       lds_bytes, stream, args);
+        if (e != (int)hipSuccess) return e;
+    }
+    return (int)hipSuccess;
 }
 
 int ddl_launch_copy(void* dst, const void* src, uint64_t n16, uint32_t grid, void* stream)
