@@ -92,6 +92,8 @@ def parse_args():
     ap.add_argument("--tiles-per-block", type=int, default=None)
     ap.add_argument("--max-blocks-per-cu", type=int, default=None)
     ap.add_argument("--rda-blocks-per-cu", type=int, default=None)
+    ap.add_argument("--max-tiles-per-launch", type=int, default=None)
+    ap.add_argument("--part-megabytes", type=int, default=None)
     return ap.parse_args()
 
 
@@ -99,15 +101,17 @@ def parse_args():
 # HBM traffic from the committed counter runs
 # ------------------------------------------------------------------------------------------
 def profiled_traffic(ddl, workload, merge, default_shape):
-    """(bytes per launch or None, source string).  The figure comes from a line
-    ``TRAFFIC workload=<w> merge=<m> bytes_per_launch=<int> build_id=<id>`` of a summary under
+    """(HBM bytes of one step or None, source string).  The figure comes from a line
+    ``TRAFFIC workload=<w> merge=<m> bytes_per_step=<int> build_id=<id>`` of a summary under
     profiles/ (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this script, each scaled by the
-    same counter's reading for ddl_copy_probe).  It is reported only if it was taken on the
-    very sources the loaded library was built from and in the default launch shape; otherwise
+    same counter's reading for ddl_copy_probe, summed over the kernel launches of a step).  It is reported only if it was taken on the
+    very kernel sources the loaded library was built from (ddl_kernel_build_id) and in the
+    default launch shape; otherwise
     the value is null and the source string says why."""
     if not default_shape:
         return None, "not reported: launch-shape options differ from the profiled defaults"
-    here = ddl.build_id()
+    here = ddl.kernel_build_id("rda" if merge.startswith("rda") else
+                               "q4" if merge.startswith("q4") else "merge")
     stale = None
     pdir = os.path.join(ROOT, "profiles")
     for name in sorted(os.listdir(pdir)) if os.path.isdir(pdir) else []:
@@ -121,7 +125,7 @@ def profiled_traffic(ddl, workload, merge, default_shape):
                 if kv.get("workload") != workload or kv.get("merge") != merge:
                     continue
                 if kv.get("build_id") == here:
-                    return int(kv["bytes_per_launch"]), f"profiles/{name} (build {here})"
+                    return int(kv["bytes_per_step"]), f"profiles/{name} (build {here})"
                 stale = (f"profiles/{name} holds a figure taken on build {kv.get('build_id')}; "
                          f"this library is build {here}: not reported")
     return None, stale or "no counter run for this workload under profiles/"
@@ -160,29 +164,33 @@ def build_setup(args, wl, ddl, ddl_synth, torch, replicas=None):
                 s.bcast = (torch.empty(s.theta.numel(), dtype=torch.bfloat16, device="cuda:0")
                            if args.bcast else None)
         if args.merge == "q4":
-            # The learners' outer gradients are encoded once, outside the timed region, as a
-            # learner would send them; each fragment's codes and scales are one flat array per
-            # learner (its tensors back to back), Theta and v are views into flat arrays.
-            calls = []
-            for fi in wl.arrival_order:
-                f = wl.fragments[fi]
-                theta = torch.cat([s.theta for s in data[fi]])
-                v = torch.cat([s.v for s in data[fi]])
-                codes, scales = [], []
-                for m in range(f.M):
-                    if not (f.quorum_mask[m] and f.token_counts[m] > 0):
-                        codes.append(None)
-                        scales.append(None)
-                        continue
-                    c, sc = ddl.q4_encode(theta, torch.cat([s.learners[m] for s in data[fi]]),
-                                          args.q4_block)
-                    codes.append(c)
-                    scales.append(sc)
-                calls.append((f, theta, v, codes, scales))
-                data[fi] = None
+            # The learners' outer gradients are encoded once, tensor by tensor, outside the
+            # timed region, as a learner would send them; the parameter copies are then dropped
+            # (the 4-bit merge reads codes and scales only).
+            sources = []
+            for f, segs in zip(wl.fragments, data):
+                for s in segs:
+                    codes, scales = [], []
+                    for m in range(f.M):
+                        if f.quorum_mask[m] and f.token_counts[m] > 0:
+                            c, sc = ddl.q4_encode(s.theta, s.learners[m], args.q4_block)
+                        else:
+                            c, sc = None, None
+                        codes.append(c)
+                        scales.append(sc)
+                    s.learners = [None] * f.M
+                    s.q4 = (codes, scales)
+                    sources.append((codes, scales))
             torch.cuda.synchronize()
             torch.cuda.empty_cache()
-            copies.append((data, "q4", calls))
+            plan = ddl.Plan([ddl.Fragment([(s.theta, s.v, s.learners, s.bcast) for s in segs],
+                                          M=f.M, learner_dtype=dt[f.learner_dtype])
+                             for f, segs in zip(wl.fragments, data)])
+            plan.set_q4_sources(sources, args.q4_block)
+            calls = [plan.prepare([(fi, wl.fragments[fi].token_counts,
+                                    wl.fragments[fi].quorum_mask, wl.fragments[fi].lr,
+                                    wl.fragments[fi].mu)]) for fi in wl.arrival_order]
+            copies.append((data, ("q4-plan", plan, None), calls))
         elif args.merge == "rda" and args.api == "plan":
             plan = ddl.Plan([ddl.Fragment([(s.theta, s.v, s.learners, s.bcast) for s in segs],
                                           M=f.M, learner_dtype=dt[f.learner_dtype])
@@ -225,18 +233,19 @@ def build_setup(args, wl, ddl, ddl_synth, torch, replicas=None):
         """One step over one copy as a list of (fragment index, bytes, callable)."""
         _, plan, calls = copy
         out = []
-        if isinstance(plan, tuple):
+        if isinstance(plan, tuple) and plan[0] == "q4-plan":
+            _, qplan, _ = plan
+            for fi, c in zip(wl.arrival_order, calls):
+                nb = sum(s.theta.numel() * (16 + (2 if s.bcast is not None else 0)) +
+                         sum(cc.numel() + 4 * sc.numel()
+                             for cc, sc in zip(*s.q4) if cc is not None)
+                         for s in copy[0][fi])
+                out.append((fi, nb, lambda c=c, qplan=qplan: qplan.q4_merge(c)))
+        elif isinstance(plan, tuple):
             _, rplan, ws = plan
             for fi, c in zip(wl.arrival_order, calls):
                 out.append((fi, wl.fragments[fi].numel * wl.fragments[fi].bytes_per_param,
                             lambda c=c, rplan=rplan, ws=ws: rplan.rda_merge(c, ws)))
-        elif plan == "q4":
-            for f, theta, v, codes, scales in calls:
-                nb = theta.numel() * 16 + sum(c.numel() + 4 * sc.numel()
-                                              for c, sc in zip(codes, scales) if c is not None)
-                out.append((f.index, nb, lambda f=f, theta=theta, v=v, codes=codes, scales=scales:
-                            ddl.q4_merge_fragment(theta, v, codes, scales, f.token_counts,
-                                                  f.quorum_mask, args.q4_block, f.lr, f.mu)))
         elif plan == "rda":
             for s, f, g, ws in calls:
                 nb = s.theta.numel() * f.bytes_per_param
@@ -256,7 +265,7 @@ def build_setup(args, wl, ddl, ddl_synth, torch, replicas=None):
 
     su.launch_lists = [launch_list(c) for c in copies]
     su.launches_per_step = (wl.num_segments if args.api == "tensor" else len(su.launch_lists[0]))
-    if args.merge == "q4":
+    if args.merge == "q4":      # codes and scales as stored; the bf16 copy is counted there too
         su.alg_bytes = sum(nb for _, nb, _ in su.launch_lists[0])
     else:
         su.alg_bytes = wl.algorithmic_bytes + (2 * wl.numel if args.bcast else 0)
@@ -283,7 +292,7 @@ def host_cores():
 
 
 def parity_supported(args):
-    return (args.merge in ("avg", "rda") and args.api in ("plan", "batch") and
+    return (args.merge in ("avg", "rda", "q4") and args.api in ("plan", "batch") and
             args.syncs_per_call == 1 and not (args.merge == "rda" and args.api == "batch"))
 
 
@@ -318,16 +327,28 @@ def oracle_leg(args, su, torch, ddl_synth, budget_s, single_core_s, must_cover=(
         present = [bool(q) and t > 0 for q, t in zip(f.quorum_mask, f.token_counts)]
         for si, (s, (th0, v0)) in enumerate(zip(segs, before)):
             n = th0.numel()
-            g = su.rda_groups[fi][si] if su.rda_groups else 1
+            g = (su.rda_groups[fi][si] if su.rda_groups else
+                 args.q4_block if args.merge == "q4" else 1)   # chunks end on these boundaries
             # chunks end on group boundaries; a group longer than a chunk is taken whole
             chunk = max(g, PARITY_CHUNK // g * g) if g > 1 else PARITY_CHUNK
             for lo in range(0, n, chunk):
                 hi = min(n, lo + chunk)
                 th = ddl_synth.to_host_array(th0[lo:hi])
                 vv = ddl_synth.to_host_array(v0[lo:hi])
-                ls = [ddl_synth.to_host_array(x[lo:hi]) if p else None
+                ls = [ddl_synth.to_host_array(x[lo:hi]) if (p and x is not None) else None
                       for x, p in zip(s.learners, present)]
-                if args.merge == "rda":
+                if args.merge == "q4":
+                    B = args.q4_block
+                    cs = [c[lo // 2:(hi + 1) // 2].cpu().numpy() if c is not None else None
+                          for c in s.q4[0]]
+                    ss = [x[lo // B:-(-hi // B)].cpu().numpy() if x is not None else None
+                          for x in s.q4[1]]
+                    t0 = time.perf_counter()
+                    ref = oracle.q4_merge_fragment(th, vv, cs, ss, f.token_counts, f.quorum_mask,
+                                                   B, f.lr, f.mu)
+                    t_single += time.perf_counter() - t0
+                    n_single += hi - lo
+                elif args.merge == "rda":
                     t0 = time.perf_counter()
                     ref = oracle.rda_merge_fragment(th, vv, ls, f.token_counts, f.quorum_mask,
                                                     min(g, hi - lo), f.lr, f.mu)
@@ -378,7 +399,7 @@ def oracle_leg(args, su, torch, ddl_synth, budget_s, single_core_s, must_cover=(
         "sample": (f"{len(covered)} whole fragment(s) of workload {wl.name} (fragment indices "
                    f"{covered}): {done} of {wl.numel} params; "
                    + (f"fp64 scalar loop chunked over {cores} threads" if multi else
-                      "fp64 scalar loop on one core (the RDA oracle has no threaded form)")),
+                      "fp64 scalar loop on one core (this oracle function has no threaded form)")),
         "fragments_covered": covered,
         "params_covered": done,
         "value_1core": (n_single / t_single) if n_single else None,
@@ -433,10 +454,10 @@ def detail_pass(torch, su, reps, extra_bytes_per_step):
     return out
 
 
-def timed_region(args, su, torch, steps, warmup):
+def timed_region(args, su, ddl, torch, steps, warmup):
     """W untimed steps, then exactly K steps between synchronisations.  Returns (wall ms per
-    step, event ms per step); the events are recorded on torch's current stream, which is
-    the stream every call of a step is enqueued on."""
+    step, event ms per step, several streams?, kernel grids per step); the events are recorded
+    on torch's current stream, which is the stream every call of a step is enqueued on."""
     streams = [torch.cuda.Stream() for _ in range(args.streams)] if args.streams > 1 else None
 
     def step():
@@ -459,6 +480,12 @@ def timed_region(args, su, torch, steps, warmup):
         if streams is not None:
             for st in streams:
                 torch.cuda.current_stream().wait_stream(st)
+
+    # How many kernel grids a step enqueues (a long fragment goes out as several): counted by
+    # the library, over one untimed eager step.
+    g0 = ddl.get_option("grids_enqueued")
+    step()
+    grids_per_step = ddl.get_option("grids_enqueued") - g0
 
     if args.graph:
         eager_step = step
@@ -497,7 +524,8 @@ def timed_region(args, su, torch, steps, warmup):
     ev1.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    return (t1 - t0) * 1e3 / steps, ev0.elapsed_time(ev1) / steps, streams is not None
+    return ((t1 - t0) * 1e3 / steps, ev0.elapsed_time(ev1) / steps, streams is not None,
+            grids_per_step)
 
 
 def time_copy_probe(ddl, torch, nbytes=1 << 30, reps=20):
@@ -532,20 +560,23 @@ def measure(args, name, ddl, ddl_synth, torch, steps, warmup, parity_budget, mus
         must = must_cover_fn(wl) if must_cover_fn else ()
         cpu = oracle_leg(args, su, torch, ddl_synth, parity_budget,
                          single_core_s=5.0, must_cover=must)
-    wall_ms, gpu_ms, multi_stream = timed_region(args, su, torch, steps, warmup)
+    wall_ms, gpu_ms, multi_stream, grids = timed_region(args, su, ddl, torch, steps, warmup)
     detail = None
     if with_detail and not args.graph and not multi_stream:
-        detail = detail_pass(torch, su, min(steps, 40), 2 * wl.numel if args.bcast else 0)
-    # A step consists of merge-kernel launches only (no copies, no other kernels), so the event
-    # time per step divided by the launches per step is the average launch duration, gaps
-    # between back-to-back launches included.
-    kernel_ms = gpu_ms / su.launches_per_step
-    achieved = su.alg_bytes / su.launches_per_step / (kernel_ms * 1e-3) / 1e9
+        detail = detail_pass(torch, su, min(steps, 40),
+                             2 * wl.numel if (args.bcast and args.merge != "q4") else 0)
+    # A step consists of merge-kernel grids only (no copies, no other kernels), so the event
+    # time per step divided by the grids per step is the average duration of one kernel launch,
+    # the gaps between back-to-back launches included.
+    kernel_ms = gpu_ms / grids
+    achieved = su.alg_bytes / grids / (kernel_ms * 1e-3) / 1e9
     merge_tag = (args.merge if args.merge == "avg" else
                  f"q4/block{args.q4_block}" if args.merge == "q4" else f"rda/{args.rda_group}")
     plain = default_shape and not (args.bcast or args.balanced or args.graph or multi_stream or
                                    args.api != "plan" or args.syncs_per_call != 1)
     traffic, traffic_source = profiled_traffic(ddl, wl.name, merge_tag, plain)
+    if traffic is not None:
+        traffic = round(traffic / grids)      # per launch, like `achieved`
     summary = {
         "workload": wl.name,
         "params": wl.numel,
@@ -558,7 +589,8 @@ def measure(args, name, ddl, ddl_synth, torch, steps, warmup, parity_budget, mus
         "replicas": su.replicas,
         "ms_per_step": wall_ms,
         "params_per_s": wl.numel / (wall_ms * 1e-3),
-        "launches_per_step": su.launches_per_step,
+        "calls_per_step": su.launches_per_step,
+        "launches_per_step": grids,
         "avg_launch_ms": kernel_ms,
         "algorithmic_bytes_per_step": su.alg_bytes,
         "achieved": achieved,
@@ -581,8 +613,8 @@ def main():
             "bench.py: this build is single-GPU by design (the synchronizer path is element-wise "
             "and has no collectives here); run with --gpus 1.\n")
         sys.exit(2)
-    if args.merge == "q4" and (args.bcast or args.balanced or args.api != "plan"):
-        sys.stderr.write("bench.py: --merge q4 takes none of --bcast, --balanced, --api\n")
+    if args.merge == "q4" and args.api != "plan":
+        sys.stderr.write("bench.py: --merge q4 goes through the plan\n")
         sys.exit(2)
     if args.merge == "rda" and args.api == "batch":
         sys.stderr.write("bench.py: --merge rda goes with --api plan or --api tensor\n")
@@ -606,7 +638,9 @@ def main():
     default_shape = True
     for opt, val in (("tiles_per_block", args.tiles_per_block), ("tile_rotate", args.tile_rotate),
                      ("max_blocks_per_cu", args.max_blocks_per_cu),
-                     ("rda_blocks_per_cu", args.rda_blocks_per_cu)):
+                     ("rda_blocks_per_cu", args.rda_blocks_per_cu),
+                     ("max_tiles_per_launch", args.max_tiles_per_launch),
+                     ("part_megabytes", args.part_megabytes)):
         if val is not None:
             default_shape = default_shape and ddl.get_option(opt) == val
             ddl.set_option(opt, val)
@@ -679,6 +713,7 @@ def main():
             "merge": (args.merge if args.merge == "avg" else
                       f"q4/block{args.q4_block}" if args.merge == "q4" else
                       f"rda/{args.rda_group}"),
+            "calls_per_step": main_summary["calls_per_step"],
             "launches_per_step": main_summary["launches_per_step"],
             "syncs_per_call": args.syncs_per_call,
             "streams": args.streams,
@@ -689,6 +724,8 @@ def main():
             "tile_rotate": ddl.get_option("tile_rotate"),
             "max_blocks_per_cu": ddl.get_option("max_blocks_per_cu"),
             "library_build": ddl.build_id(),
+            "kernel_build": ddl.kernel_build_id("rda" if args.merge == "rda" else
+                                                "q4" if args.merge == "q4" else "merge"),
         },
         "achieved_gbps": main_summary["algorithmic_bytes_per_step"] /
                          (main_summary["ms_per_step"] * 1e-3) / 1e9,

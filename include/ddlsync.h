@@ -78,6 +78,11 @@ DDL_API int ddl_version(void);
  * kernels is not mistaken for a current one. */
 DDL_API const char* ddl_build_id(void);
 
+/* The same for one kernel family -- "merge" (direct averaging), "rda", "q4": a hash over only
+ * the sources that decide that family's code, so that an unrelated change elsewhere does not
+ * age its counter figures.  "" for an unknown name. */
+DDL_API const char* ddl_kernel_build_id(const char* kernel);
+
 /* Static string for a status code. */
 DDL_API const char* ddl_status_string(ddl_status s);
 
@@ -359,6 +364,40 @@ DDL_API ddl_status ddl_plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, int
                                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * 4-bit outer gradients (Appendix D.3; format as defined at ddl_q4_encode) through a plan: the
+ * fragments named by the syncs are merged from the learners' codes and scales instead of their
+ * parameter copies, whole fragments of many tensors per kernel launch, exactly as
+ * ddl_plan_merge does for bf16 / fp32 learners.  Each tensor of a learner is encoded on its own
+ * (blocks never straddle tensors), as ddl_q4_encode writes it.
+ *
+ * ddl_plan_set_q4_sources   segs[s] for every segment the plan was created with, empty ones
+ *                           included, fragment by fragment in creation order (num_segments =
+ *                           their total): HOST arrays of M DEVICE pointers to learner m's
+ *                           codes ((n + 1) / 2 bytes) and scales (ceil(n / block_len) floats) of
+ *                           that tensor, 4-byte aligned; both NULL for a learner that will never
+ *                           contribute there.  The plan's learner pointers are not used by the
+ *                           4-bit merge and may have been NULL at creation.  Theta and v of every
+ *                           non-empty tensor must be 16-byte aligned (a theta_bf16, 8-byte).
+ *                           Uploads a device table (allocates; not for capture); may be called
+ *                           again once no merge of the plan is running.
+ * ddl_plan_q4_merge         as ddl_plan_merge.  Only enqueues kernels; a segment's optional
+ *                           theta_bf16 receives the new Theta as bf16 in the same pass.
+ * Errors as ddl_plan_merge; INVALID_ARG also if the sources were never set, num_segments does
+ * not match, block_len is bad, an array is misaligned, or a contributing learner has no
+ * sources in some tensor of a fragment that is due; ALIAS if a source array overlaps Theta, v
+ * or a bf16 copy of the plan.  Theta and v are untouched on error.
+ */
+typedef struct ddl_q4_segment {
+    const uint8_t* const* codes; /* HOST array of M DEVICE pointers (M of the fragment)         */
+    const float* const* scales;  /* HOST array of M DEVICE pointers                              */
+} ddl_q4_segment;
+
+DDL_API ddl_status ddl_plan_set_q4_sources(ddl_plan* plan, const ddl_q4_segment* segs,
+                                           size_t num_segments, size_t block_len);
+DDL_API ddl_status ddl_plan_q4_merge(ddl_plan* plan, const ddl_sync* syncs, int count,
+                                     void* hip_stream);
+
+/*
  * Balanced tensor fragmentation (Section 5.1; Appendix C, "Balanced tensor fragmentation"):
  * greedy number partitioning of the model's tensors into num_fragments fragments -- tensors are
  * taken in descending order of size and each goes to the fragment whose total is the smallest
@@ -382,14 +421,22 @@ DDL_API ddl_status ddl_balanced_fragments(const uint64_t* sizes, int num_tensors
 DDL_API ddl_status ddl_copy_probe(void* dst, const void* src, size_t bytes, void* hip_stream);
 
 /*
- * Launch-shape knobs, for measurement.  Names: "tiles_per_block" (how many consecutive
- * 1024-element tiles one workgroup walks, 1..1024; default 1), "max_blocks_per_cu" (0: no cap;
- * k in 3..64: at most k workgroups resident per compute unit; -1, the default: chosen by
- * learner type and count, 3 to 6), "tile_rotate" (0: workgroup b takes run-of-tiles b; k in
- * 2..4096: the index is rotated within groups of k by the group's number, which spreads every
- * XCD's accesses over all memory channels; default 64), "rda_blocks_per_cu" (the residency cap
- * of the RDA one-kernel shapes; default 0).  Affects later calls.  Unknown name or bad value:
- * INVALID_ARG.  ddl_get_option writes the current value.
+ * Launch-shape knobs, for measurement; process-wide, read by every later call.  Names:
+ *   "tiles_per_block"       consecutive 1024-element tiles one workgroup walks, 1..1024; -1
+ *                           (default): one, two for 4-bit codes of more than eight learners
+ *   "max_blocks_per_cu"     0: no cap; k in 3..64: at most k workgroups resident per compute
+ *                           unit; -1 (default): chosen by learner type and count, 3 to 6
+ *   "tile_rotate"           0: workgroup b takes run-of-tiles b; k in 2..4096: the index is
+ *                           rotated within groups of k by the group's number, which spreads
+ *                           every XCD's accesses over all memory channels (64)
+ *   "max_tiles_per_launch"  a sync of more tiles than this goes out as several equal kernel
+ *                           launches back to back, which keeps the eight XCDs aligned; 0: never
+ *                           split; -1 (default): from "part_megabytes" and the bytes per tile
+ *   "part_megabytes"        algorithmic traffic one such launch should carry, in 10^6 bytes,
+ *                           1..1000000 (2500)
+ *   "rda_blocks_per_cu"     residency cap of the RDA one-kernel shapes (0: none)
+ *   "grids_enqueued"        read-only statistic: kernel launches this process has enqueued
+ * Unknown name or bad value: INVALID_ARG.  ddl_get_option writes the current value.
  */
 DDL_API ddl_status ddl_set_option(const char* name, long value);
 DDL_API ddl_status ddl_get_option(const char* name, long* value_out);

@@ -14,7 +14,8 @@ from typing import List, Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libddlsync.so")
+# DDLSYNC_LIBRARY names another build of the same library (the diagnostic one, say).
+LIB_PATH = os.environ.get("DDLSYNC_LIBRARY") or os.path.join(_HERE, "libddlsync.so")
 
 DDL_OK, DDL_ERR_INVALID_ARG, DDL_ERR_EMPTY_QUORUM, DDL_ERR_ALIAS, DDL_ERR_RUNTIME = range(5)
 DDL_F32, DDL_BF16 = 0, 1
@@ -45,6 +46,11 @@ class _Fragment(ctypes.Structure):
                 ("lr", ctypes.c_float), ("mu", ctypes.c_float)]
 
 
+class _Q4Segment(ctypes.Structure):
+    _fields_ = [("codes", ctypes.POINTER(ctypes.c_void_p)),
+                ("scales", ctypes.POINTER(ctypes.c_void_p))]
+
+
 class _Sync(ctypes.Structure):
     _fields_ = [("fragment", ctypes.c_int), ("token_counts", ctypes.POINTER(ctypes.c_uint64)),
                 ("quorum_mask", ctypes.POINTER(ctypes.c_uint8)), ("lr", ctypes.c_float),
@@ -61,6 +67,8 @@ def _load() -> ctypes.CDLL:
     f64p, vpp = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_void_p)
     lib.ddl_version.restype = ctypes.c_int
     lib.ddl_build_id.restype = ctypes.c_char_p
+    lib.ddl_kernel_build_id.argtypes = [ctypes.c_char_p]
+    lib.ddl_kernel_build_id.restype = ctypes.c_char_p
     lib.ddl_status_string.argtypes = [ctypes.c_int]
     lib.ddl_status_string.restype = ctypes.c_char_p
     lib.ddl_last_error_message.restype = ctypes.c_char_p
@@ -108,6 +116,10 @@ def _load() -> ctypes.CDLL:
     lib.ddl_q4_merge_fragment.argtypes = [ctypes.c_void_p, ctypes.c_void_p, vpp, vpp, u64p, u8p,
                                           ctypes.c_int, ctypes.c_size_t, ctypes.c_size_t,
                                           ctypes.c_float, ctypes.c_float, ctypes.c_void_p]
+    lib.ddl_plan_set_q4_sources.argtypes = [ctypes.c_void_p, ctypes.POINTER(_Q4Segment),
+                                            ctypes.c_size_t, ctypes.c_size_t]
+    lib.ddl_plan_q4_merge.argtypes = [ctypes.c_void_p, ctypes.POINTER(_Sync), ctypes.c_int,
+                                      ctypes.c_void_p]
     lib.ddl_balanced_fragments.argtypes = [u64p, ctypes.c_int, ctypes.c_int,
                                            ctypes.POINTER(ctypes.c_int)]
     lib.ddl_copy_probe.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
@@ -119,7 +131,8 @@ def _load() -> ctypes.CDLL:
                  "ddl_plan_merge", "ddl_plan_destroy", "ddl_set_option", "ddl_get_option",
                  "ddl_copy_probe", "ddl_balanced_fragments", "ddl_merge_fragment_bcast",
                  "ddl_rda_merge_fragment", "ddl_plan_set_rda_groups", "ddl_plan_rda_merge",
-                 "ddl_q4_encode", "ddl_q4_merge_fragment", "ddl_rda_merge_fragment_static"):
+                 "ddl_q4_encode", "ddl_q4_merge_fragment", "ddl_rda_merge_fragment_static",
+                 "ddl_plan_set_q4_sources", "ddl_plan_q4_merge"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -197,6 +210,11 @@ def version() -> int:
 def build_id() -> str:
     """ddl_build_id: hash of the sources the loaded library was built from."""
     return _lib.ddl_build_id().decode()
+
+
+def kernel_build_id(kernel: str) -> str:
+    """ddl_kernel_build_id: hash of the sources of one kernel family ("merge", "rda", "q4")."""
+    return _lib.ddl_kernel_build_id(kernel.encode()).decode()
 
 
 def compute_weights(token_counts, quorum_mask) -> List[float]:
@@ -504,6 +522,43 @@ class Plan:
             ptr, nbytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
         _check(_lib.ddl_plan_rda_merge(self._h, arr, count, ptr, nbytes, _stream_handle(stream)),
                "ddl_plan_rda_merge")
+
+    def set_q4_sources(self, sources, block_len: int) -> None:
+        """ddl_plan_set_q4_sources: ``sources[s] = (codes, scales)`` for every segment of the
+        plan in creation order, each a list of M device tensors (uint8 codes, float32 scales)
+        or None for a learner that never contributes to that tensor."""
+        n = len(sources)
+        arr = (_Q4Segment * max(1, n))()
+        keep = []
+        for i, (codes, scales) in enumerate(sources):
+            M = len(codes)
+            if len(scales) != M:
+                raise ValueError("one scales entry per codes entry")
+            ctab, stab = (ctypes.c_void_p * M)(), (ctypes.c_void_p * M)()
+            for m in range(M):
+                c, sc = codes[m], scales[m]
+                if c is not None:
+                    if c.dtype != torch.uint8 or not c.is_cuda or not c.is_contiguous():
+                        raise TypeError("codes must be contiguous device uint8 tensors")
+                    ctab[m] = c.data_ptr()
+                if sc is not None:
+                    if sc.dtype != torch.float32 or not sc.is_cuda or not sc.is_contiguous():
+                        raise TypeError("scales must be contiguous device float32 tensors")
+                    stab[m] = sc.data_ptr()
+            arr[i].codes = ctypes.cast(ctab, ctypes.POINTER(ctypes.c_void_p))
+            arr[i].scales = ctypes.cast(stab, ctypes.POINTER(ctypes.c_void_p))
+            keep += [ctab, stab, codes, scales]
+        _check(_lib.ddl_plan_set_q4_sources(self._h, arr, n, block_len),
+               "ddl_plan_set_q4_sources")
+        self._q4_keep = keep                # keeps the source tensors alive
+
+    def q4_merge(self, syncs, stream=None) -> None:
+        """ddl_plan_q4_merge: ``merge`` from the learners' 4-bit outer gradients."""
+        if not (isinstance(syncs, tuple) and len(syncs) == 3 and isinstance(syncs[1], int)):
+            syncs = self.prepare(syncs)
+        arr, count, _keep = syncs
+        _check(_lib.ddl_plan_q4_merge(self._h, arr, count, _stream_handle(stream)),
+               "ddl_plan_q4_merge")
 
     def destroy(self) -> None:
         if self._h:

@@ -16,6 +16,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libddlsync.so")
+# The same library compiled with -DDDL_TRACE: every merge workgroup also records when it
+# started, on which XCD and with which tile (a diagnostic; see trace_tiles.py).
+TRACE_LIB_PATH = os.path.join(HERE, "libddlsync_trace.so")
 SOURCES = ["ddl_kernels.hip", "ddl_host.hip", "ddl_partition.hip", "ddl_rda.hip", "ddl_q4.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -26,24 +29,40 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextr
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-def source_id() -> str:
-    """Twelve hex digits identifying the kernel and host sources the library is built from
-    (every file under csrc/ plus the public header): what ``ddl_build_id()`` returns, and
-    what a profile summary records so that a stale counter figure can be told from a current
-    one."""
+# Which sources decide the code of which kernel family (for ddl_kernel_build_id).
+_COMMON = ["ddl_kernel_util.h", "ddl_device.h", "ddl_host.hip", "ddl_host_internal.h"]
+KERNEL_SOURCES = {
+    "merge": ["ddl_kernels.hip"] + _COMMON,
+    "rda": ["ddl_rda.hip", "ddl_kernels.hip"] + _COMMON,
+    "q4": ["ddl_q4.hip"] + _COMMON,
+}
+
+
+def _hash_files(names) -> str:
     h = hashlib.sha256()
-    files = sorted(os.listdir(CSRC))
-    for name in files:
-        if name.endswith((".hip", ".h")):
-            with open(os.path.join(CSRC, name), "rb") as fh:
-                h.update(name.encode() + b"\0" + fh.read())
+    for name in sorted(names):
+        with open(os.path.join(CSRC, name), "rb") as fh:
+            h.update(name.encode() + b"\0" + fh.read())
+    return h.hexdigest()[:12]
+
+
+def source_id(kernel: str = "") -> str:
+    """Twelve hex digits identifying the sources the library is built from: every file under
+    csrc/ plus the public header (what ``ddl_build_id()`` returns), or, for a kernel family
+    ("merge", "rda", "q4"), only the files that decide that family's code (what
+    ``ddl_kernel_build_id()`` returns, and what a profile summary records next to a counter
+    figure, so that a figure taken on other kernels is not mistaken for a current one)."""
+    if kernel:
+        return _hash_files(KERNEL_SOURCES[kernel])
+    h = hashlib.sha256()
+    h.update(_hash_files(n for n in os.listdir(CSRC) if n.endswith((".hip", ".h"))).encode())
     with open(os.path.join(HERE, "..", "include", "ddlsync.h"), "rb") as fh:
         h.update(b"ddlsync.h\0" + fh.read())
     return h.hexdigest()[:12]
 
 
-def _compile(src: str, extra) -> str:
-    obj = os.path.join(BUILD_DIR, os.path.splitext(src)[0] + ".o")
+def _compile(src: str, extra, build_dir: str = BUILD_DIR) -> str:
+    obj = os.path.join(build_dir, os.path.splitext(src)[0] + ".o")
     cmd = [HIPCC, *FLAGS, "-Rpass-analysis=kernel-resource-usage", *extra, "-c",
            os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
@@ -59,19 +78,29 @@ def _compile(src: str, extra) -> str:
     return obj
 
 
-def build(extra_flags=(), out: str = LIB_PATH, verbose: bool = False) -> str:
-    """Compile every HIP source and link the shared library.  Always recompiles."""
+def build(extra_flags=(), out: str = LIB_PATH, verbose: bool = False, trace: bool = True) -> str:
+    """Compile every HIP source and link the shared library; with ``trace`` also the
+    diagnostic variant.  Always recompiles."""
+    ids = [f'-DDDL_BUILD_ID="{source_id()}"'] + [
+        f'-DDDL_BUILD_ID_{k.upper()}="{source_id(k)}"' for k in KERNEL_SOURCES]
+    jobs = [(s, list(extra_flags) + ids, BUILD_DIR) for s in SOURCES]
+    if trace:
+        tdir = os.path.join(BUILD_DIR, "trace")
+        jobs += [(s, list(extra_flags) + ids + ["-DDDL_TRACE"], tdir) for s in SOURCES]
+        os.makedirs(tdir, exist_ok=True)
     os.makedirs(BUILD_DIR, exist_ok=True)
-    extra = list(extra_flags) + [f'-DDDL_BUILD_ID="{source_id()}"']
-    with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
-        objs = list(ex.map(lambda s: _compile(s, extra), SOURCES))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", out]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        sys.stderr.write(r.stdout + r.stderr)
-        raise RuntimeError("link failed")
-    if verbose:
-        print("built", out)
+    with ThreadPoolExecutor(max_workers=min(len(jobs), os.cpu_count() or 4)) as ex:
+        objs = list(ex.map(lambda j: _compile(*j), jobs))
+    for group, target in ((objs[:len(SOURCES)], out), (objs[len(SOURCES):], TRACE_LIB_PATH)):
+        if not group:
+            continue
+        cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *group, "-o", target]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            sys.stderr.write(r.stdout + r.stderr)
+            raise RuntimeError("link failed")
+        if verbose:
+            print("built", target)
     return out
 
 

@@ -31,6 +31,14 @@ struct DdlSegDesc {
 };
 static_assert(sizeof(DdlSegDesc) == 168, "descriptor layout");
 
+// The 4-bit sources of one tensor (codes and per-block scales of every learner), parallel to
+// its DdlSegDesc: entry i of the plan's DdlQ4Desc table belongs to descriptor i.
+struct DdlQ4Desc {
+    const uint8_t* codes[DDL_MAXL];  // two signed 4-bit codes per byte, element 2k in the low nibble
+    const float* scales[DDL_MAXL];   // one fp32 scale per block of block_len elements
+};
+static_assert(sizeof(DdlQ4Desc) == 256, "q4 descriptor layout");
+
 struct DdlItem {
     uint32_t seg_begin;     // first descriptor of the fragment in the table
     uint32_t num_segs;      // its number of (non-empty) segments
@@ -58,13 +66,21 @@ struct DdlLaunchArgs {
 #ifdef DDL_TRACE
     uint64_t* trace;  // diagnostic build only: per workgroup {start clock, XCD, tile}
 #endif
+    // 4-bit sources only: the table parallel to segs (unused by the flat variant), and the
+    // block length of the scales (block_shift = log2 of it, or 0xffffffff if no power of two).
+    const DdlQ4Desc* q4;
+    uint32_t block_len;
+    uint32_t block_shift;
     DdlItem item[DDL_MAX_ITEMS];
     DdlSegDesc flat;         // the one segment of the flat variant
+    DdlQ4Desc flat_q4;       // ... and its 4-bit sources
 };
 static_assert(sizeof(DdlLaunchArgs) <= 4096, "kernel argument block limit");
 
 // Launches the merge kernel specialised for (learner dtype, contributing learners, flat or
-// table).  dtype: 0 fp32, 1 bf16 (values of ddl_dtype).  Returns a hipError_t as int.
+// table).  dtype: 0 fp32, 1 bf16 (values of ddl_dtype), 2: the learners' outer gradients as
+// 4-bit codes with block scales.  Returns a hipError_t as int.
+#define DDL_SRC_Q4 2
 // lds_bytes of (unused) dynamic LDS per workgroup cap how many workgroups a compute unit holds.
 int ddl_launch_merge(int dtype, int Mq, bool flat, uint32_t grid, uint32_t lds_bytes, void* stream,
                      const DdlLaunchArgs& args);
@@ -80,3 +96,8 @@ int ddl_launch_copy(void* dst, const void* src, uint64_t n16, uint32_t grid, voi
 // Launch-shape knob of the one-kernel RDA shape (set through ddl_set_option): at most this
 // many workgroups resident per compute unit (0: no cap), enforced with unused dynamic LDS.
 extern std::atomic<long> ddl_opt_rda_blocks_per_cu;
+
+// Statistic read through ddl_get_option("grids_enqueued"): kernel grids this process has
+// enqueued so far (one sync of a fragment may be several).  Every launch site counts itself.
+extern std::atomic<long> ddl_stat_grids;
+#define DDL_COUNT_GRID() ((void)ddl_stat_grids.fetch_add(1, std::memory_order_relaxed))

@@ -21,6 +21,7 @@ using namespace ddlh;
 static_assert(DDL_MAXL == DDL_MAX_LEARNERS, "device and public learner limits differ");
 
 std::atomic<long> ddl_opt_rda_blocks_per_cu{0};
+std::atomic<long> ddl_stat_grids{0};
 
 namespace {
 
@@ -50,7 +51,8 @@ namespace {
 // The launch-shape options are process-wide atomics: a launch reads each one once, so a call
 // racing with ddl_set_option sees either the old or the new value, never a torn one.  No
 // lock is taken on any launch path; the only lock guards the staging cache of ddl_merge_batch.
-std::atomic<long> g_tiles_per_block{1};     // consecutive tiles a workgroup walks
+std::atomic<long> g_tiles_per_block{-1};    // consecutive tiles a workgroup walks; -1: chosen
+                                            // by the kind of learner data
 std::atomic<long> g_tile_rotate{64};        // group size of the tile rotation (0: off)
 std::atomic<long> g_max_blocks_per_cu{-1};  // -1: by learner type and count; 0: no cap; k: at
                                             // most k resident workgroups per compute unit
@@ -97,6 +99,17 @@ ddl_status device_state(DeviceState** out)
     return DDL_OK;
 }
 
+// Tiles per workgroup when left to the library: one, except for 4-bit codes of more than eight
+// learners -- their streams are so thin (512 B per learner and tile) that two tiles per
+// workgroup pay (moe, 11 learners: 5985 -> 6244 GB/s; with fewer learners, and for bf16 / fp32
+// learners of any count, two tiles per workgroup cost 3-8 %).
+uint32_t tiles_per_block(int elem_bytes, int Mq)
+{
+    const long opt = g_tiles_per_block.load(std::memory_order_relaxed);
+    if (opt >= 1) return (uint32_t)opt;
+    return elem_bytes == 0 && Mq > 8 ? 2u : 1u;
+}
+
 // A long launch goes out as several grids, back to back on the stream.  The eight XCDs each
 // work through their own share of a grid's workgroups at their own pace, and nothing
 // re-aligns them before the grid ends: over some hundred thousand workgroups their positions
@@ -104,7 +117,7 @@ ddl_status device_state(DeviceState** out)
 // 3-6 %.  A grid boundary re-aligns them at the price of one drain (about 3 us).  Measured on
 // MI355X, grids of 0.3-0.5 ms (2-3 GB of traffic) are the best trade for every learner count.
 // elem_bytes: bytes per learner element (0: 4-bit codes); extra: other bytes per element.
-uint32_t max_tiles_per_launch(int elem_bytes, int Mq, int extra = 0)
+uint32_t part_tiles(int elem_bytes, int Mq, int extra)
 {
     const long opt = g_max_tiles_per_launch.load(std::memory_order_relaxed);
     if (opt >= 0) return (uint32_t)opt;
@@ -120,13 +133,15 @@ uint32_t max_tiles_per_launch(int elem_bytes, int Mq, int extra = 0)
 // The cap itself, when left to the library (measured on MI355X; what matters is roughly the
 // bytes one compute unit has in flight): few bf16 learners leave room for six workgroups, many
 // want four; fp32 learners, twice the bytes per tile, want four and from four learners on
-// three; 4-bit codes are so few bytes that six is best throughout.
+// three; 4-bit codes (half a byte per element) want eight, the most the kernel's registers
+// allow anyway (dense_block / large_dense / moe at 4, 5, 6, 8, none: 6020/6013/5504,
+// 6033/6011/5492, 6331/6261/5993, 6408/6538/5995, 6434/6544/5989 GB/s).
 // elem_bytes: 4 fp32 learners, 2 bf16, 0 the 4-bit codes.
 long auto_blocks_per_cu(int elem_bytes, int Mq)
 {
     if (elem_bytes == 4) return Mq >= 4 ? 3 : 4;
     if (elem_bytes == 2) return Mq <= 5 ? 6 : 4;
-    return 6;
+    return 8;
 }
 
 uint32_t lds_cap_bytes(int elem_bytes, int Mq)
@@ -141,6 +156,10 @@ uint32_t lds_cap_bytes(int elem_bytes, int Mq)
 }  // namespace
 
 uint32_t ddlh::merge_lds_cap_bytes(int elem_bytes, int Mq) { return lds_cap_bytes(elem_bytes, Mq); }
+uint32_t ddlh::max_tiles_per_launch(int elem_bytes, int Mq, int extra)
+{
+    return part_tiles(elem_bytes, Mq, extra);
+}
 uint32_t ddlh::tile_rotate() { return (uint32_t)g_tile_rotate.load(std::memory_order_relaxed); }
 
 // ------------------------------------------------------------------------------------------
@@ -226,12 +245,9 @@ namespace {
 // ------------------------------------------------------------------------------------------
 // overlap check: an output range (Theta, v) may overlap nothing; inputs may overlap inputs
 // ------------------------------------------------------------------------------------------
-struct Range {
-    uintptr_t lo, hi;
-    bool out;
-};
+}  // namespace
 
-bool ranges_alias(std::vector<Range>& r)
+bool ddlh::ranges_alias(std::vector<Range>& r)
 {
     std::sort(r.begin(), r.end(), [](const Range& a, const Range& b) { return a.lo < b.lo; });
     uintptr_t max_hi_any = 0, max_hi_out = 0;
@@ -243,13 +259,9 @@ bool ranges_alias(std::vector<Range>& r)
     return false;
 }
 
-inline size_t elem_size(ddl_dtype d) { return d == DDL_BF16 ? 2 : 4; }
-
-inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
-
 // Appends [p, p + elem * n); false if the end is not representable (the range would wrap
 // around the address space: no such array exists, and a wrapped end would hide an overlap).
-bool add_range(const void* p, size_t elem, size_t n, bool out, std::vector<Range>& r)
+bool ddlh::add_range(const void* p, size_t elem, size_t n, bool out, std::vector<Range>& r)
 {
     size_t bytes = 0;
     uintptr_t hi = 0;
@@ -259,6 +271,12 @@ bool add_range(const void* p, size_t elem, size_t n, bool out, std::vector<Range
     r.push_back({(uintptr_t)p, hi, out});
     return true;
 }
+
+namespace {
+
+inline size_t elem_size(ddl_dtype d) { return d == DDL_BF16 ? 2 : 4; }
+
+inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
 // Appends the ranges of one segment; false if a needed pointer is NULL or misaligned for its
 // element type, or a range wraps.  `learner_bits` selects which learners' ranges count.
@@ -279,8 +297,10 @@ bool add_segment_ranges(const float* theta, const float* v, const void* theta_bf
     return true;
 }
 
-void fill_desc(DdlSegDesc& d, float* theta, float* v, void* theta_bf16,
-               const void* const* learners, int M, size_t n, uint32_t tile_begin)
+}  // namespace
+
+void ddlh::fill_desc(DdlSegDesc& d, float* theta, float* v, void* theta_bf16,
+                     const void* const* learners, int M, size_t n, uint32_t tile_begin)
 {
     std::memset(&d, 0, sizeof d);
     d.theta = theta;
@@ -290,10 +310,12 @@ void fill_desc(DdlSegDesc& d, float* theta, float* v, void* theta_bf16,
     d.tile_begin = tile_begin;
     d.base_aligned = aligned(theta, 16) && aligned(v, 16) && aligned(theta_bf16, 8);
     for (int m = 0; m < M; ++m) {
-        d.learner[m] = learners[m];
-        if (aligned(learners[m], 16)) d.learner_aligned |= (uint16_t)(1u << m);
+        d.learner[m] = learners ? learners[m] : nullptr;
+        if (learners && aligned(learners[m], 16)) d.learner_aligned |= (uint16_t)(1u << m);
     }
 }
+
+namespace {
 
 void fill_item(DdlItem& it, const Quorum& q, float lr, float mu, uint32_t seg_begin,
                uint32_t num_segs, uint32_t tile_off, uint32_t coarse_begin = 0,
@@ -398,22 +420,28 @@ ddl_status build_table(const ddl_fragment* frags, int num_frags, const uint32_t*
     return DDL_OK;
 }
 
-// One sync of one fragment, ready to launch.
-struct Work {
-    uint32_t frag;  // index into Table::frags
-    Quorum q;
-    float lr, mu;
-};
+uint32_t log2_or_none(uint32_t x)  // log2 of a power of two, else 0xffffffff
+{
+    if (x == 0 || (x & (x - 1))) return 0xffffffffu;
+    uint32_t s = 0;
+    while ((1u << s) < x) ++s;
+    return s;
+}
+
+}  // namespace
 
 // Enqueue the fragments in `work`: one launch per group of up to DDL_MAX_ITEMS fragments with
 // the same learner dtype and number of contributing learners.
-ddl_status launch_work(const Table& T, const void* d_table, std::vector<Work>& work,
-                       void* stream)
+ddl_status ddlh::launch_work(const Table& T, const void* d_table, std::vector<Work>& work,
+                             void* stream, const Q4Source* q4)
 {
+    // source kind and bytes per learner element of a fragment in this call
+    auto kind = [&](const FragInfo& f) { return q4 ? DDL_SRC_Q4 : (int)f.dt; };
+    auto ebytes = [&](const FragInfo& f) { return q4 ? 0 : (int)elem_size(f.dt); };
     std::stable_sort(work.begin(), work.end(), [&](const Work& a, const Work& b) {
         const FragInfo& fa = T.frags[a.frag];
         const FragInfo& fb = T.frags[b.frag];
-        if (fa.dt != fb.dt) return fa.dt < fb.dt;
+        if (kind(fa) != kind(fb)) return kind(fa) < kind(fb);
         return a.q.Mq < b.q.Mq;
     });
     size_t i = 0;
@@ -424,14 +452,19 @@ ddl_status launch_work(const Table& T, const void* d_table, std::vector<Work>& w
         a.segs = static_cast<const DdlSegDesc*>(d_table);
         a.coarse = reinterpret_cast<const uint32_t*>(static_cast<const char*>(d_table) +
                                                      T.seg_bytes());
-        a.tiles_per_block = (uint32_t)g_tiles_per_block.load(std::memory_order_relaxed);
+        a.tiles_per_block = tiles_per_block(ebytes(f0), work[i].q.Mq);
         a.rotate = (int32_t)tile_rotate();
+        if (q4) {
+            a.q4 = q4->d_table;
+            a.block_len = q4->block_len;
+            a.block_shift = log2_or_none(q4->block_len);
+        }
         uint64_t tiles = 0;
         int items = 0;
         size_t j = i;
         for (; j < work.size() && items < DDL_MAX_ITEMS; ++j) {
             const FragInfo& f = T.frags[work[j].frag];
-            if (f.dt != f0.dt || work[j].q.Mq != work[i].q.Mq) break;
+            if (kind(f) != kind(f0) || work[j].q.Mq != work[i].q.Mq) break;
             if (f.tiles == 0) continue;
             if (tiles + f.tiles > 0x7fffffffull) break;
             fill_item(a.item[items], work[j].q, work[j].lr, work[j].mu, f.seg_begin, f.num_segs,
@@ -446,9 +479,8 @@ ddl_status launch_work(const Table& T, const void* d_table, std::vector<Work>& w
             a.trace = reinterpret_cast<uint64_t*>(g_trace_buffer.load());
 #endif
             const int e = ddl_launch_merge_parts(
-                (int)f0.dt, work[i].q.Mq, false,
-                max_tiles_per_launch((int)elem_size(f0.dt), work[i].q.Mq),
-                lds_cap_bytes((int)elem_size(f0.dt), work[i].q.Mq), stream, a);
+                kind(f0), work[i].q.Mq, false, max_tiles_per_launch(ebytes(f0), work[i].q.Mq),
+                lds_cap_bytes(ebytes(f0), work[i].q.Mq), stream, a);
             if (e != (int)hipSuccess) return runtime_error((hipError_t)e, "merge kernel launch");
         }
         if (j == i) return DDL_ERR_INVALID_ARG;  // cannot happen: a lone fragment always fits
@@ -456,6 +488,37 @@ ddl_status launch_work(const Table& T, const void* d_table, std::vector<Work>& w
     }
     return DDL_OK;
 }
+
+// ONE tensor whose descriptor travels in the kernel-argument block.
+ddl_status ddlh::launch_flat(const DdlSegDesc& desc, int src, const Quorum& q, float lr, float mu,
+                             void* stream, const DdlQ4Desc* q4d, uint32_t block_len)
+{
+    const uint64_t tiles = (desc.n + DDL_TILE - 1) / DDL_TILE;
+    if (tiles == 0) return DDL_OK;
+    if (tiles > 0x7fffffffull) return DDL_ERR_INVALID_ARG;
+    DdlLaunchArgs a;
+    std::memset(&a, 0, sizeof a);
+    const int ebytes = src == DDL_SRC_Q4 ? 0 : src == (int)DDL_BF16 ? 2 : 4;
+    a.tiles_per_block = tiles_per_block(ebytes, q.Mq);
+    a.rotate = (int32_t)tile_rotate();
+    a.total_tiles = (uint32_t)tiles;
+    a.num_items = 1;
+    a.flat = desc;
+    a.flat.tile_begin = 0;
+    if (src == DDL_SRC_Q4) {
+        if (!q4d) return DDL_ERR_INVALID_ARG;
+        a.flat_q4 = *q4d;
+        a.block_len = block_len;
+        a.block_shift = log2_or_none(block_len);
+    }
+    fill_item(a.item[0], q, lr, mu, 0, 1, 0);
+    const int e = ddl_launch_merge_parts(src, q.Mq, true, max_tiles_per_launch(ebytes, q.Mq),
+                                         lds_cap_bytes(ebytes, q.Mq), stream, a);
+    if (e != (int)hipSuccess) return runtime_error((hipError_t)e, "merge kernel launch");
+    return DDL_OK;
+}
+
+namespace {
 
 ddl_status merge_flat(float* theta, float* v, void* theta_bf16, const void* const* learner_params,
                       ddl_dtype dt, const double* w, int M, size_t n, float lr, float mu,
@@ -474,21 +537,9 @@ ddl_status merge_flat(float* theta, float* v, void* theta_bf16, const void* cons
         return DDL_ERR_INVALID_ARG;
     if (ranges_alias(ranges)) return DDL_ERR_ALIAS;
 
-    const uint64_t tiles = (n + DDL_TILE - 1) / DDL_TILE;
-    if (tiles > 0x7fffffffull) return DDL_ERR_INVALID_ARG;
-    DdlLaunchArgs a;
-    std::memset(&a, 0, sizeof a);
-    a.tiles_per_block = (uint32_t)g_tiles_per_block.load(std::memory_order_relaxed);
-    a.rotate = (int32_t)tile_rotate();
-    a.total_tiles = (uint32_t)tiles;
-    a.num_items = 1;
-    fill_desc(a.flat, theta, v, theta_bf16, lp, M, n, 0);
-    fill_item(a.item[0], q, lr, mu, 0, 1, 0);
-    const int e = ddl_launch_merge_parts((int)dt, q.Mq, true,
-                                         max_tiles_per_launch((int)elem_size(dt), q.Mq),
-                                         lds_cap_bytes((int)elem_size(dt), q.Mq), stream, a);
-    if (e != (int)hipSuccess) return runtime_error((hipError_t)e, "merge kernel launch");
-    return DDL_OK;
+    DdlSegDesc d;
+    fill_desc(d, theta, v, theta_bf16, lp, M, n, 0);
+    return launch_flat(d, (int)dt, q, lr, mu, stream);
 }
 
 }  // namespace
@@ -499,23 +550,7 @@ ddl_status merge_flat(float* theta, float* v, void* theta_bf16, const void* cons
 ddl_status ddlh::launch_one_direct(const DdlSegDesc& desc, ddl_dtype dt, const Quorum& q, float lr,
                                    float mu, void* stream)
 {
-    const uint64_t tiles = (desc.n + DDL_TILE - 1) / DDL_TILE;
-    if (tiles == 0) return DDL_OK;
-    if (tiles > 0x7fffffffull) return DDL_ERR_INVALID_ARG;
-    DdlLaunchArgs a;
-    std::memset(&a, 0, sizeof a);
-    a.tiles_per_block = (uint32_t)g_tiles_per_block.load(std::memory_order_relaxed);
-    a.rotate = (int32_t)tile_rotate();
-    a.total_tiles = (uint32_t)tiles;
-    a.num_items = 1;
-    a.flat = desc;
-    a.flat.tile_begin = 0;
-    fill_item(a.item[0], q, lr, mu, 0, 1, 0);
-    const int e = ddl_launch_merge_parts((int)dt, q.Mq, true,
-                                         max_tiles_per_launch((int)elem_size(dt), q.Mq),
-                                         lds_cap_bytes((int)elem_size(dt), q.Mq), stream, a);
-    if (e != (int)hipSuccess) return runtime_error((hipError_t)e, "merge kernel launch");
-    return DDL_OK;
+    return launch_flat(desc, (int)dt, q, lr, mu, stream);
 }
 
 extern "C" {
@@ -526,6 +561,19 @@ int ddl_version(void) { return 200; }
 #define DDL_BUILD_ID "unknown"
 #endif
 const char* ddl_build_id(void) { return DDL_BUILD_ID; }
+
+#ifndef DDL_BUILD_ID_MERGE
+#define DDL_BUILD_ID_MERGE "unknown"
+#define DDL_BUILD_ID_RDA "unknown"
+#define DDL_BUILD_ID_Q4 "unknown"
+#endif
+const char* ddl_kernel_build_id(const char* kernel)
+{
+    if (kernel && !std::strcmp(kernel, "merge")) return DDL_BUILD_ID_MERGE;
+    if (kernel && !std::strcmp(kernel, "rda")) return DDL_BUILD_ID_RDA;
+    if (kernel && !std::strcmp(kernel, "q4")) return DDL_BUILD_ID_Q4;
+    return "";
+}
 
 const char* ddl_status_string(ddl_status s)
 {
@@ -765,6 +813,7 @@ ddl_status ddl_plan_destroy(ddl_plan* plan)
     if (!plan) return DDL_OK;
     ddl_status st = DDL_OK;
     if (plan->rda) ddl_rda_plan_free(plan->rda);
+    if (plan->d_q4) (void)hipFree(plan->d_q4);
     if (plan->d_table) {
         const hipError_t e = hipFree(plan->d_table);
         if (e != hipSuccess) st = runtime_error(e, "hipFree");
@@ -800,7 +849,7 @@ ddl_status ddl_set_option(const char* name, long value)
 {
     if (!name) return DDL_ERR_INVALID_ARG;
     if (!std::strcmp(name, "tiles_per_block")) {
-        if (value < 1 || value > 1024) return DDL_ERR_INVALID_ARG;
+        if (value != -1 && (value < 1 || value > 1024)) return DDL_ERR_INVALID_ARG;
         g_tiles_per_block = value;
         return DDL_OK;
     }
@@ -859,6 +908,10 @@ ddl_status ddl_get_option(const char* name, long* value_out)
     }
     if (!std::strcmp(name, "part_megabytes")) {
         *value_out = g_part_megabytes;
+        return DDL_OK;
+    }
+    if (!std::strcmp(name, "grids_enqueued")) {
+        *value_out = ddl_stat_grids;
         return DDL_OK;
     }
     if (!std::strcmp(name, "rda_blocks_per_cu")) {

@@ -58,9 +58,45 @@ bool finite_nonneg(float x);
 uint32_t merge_lds_cap_bytes(int elem_bytes, int Mq);
 // Group size of the tile rotation (option tile_rotate; 0: off).
 uint32_t tile_rotate();
+// Most 1024-element tiles one kernel launch should cover (0: no limit): options
+// max_tiles_per_launch / part_megabytes.  elem_bytes: bytes per learner element (0: 4-bit
+// codes); extra: bytes per element beyond the learners' and the 16 of Theta and v.
+uint32_t max_tiles_per_launch(int elem_bytes, int Mq, int extra = 0);
+// One sync of one fragment of a table, ready to launch.
+struct Work {
+    uint32_t frag;  // index into Table::frags
+    Quorum q;
+    float lr, mu;
+};
+// The learners' outer gradients as 4-bit codes: the device table parallel to the descriptors
+// (null for the flat variant) and the block length of the scales.
+struct Q4Source {
+    const DdlQ4Desc* d_table;
+    uint32_t block_len;
+};
+// Enqueues the fragments in `work` (merge + outer step): one launch per group of up to
+// DDL_MAX_ITEMS fragments with the same learner type and number of contributing learners, each
+// cut into parts if long.  q4: the fragments' learners come as 4-bit codes (else their
+// bf16 / fp32 copies in the descriptors).
+ddl_status launch_work(const Table& T, const void* d_table, std::vector<Work>& work, void* stream,
+                       const Q4Source* q4 = nullptr);
+// The same for ONE tensor whose descriptor travels in the kernel-argument block (src: 0 fp32,
+// 1 bf16 learners in desc.learner; DDL_SRC_Q4: codes and scales in *q4d, blocks of block_len).
+ddl_status launch_flat(const DdlSegDesc& desc, int src, const Quorum& q, float lr, float mu,
+                       void* stream, const DdlQ4Desc* q4d = nullptr, uint32_t block_len = 0);
 // Enqueues the direct-averaging merge + outer step of one tensor given by its descriptor.
 ddl_status launch_one_direct(const DdlSegDesc& desc, ddl_dtype dt, const Quorum& q, float lr,
                              float mu, void* stream);
+// Address ranges of a call and the overlap rule: an output range (Theta, v, a bf16 copy) may
+// overlap nothing, inputs may overlap inputs.  add_range: false if the range would wrap.
+struct Range {
+    uintptr_t lo, hi;
+    bool out;
+};
+bool add_range(const void* p, size_t elem, size_t n, bool out, std::vector<Range>& r);
+bool ranges_alias(std::vector<Range>& r);
+void fill_desc(DdlSegDesc& d, float* theta, float* v, void* theta_bf16,
+               const void* const* learners, int M, size_t n, uint32_t tile_begin);
 // Records the message for ddl_last_error_message and returns DDL_ERR_RUNTIME.
 ddl_status runtime_error(hipError_t e, const char* what);
 // Records a message for ddl_last_error_message (for an error that is not a HIP failure).
@@ -77,4 +113,9 @@ struct ddl_plan {
     ddlh::Table table;
     void* d_table = nullptr;  // descriptors followed by the coarse index
     DdlRdaPlan* rda = nullptr;
+    // 4-bit sources (ddl_plan_set_q4_sources): DdlQ4Desc per descriptor, on the device
+    void* d_q4 = nullptr;
+    uint32_t q4_block_len = 0;
+    std::vector<uint32_t> q4_nonnull_bits;  // per fragment: learners with codes and scales in
+                                            // every tensor
 };

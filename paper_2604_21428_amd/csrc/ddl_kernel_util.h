@@ -6,8 +6,12 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+// Load form of the streaming merge kernels (see ld<> below): 2 = raw buffer load with "nt".
+// The buffer form of the same non-temporal load measured faster than the global form on
+// MI355X: moe (11 learner streams) +1.7 %, large_dense +0.7 %, a 243 M-parameter block +0.4 %,
+// dense_block equal; adding "sc1" or "sc0 sc1" to the loads changes nothing.
 #ifndef DDL_NT_LOAD
-#define DDL_NT_LOAD 1
+#define DDL_NT_LOAD 2
 #endif
 #ifndef DDL_NT_STATE_LOAD
 #define DDL_NT_STATE_LOAD DDL_NT_LOAD
@@ -24,12 +28,30 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #define DDL_GLOBAL __attribute__((address_space(1)))
 #define DDL_CONST __attribute__((address_space(4)))
 
-template <typename T, bool NT>
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t raw_buffer(uint64_t base)
+{
+    // stride 0, no range limit below 4 GiB past the base, 32-bit raw data format
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(base), 0, -1, 0x00020000);
+}
+
+// POLICY 0: ordinary cached load; 1: non-temporal global load; any other value: raw buffer
+// load with that value as its cache-policy bits (bit 0 sc0, bit 1 nt, bit 4 sc1).
+template <typename T, int POLICY>
 __device__ __forceinline__ T ld(uint64_t base, uint32_t index)
 {
-    const DDL_GLOBAL T* p = reinterpret_cast<const DDL_GLOBAL T*>(base) + index;
-    if (NT) return __builtin_nontemporal_load(p);
-    return *p;
+    if constexpr (POLICY == 0 || POLICY == 1) {
+        const DDL_GLOBAL T* p = reinterpret_cast<const DDL_GLOBAL T*>(base) + index;
+        if (POLICY == 1) return __builtin_nontemporal_load(p);
+        return *p;
+    } else {
+        const uint32_t off = index * (uint32_t)sizeof(T);
+        if constexpr (sizeof(T) == 16)
+            return __builtin_bit_cast(T, __builtin_amdgcn_raw_buffer_load_b128(raw_buffer(base), off, 0, POLICY));
+        else if constexpr (sizeof(T) == 8)
+            return __builtin_bit_cast(T, __builtin_amdgcn_raw_buffer_load_b64(raw_buffer(base), off, 0, POLICY));
+        else
+            return __builtin_bit_cast(T, __builtin_amdgcn_raw_buffer_load_b16(raw_buffer(base), off, 0, POLICY));
+    }
 }
 
 // Streaming stores carry explicit cache-policy bits: "nt" (streamed through L2, first to be
@@ -43,12 +65,6 @@ __device__ __forceinline__ T ld(uint64_t base, uint32_t index)
 #ifndef DDL_STORE_AUX
 #define DDL_STORE_AUX 0x12  // bit 1: nt, bit 4: sc1 (bit 0 would be sc0)
 #endif
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t raw_buffer(uint64_t base)
-{
-    // stride 0, no range limit below 4 GiB past the base, 32-bit raw data format
-    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(base), 0, -1, 0x00020000);
-}
-
 template <typename T>
 __device__ __forceinline__ void st(uint64_t base, uint32_t index, T x)
 {
@@ -127,6 +143,25 @@ struct LearnerBF16 {
     }
 };
 
+// 4-bit outer gradients: `raw` holds the four codes of a lane's group of four elements, and
+// what is widened is the code itself (-8 .. 7); the block's scale is folded into the weight.
+struct LearnerQ4 {
+    typedef uint8_t elem;  // two elements per byte
+    typedef uint16_t raw;
+    // signed value of nibble k (0 .. 3) of a group of codes
+    static __device__ __forceinline__ float nibble(uint32_t c, int k)
+    {
+        return (float)((int32_t)(c << (28 - 4 * k)) >> 28);
+    }
+    static __device__ __forceinline__ void widen(const raw& r, float (&x)[4])
+    {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) x[k] = nibble(r, k);
+    }
+};
+template <typename L> struct IsQ4 { static constexpr bool value = false; };
+template <> struct IsQ4<LearnerQ4> { static constexpr bool value = true; };
+
 // fp32 -> bf16, round to nearest, ties to even; NaN stays a (quiet) NaN.
 __device__ __forceinline__ uint32_t bf16_rne(float x)
 {
@@ -137,14 +172,15 @@ __device__ __forceinline__ uint32_t bf16_rne(float x)
 
 // One element: Delta = sum_j w_j (Theta - x_j); v' = mu v + Delta;
 // Theta' = Theta - lr (Delta + mu v').  The difference form keeps the fp32 rounding of the
-// weights (their sum is 1 only to ~1e-7) away from |Theta|.
-template <int MQ>
+// weights (their sum is 1 only to ~1e-7) away from |Theta|.  GRAD: the x_j are the learners'
+// outer gradients themselves (already Theta - theta_j), so Delta = sum_j w_j x_j.
+template <int MQ, bool GRAD = false>
 __device__ __forceinline__ void outer_step(float& theta, float& v, const float (&x)[MQ],
                                            const float (&w)[MQ], float lr, float mu)
 {
     float delta = 0.0f;
 #pragma unroll
-    for (int j = 0; j < MQ; ++j) delta = fmaf(w[j], theta - x[j], delta);
+    for (int j = 0; j < MQ; ++j) delta = fmaf(w[j], GRAD ? x[j] : theta - x[j], delta);
     const float v_new = fmaf(mu, v, delta);
     theta = fmaf(-lr, fmaf(mu, v_new, delta), theta);
     v = v_new;

@@ -13,8 +13,11 @@
 // Merge (the syncer side): Delta_i = sum_j w_j s_j q_ji, then the same fused outer Nesterov
 // step as the bf16 path.  Per element it reads Mq / 2 bytes of codes instead of 2 Mq bytes of
 // bf16 parameters, so the pass approaches the 16 B/param of the read-modify-write of Theta
-// and v.  Same tile shape and cache hints as the bf16 merge kernel: 1024 elements per
-// workgroup, one group of four per lane, every tensor access non-temporal.
+// and v.  The merge is the ordinary merge kernel (ddl_kernels.hip) instantiated for a third
+// kind of learner data, so it has the same tile shape, cache hints, tile rotation, split
+// launches, descriptor table and optional bf16 copy of the new Theta; this file holds the
+// encoder kernel and the host side: one flat fragment per call, or whole fragments of many
+// tensors through a plan.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -26,19 +29,6 @@
 #include "ddl_host_internal.h"
 #include "ddl_kernel_util.h"
 
-struct DdlQ4Args {
-    uint64_t theta, v;          // device addresses, 16-byte aligned
-    uint64_t codes[DDL_MAXL];   // contributing learners only, compacted
-    uint64_t scales[DDL_MAXL];
-    float w[DDL_MAXL];
-    uint64_t n;
-    uint32_t block_len;         // multiple of 8
-    uint32_t block_shift;       // log2(block_len) if it is a power of two, else 0xffffffff
-    float lr, mu;
-    uint32_t rotate;            // group size of the tile rotation, 0: off
-    uint32_t pad;
-};
-
 struct DdlQ4EncodeArgs {
     uint64_t theta, learner, codes, scales;
     uint64_t n;
@@ -49,74 +39,6 @@ struct DdlQ4EncodeArgs {
 };
 
 namespace {
-
-// Signed value of nibble k (0..3) of a 16-bit group of four codes.
-__device__ __forceinline__ float nibble(uint32_t c, int k)
-{
-    return (float)((int32_t)(c << (28 - 4 * k)) >> 28);
-}
-
-template <int MQ>
-__global__ void __launch_bounds__(DDL_BLOCK) q4_merge_kernel(const DdlQ4Args a)
-{
-    const uint64_t e0 =                                        // first element of the tile
-        (uint64_t)rotate_tile(blockIdx.x, gridDim.x, a.rotate) * DDL_TILE;
-    const uint64_t left = a.n - e0;                            // > 0 by the grid size
-    const uint32_t cnt = left < DDL_TILE ? (uint32_t)left : DDL_TILE;
-    const uint32_t i0 = threadIdx.x * 4;                       // this lane's elements in the tile
-    if (i0 >= cnt) return;
-    const uint64_t th = a.theta + e0 * 4, vv = a.v + e0 * 4;
-
-    // block of the lane's first element; a group of four never straddles a block
-    const uint64_t blk0 = e0 / a.block_len;
-    const uint32_t off = (uint32_t)(e0 - blk0 * a.block_len) + i0;
-    const uint64_t blk =
-        blk0 + (a.block_shift != 0xffffffffu ? off >> a.block_shift : off / a.block_len);
-
-    float sw[MQ];  // w_j * s_j for this lane's block
-#pragma unroll
-    for (int j = 0; j < MQ; ++j)
-        sw[j] = a.w[j] * *(reinterpret_cast<const DDL_GLOBAL float*>(a.scales[j]) + blk);
-    const float lr = a.lr, mu = a.mu;
-
-    if (i0 + 4 <= cnt) {
-        uint32_t c[MQ];
-#pragma unroll
-        for (int j = 0; j < MQ; ++j) c[j] = ld<uint16_t, true>(a.codes[j] + e0 / 2, threadIdx.x);
-        const f32x4 T = ld<f32x4, true>(th, threadIdx.x);
-        const f32x4 V = ld<f32x4, true>(vv, threadIdx.x);
-        float t4[4] = {T.x, T.y, T.z, T.w};
-        float v4[4] = {V.x, V.y, V.z, V.w};
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            float delta = 0.0f;
-#pragma unroll
-            for (int j = 0; j < MQ; ++j) delta = fmaf(sw[j], nibble(c[j], k), delta);
-            v4[k] = fmaf(mu, v4[k], delta);
-            t4[k] = fmaf(-lr, fmaf(mu, v4[k], delta), t4[k]);
-        }
-        const f32x4 tn = {t4[0], t4[1], t4[2], t4[3]};
-        const f32x4 vn = {v4[0], v4[1], v4[2], v4[3]};
-        st<f32x4>(th, threadIdx.x, tn);
-        st<f32x4>(vv, threadIdx.x, vn);
-    } else {  // the last one to three elements of the tensor
-        for (uint32_t e = i0; e < cnt; ++e) {
-            const uint64_t i = e0 + e;
-            float delta = 0.0f;
-#pragma unroll
-            for (int j = 0; j < MQ; ++j) {
-                const uint32_t byte =
-                    *(reinterpret_cast<const DDL_GLOBAL uint8_t*>(a.codes[j]) + i / 2);
-                delta = fmaf(sw[j], nibble(byte, (int)(i & 1)), delta);
-            }
-            const float t = *(reinterpret_cast<const DDL_GLOBAL float*>(th) + e);
-            const float v = *(reinterpret_cast<const DDL_GLOBAL float*>(vv) + e);
-            const float v_new = fmaf(mu, v, delta);
-            *(reinterpret_cast<DDL_GLOBAL float*>(th) + e) = fmaf(-lr, fmaf(mu, v_new, delta), t);
-            *(reinterpret_cast<DDL_GLOBAL float*>(vv) + e) = v_new;
-        }
-    }
-}
 
 // Encoder: a group of `lanes_per_block` lanes (a power of two, at most a wavefront) per block;
 // a wavefront holds 64 / lanes_per_block blocks side by side.  The lanes of a group walk their
@@ -194,21 +116,6 @@ __global__ void __launch_bounds__(DDL_BLOCK) q4_encode_kernel(const DdlQ4EncodeA
     }
 }
 
-typedef void (*q4_fn)(const DdlQ4Args);
-
-q4_fn pick_q4(int Mq)
-{
-    switch (Mq) {
-#define DDL_CASE(q) \
-    case q: return q4_merge_kernel<q>;
-        DDL_CASE(1) DDL_CASE(2) DDL_CASE(3) DDL_CASE(4) DDL_CASE(5) DDL_CASE(6) DDL_CASE(7)
-        DDL_CASE(8) DDL_CASE(9) DDL_CASE(10) DDL_CASE(11) DDL_CASE(12) DDL_CASE(13)
-        DDL_CASE(14) DDL_CASE(15) DDL_CASE(16)
-#undef DDL_CASE
-    }
-    return nullptr;
-}
-
 inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
 
 bool block_len_ok(size_t block_len)
@@ -255,6 +162,7 @@ extern "C" ddl_status ddl_q4_encode(const float* theta, const void* learner_para
     const uint64_t waves = (blocks + per_wave - 1) / per_wave;
     const dim3 grid((uint32_t)((waves + DDL_BLOCK / 64 - 1) / (DDL_BLOCK / 64))), block(DDL_BLOCK);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    DDL_COUNT_GRID();
     if (learner_dtype == DDL_F32)
         hipLaunchKernelGGL(q4_encode_kernel<LearnerF32>, grid, block, 0, stream, a);
     else
@@ -277,45 +185,124 @@ extern "C" ddl_status ddl_q4_merge_fragment(float* theta, float* v, const uint8_
     if (n == 0) return DDL_OK;
     if (!theta || !v || !codes || !scales || !aligned(theta, 16) || !aligned(v, 16))
         return DDL_ERR_INVALID_ARG;
-    const uint64_t tiles = (n + DDL_TILE - 1) / DDL_TILE;
-    if (tiles > 0x7fffffffull) return DDL_ERR_INVALID_ARG;
     const uint64_t blocks = (n + block_len - 1) / block_len;
 
     ddlh::Quorum q;
     ddlh::compact(w, M, q);
-    DdlQ4Args a;
-    std::memset(&a, 0, sizeof a);
-    const uintptr_t out_lo[2] = {(uintptr_t)theta, (uintptr_t)v};
-    if (out_lo[0] < out_lo[1] + 4 * n && out_lo[1] < out_lo[0] + 4 * n) return DDL_ERR_ALIAS;
+    std::vector<ddlh::Range> r;
+    if (!ddlh::add_range(theta, 4, n, true, r) || !ddlh::add_range(v, 4, n, true, r))
+        return DDL_ERR_INVALID_ARG;
+    DdlQ4Desc qd;
+    std::memset(&qd, 0, sizeof qd);
     for (int j = 0; j < q.Mq; ++j) {
-        const uint8_t* c = codes[q.idx[j]];
-        const float* s = scales[q.idx[j]];
-        if (!c || !s || !aligned(c, 4) || !aligned(s, 4)) return DDL_ERR_INVALID_ARG;
-        const uintptr_t in_lo[2] = {(uintptr_t)c, (uintptr_t)s};
-        const uintptr_t in_hi[2] = {in_lo[0] + (n + 1) / 2, in_lo[1] + 4 * blocks};
-        for (int o = 0; o < 2; ++o)
-            for (int x = 0; x < 2; ++x)
-                if (out_lo[o] < in_hi[x] && in_lo[x] < out_lo[o] + 4 * n) return DDL_ERR_ALIAS;
-        a.codes[j] = (uint64_t)in_lo[0];
-        a.scales[j] = (uint64_t)in_lo[1];
-        a.w[j] = q.w[j];
+        const int m = q.idx[j];
+        const uint8_t* c = codes[m];
+        const float* s = scales[m];
+        if (!c || !s || !aligned(c, 4) || !aligned(s, 4) ||
+            !ddlh::add_range(c, 1, (n + 1) / 2, false, r) || !ddlh::add_range(s, 4, blocks, false, r))
+            return DDL_ERR_INVALID_ARG;
+        qd.codes[m] = c;
+        qd.scales[m] = s;
     }
-    a.theta = (uint64_t)out_lo[0];
-    a.v = (uint64_t)out_lo[1];
-    a.n = n;
-    a.block_len = (uint32_t)block_len;
-    a.block_shift = 0xffffffffu;
-    if ((block_len & (block_len - 1)) == 0) {
-        a.block_shift = 0;
-        while (((size_t)1 << a.block_shift) < block_len) ++a.block_shift;
+    if (ddlh::ranges_alias(r)) return DDL_ERR_ALIAS;
+    DdlSegDesc d;
+    ddlh::fill_desc(d, theta, v, nullptr, nullptr, M, n, 0);
+    return ddlh::launch_flat(d, DDL_SRC_Q4, q, lr, mu, hip_stream, &qd, (uint32_t)block_len);
+}
+
+// ------------------------------------------------------------------------------------------
+// 4-bit sources through a plan: whole fragments of many tensors per launch
+// ------------------------------------------------------------------------------------------
+extern "C" ddl_status ddl_plan_set_q4_sources(ddl_plan* plan, const ddl_q4_segment* segs,
+                                              size_t num_segments, size_t block_len)
+{
+    if (!plan || num_segments != plan->table.given_segs || (num_segments > 0 && !segs))
+        return DDL_ERR_INVALID_ARG;
+    if (!block_len_ok(block_len)) return DDL_ERR_INVALID_ARG;
+    const ddlh::Table& T = plan->table;
+    std::vector<DdlQ4Desc> table(T.segs.size());
+    std::vector<uint32_t> nonnull(T.frags.size());
+    std::vector<ddlh::Range> r;
+    for (size_t f = 0; f < T.frags.size(); ++f) {
+        const ddlh::FragInfo& fi = T.frags[f];
+        nonnull[f] = (1u << fi.M) - 1u;
+        for (uint32_t d = fi.seg_begin; d < fi.seg_begin + fi.num_segs; ++d) {
+            const DdlSegDesc& sd = T.segs[d];
+            const ddl_q4_segment& g = segs[T.origin[d]];
+            if (!g.codes || !g.scales) return DDL_ERR_INVALID_ARG;
+            // the kernel takes Theta and v of such tensors in 128-bit accesses only
+            if (!sd.base_aligned) return DDL_ERR_INVALID_ARG;
+            const uint64_t blocks = (sd.n + block_len - 1) / block_len;
+            if (!ddlh::add_range(sd.theta, 4, sd.n, true, r) ||
+                !ddlh::add_range(sd.v, 4, sd.n, true, r) ||
+                (sd.theta_bf16 && !ddlh::add_range(sd.theta_bf16, 2, sd.n, true, r)))
+                return DDL_ERR_INVALID_ARG;
+            DdlQ4Desc& q = table[d];
+            std::memset(&q, 0, sizeof q);
+            for (int m = 0; m < fi.M; ++m) {
+                const uint8_t* c = g.codes[m];
+                const float* s = g.scales[m];
+                if (!c || !s) {  // a learner without sources here cannot contribute
+                    if (c || s) return DDL_ERR_INVALID_ARG;
+                    nonnull[f] &= ~(1u << m);
+                    continue;
+                }
+                if (!aligned(c, 4) || !aligned(s, 4) ||
+                    !ddlh::add_range(c, 1, (sd.n + 1) / 2, false, r) ||
+                    !ddlh::add_range(s, 4, blocks, false, r))
+                    return DDL_ERR_INVALID_ARG;
+                q.codes[m] = c;
+                q.scales[m] = s;
+            }
+        }
     }
-    a.lr = lr;
-    a.mu = mu;
-    a.rotate = ddlh::tile_rotate();
-    const q4_fn fn = pick_q4(q.Mq);
-    if (!fn) return DDL_ERR_INVALID_ARG;
-    hipLaunchKernelGGL(fn, dim3((uint32_t)tiles), dim3(DDL_BLOCK), ddlh::merge_lds_cap_bytes(0, q.Mq),
-                       static_cast<hipStream_t>(hip_stream), a);
-    const hipError_t e = hipGetLastError();
-    return e == hipSuccess ? DDL_OK : ddlh::runtime_error(e, "q4 merge kernel launch");
+    if (ddlh::ranges_alias(r)) return DDL_ERR_ALIAS;
+    void* dev = nullptr;
+    if (!table.empty()) {
+        const size_t bytes = table.size() * sizeof(DdlQ4Desc);
+        hipError_t e = hipMalloc(&dev, bytes);
+        if (e == hipSuccess) e = hipMemcpy(dev, table.data(), bytes, hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            if (dev) (void)hipFree(dev);
+            return ddlh::runtime_error(e, "q4 source table upload");
+        }
+    }
+    if (plan->d_q4) (void)hipFree(plan->d_q4);
+    plan->d_q4 = dev;
+    plan->q4_block_len = (uint32_t)block_len;
+    plan->q4_nonnull_bits = nonnull;
+    return DDL_OK;
+}
+
+extern "C" ddl_status ddl_plan_q4_merge(ddl_plan* plan, const ddl_sync* syncs, int count,
+                                        void* hip_stream)
+{
+    if (!plan || plan->q4_block_len == 0 || count < 0 || (count > 0 && !syncs))
+        return DDL_ERR_INVALID_ARG;
+    if (count == 0) return DDL_OK;
+    const ddlh::Table& T = plan->table;
+    std::vector<ddlh::Work> work;
+    work.reserve((size_t)count);
+    std::vector<char> seen(T.frags.size(), 0);
+    for (int i = 0; i < count; ++i) {
+        const ddl_sync& s = syncs[i];
+        if (s.fragment < 0 || (size_t)s.fragment >= T.frags.size()) return DDL_ERR_INVALID_ARG;
+        if (seen[(size_t)s.fragment]) return DDL_ERR_ALIAS;
+        seen[(size_t)s.fragment] = 1;
+        if (!ddlh::finite_nonneg(s.lr) || !ddlh::finite_nonneg(s.mu)) return DDL_ERR_INVALID_ARG;
+        const ddlh::FragInfo& f = T.frags[(size_t)s.fragment];
+        double w[DDL_MAXL];
+        const ddl_status st = ddlh::weights_tokens(s.token_counts, s.quorum_mask, f.M, w);
+        if (st != DDL_OK) return st;
+        ddlh::Work wk;
+        wk.frag = (uint32_t)s.fragment;
+        wk.lr = s.lr;
+        wk.mu = s.mu;
+        ddlh::compact(w, f.M, wk.q);
+        if (f.num_segs > 0 && (wk.q.present_bits & ~plan->q4_nonnull_bits[(size_t)s.fragment]))
+            return DDL_ERR_INVALID_ARG;
+        work.push_back(wk);
+    }
+    const ddlh::Q4Source q4 = {static_cast<const DdlQ4Desc*>(plan->d_q4), plan->q4_block_len};
+    return ddlh::launch_work(T, plan->d_table, work, hip_stream, &q4);
 }

@@ -15,15 +15,25 @@
 //     Groups of at most 16384 elements whose data fits the register file take a variant that
 //     loads the group once into registers and sweeps those: one pass over HBM, like direct
 //     averaging.
-// (b) Long or few groups (one norm per tensor): three sweeps over the data, each a grid of one
-//     workgroup per "chunk" (at most DDL_RDA_CHUNK consecutive elements of one group), with
-//     two small per-group kernels in between:
-//   sweep 1  partial sums of d_j^2 per chunk        -> reduce: coefficients c_j = w_j / N_j, R
-//   sweep 2  partial sums of u^2 per chunk           -> reduce: scale = R / ||u||
-//   sweep 3  Delta = scale * u, outer step, write Theta and v
+// (b) Long or few groups (one norm per tensor): sweeps over the data as grids of one workgroup
+//     per "chunk" (at most DDL_RDA_CHUNK consecutive elements of one group), with small
+//     per-group kernels in between.  Everything the method needs from the first look at the
+//     data is in the Gram matrix G_jk = <d_j, d_k> of the group: N_j = sqrt(G_jj), and the norm
+//     of the mean direction is ||sum_j c_j d_j||^2 = c' G c with c_j = w_j / N_j.  So for up to
+//     kGramMaxLearners contributing learners:
+//   sweep 1  partial sums of d_j d_k (j <= k) per chunk   -> reduce (fp64, fixed order): c_j, R,
+//                                                             c' G c, scale = R / sqrt(c' G c)
+//   sweep 2  Delta = scale * sum_j c_j d_j, outer step, write Theta and v
+//     -- two passes over HBM instead of three.  c' G c cancels when the outer gradients nearly
+//     oppose each other; a group whose c' G c is below kGramTrust of sum_jk |c_j c_k G_jk| gets
+//     its direction norm from a sweep of its own after all (the kernels of that sweep run for
+//     every tensor but return at once for the other groups).  More learners than that take
+//   sweep 1  partial sums of d_j^2 per chunk              -> reduce: c_j, R
+//   sweep 2  partial sums of u^2 per chunk                -> reduce: scale = R / ||u||
+//   sweep 3  apply.
 // Partial sums are combined in a fixed order (no atomics): results are reproducible.
-// Sweeps 1 and 2 read with ordinary (cached) loads so that the later sweeps of a small group
-// find the data in L2 or the last-level cache; sweep 3 streams.
+// The sweeps before the last read with ordinary (cached) loads so that the later sweeps of a
+// small group find the data in L2 or the last-level cache; the last sweep streams.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -52,13 +62,15 @@ struct DdlRdaArgs {
     uint64_t n, group_len;
     uint32_t chunks_per_group;
     uint32_t vec_ok;            // all bases 16-byte aligned and group_len % 4 == 0
+    uint32_t gram;              // 1: sweep 1 built the Gram matrix (see the file header)
     float lr, mu;
     // workspace (device): floats
-    uint64_t partial1;          // [chunks][Mq]  sums of d_j^2
+    uint64_t partial1;          // [chunks][Mq] sums of d_j^2, or [chunks][Mq (Mq + 1) / 2] of d_j d_k
     uint64_t coef;              // [groups][Mq]  w_j / N_j (0 where N_j = 0)
     uint64_t mean_norm;         // [groups]      R
     uint64_t partial2;          // [chunks]      sums of u^2
-    uint64_t scale;             // [groups]      R / ||u|| (0 where u = 0)
+    uint64_t scale;             // [groups]      R / ||u|| (0 where u = 0; < 0: still to be
+                                //               computed from partial2)
 };
 
 namespace {
@@ -220,6 +232,157 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_sumsq_kernel(const DdlRdaArgs a
     }
 }
 
+// Contributing learners up to which the first sweep builds the Gram matrix (register budget
+// of the accumulators: Mq (Mq + 1) / 2 of them), and the cancellation it is trusted down to.
+constexpr int kGramMaxLearners = 11;
+constexpr double kGramTrust = 4e-3;
+constexpr int gram_size(int mq) { return mq * (mq + 1) / 2; }
+
+// Sums N values over a wavefront so that every total ends up in ONE lane: at each of the six
+// steps a lane keeps one half of its values and hands the other half to its partner, which
+// costs about 4 N operations in all where a butterfly per value costs 12 N.  Afterwards slot i
+// (i < slots) of lane l holds the total of entry index[i] (valid if index[i] < N).
+template <int N>
+struct WaveScatterSum {
+    static constexpr int half(int n) { return (n + 1) / 2; }
+    static constexpr int slots = half(half(half(half(half(half(N))))));
+    template <int CNT, int OFF>
+    static __device__ __forceinline__ void step(float (&x)[N], int (&index)[slots], bool)
+    {
+        if constexpr (OFF >= 1) {
+            constexpr int H = half(CNT);
+            const bool up = (threadIdx.x & OFF) != 0;
+#pragma unroll
+            for (int i = 0; i < H; ++i) {
+                const float lo = x[i];
+                const float hi = i + H < CNT ? x[i + H] : 0.0f;
+                const float got = __shfl_xor(up ? lo : hi, OFF, 64);
+                x[i] = (up ? hi : lo) + got;
+            }
+            step<H, OFF / 2>(x, index, up);
+            // entries of the upper half sit H further up in the previous numbering
+#pragma unroll
+            for (int i = 0; i < slots; ++i)
+                if (up) index[i] = index[i] < H && index[i] + H < CNT ? index[i] + H : N;
+        }
+    }
+    static __device__ __forceinline__ void run(float (&x)[N], int (&index)[slots])
+    {
+#pragma unroll
+        for (int i = 0; i < slots; ++i) index[i] = i;
+        step<N, 32>(x, index, false);
+    }
+};
+
+// Sweep 1 of the Gram form: per chunk, the sums of d_j d_k for j <= k, row-major upper triangle.
+template <typename L, int MQ>
+__global__ void __launch_bounds__(DDL_BLOCK) rda_gram_kernel(const DdlRdaArgs a)
+{
+    constexpr int P = gram_size(MQ);
+    typedef WaveScatterSum<P> Sum;
+    __shared__ float lds[DDL_BLOCK / 64][P];
+    uint64_t begin, end;
+    uint32_t group;
+    chunk_range(a, blockIdx.x, begin, end, group);
+    float acc[P];
+#pragma unroll
+    for (int p = 0; p < P; ++p) acc[p] = 0.0f;
+    auto add = [&](const float (&d)[MQ]) {
+        int p = 0;
+#pragma unroll
+        for (int j = 0; j < MQ; ++j)
+#pragma unroll
+            for (int k = j; k < MQ; ++k, ++p) acc[p] = fmaf(d[j], d[k], acc[p]);
+    };
+    sweep_chunk<L, MQ, false>(
+        a, begin, end, false,
+        [&](const float (&d)[4][MQ], const f32x4&, const f32x4&, uint32_t) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) add(d[k]);
+        },
+        [&](const float (&d)[MQ], float, float, uint32_t) { add(d); });
+    int index[Sum::slots];
+    Sum::run(acc, index);
+#pragma unroll
+    for (int i = 0; i < Sum::slots; ++i)
+        if (index[i] < P) lds[threadIdx.x >> 6][index[i]] = acc[i];
+    __syncthreads();
+    float* out = reinterpret_cast<float*>(a.partial1) + (size_t)blockIdx.x * P;
+    for (int p = threadIdx.x; p < P; p += DDL_BLOCK) {
+        float s = 0.0f;
+#pragma unroll
+        for (int wv = 0; wv < DDL_BLOCK / 64; ++wv) s += lds[wv][p];  // waves in a fixed order
+        out[p] = s;
+    }
+}
+
+// One workgroup per group: the Gram matrix from the chunk partials (each thread sums its own
+// chunks in ascending order in double, then lanes by butterfly, then the waves in sequence),
+// and from it the coefficients c_j = w_j / N_j, the mean norm R and, where c' G c can be
+// trusted, scale = R / sqrt(c' G c); otherwise scale = -1 asks for the direct sweep.
+template <int MQ>
+__global__ void __launch_bounds__(DDL_BLOCK) rda_gram_reduce_kernel(const DdlRdaArgs a)
+{
+    constexpr int P = gram_size(MQ);
+    __shared__ double lds[DDL_BLOCK / 64][P];
+    const uint32_t r = blockIdx.x;
+    const float* p1 = reinterpret_cast<const float*>(a.partial1) + (size_t)r * a.chunks_per_group * P;
+    double g[P];
+#pragma unroll
+    for (int p = 0; p < P; ++p) g[p] = 0.0;
+    for (uint32_t c = threadIdx.x; c < a.chunks_per_group; c += DDL_BLOCK) {
+        const float* row = p1 + (size_t)c * P;
+#pragma unroll
+        for (int p = 0; p < P; ++p) g[p] += (double)row[p];
+    }
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) g[p] += __shfl_xor(g[p], off, 64);
+        if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6][p] = g[p];
+    }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        double s = 0.0;
+#pragma unroll
+        for (int wv = 0; wv < DDL_BLOCK / 64; ++wv) s += lds[wv][p];
+        g[p] = s;
+    }
+    double c[MQ];
+    double R = 0.0;
+    {
+        int p = 0;
+#pragma unroll
+        for (int j = 0; j < MQ; ++j) {
+            const double N = sqrt(g[p]);  // the diagonal entry G_jj
+            R += (double)a.w[j] * N;
+            c[j] = N > 0.0 ? (double)a.w[j] / N : 0.0;
+            p += MQ - j;
+        }
+    }
+    double q = 0.0, mass = 0.0;  // c' G c and the sum of the magnitudes of its terms
+    {
+        int p = 0;
+#pragma unroll
+        for (int j = 0; j < MQ; ++j)
+#pragma unroll
+            for (int k = j; k < MQ; ++k, ++p) {
+                const double term = (j == k ? 1.0 : 2.0) * c[j] * c[k] * g[p];
+                q += term;
+                mass += fabs(term);
+            }
+    }
+    float* coef = reinterpret_cast<float*>(a.coef) + (size_t)r * MQ;
+#pragma unroll
+    for (int j = 0; j < MQ; ++j) coef[j] = (float)c[j];
+    reinterpret_cast<float*>(a.mean_norm)[r] = (float)R;
+    float scale = 0.0f;                              // no direction at all: Delta = 0
+    if (mass > 0.0) scale = q >= kGramTrust * mass ? (float)(R / sqrt(q)) : -1.0f;
+    reinterpret_cast<float*>(a.scale)[r] = scale;
+}
+
 // One workgroup per group: norms from the chunk partials (in double, fixed order), then the
 // direction coefficients w_j / N_j and the mean norm.
 __global__ void __launch_bounds__(DDL_BLOCK) rda_norms_kernel(const DdlRdaArgs a, int Mq)
@@ -255,6 +418,8 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_dirsq_kernel(const DdlRdaArgs a
     uint64_t begin, end;
     uint32_t group;
     chunk_range(a, blockIdx.x, begin, end, group);
+    // After the Gram reduce only groups whose scale is still open (< 0) need this sweep.
+    if (a.gram && !(reinterpret_cast<const float*>(a.scale)[group] < 0.0f)) return;
     float c[MQ];
 #pragma unroll
     for (int j = 0; j < MQ; ++j)
@@ -281,6 +446,7 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_scale_kernel(const DdlRdaArgs a
 {
     __shared__ double lds[DDL_BLOCK];
     const uint32_t r = blockIdx.x;
+    if (a.gram && !(reinterpret_cast<const float*>(a.scale)[r] < 0.0f)) return;
     const float* p2 = reinterpret_cast<const float*>(a.partial2) + (size_t)r * a.chunks_per_group;
     const double U = sqrt(block_sum_strided(p2, a.chunks_per_group, 1, lds));
     const double R = (double)reinterpret_cast<const float*>(a.mean_norm)[r];
@@ -454,12 +620,12 @@ __device__ __forceinline__ void rda_row_body(uint64_t th, uint64_t vv, uint64_t 
     for (int u = 0; u < K; ++u) {
         const uint32_t g = threadIdx.x + u * NTH;
 #if DDL_RDA_V_EARLY
-        V[u] = g < nvec ? ld<f32x4, true>(vv, g) : f32x4(0.0f);
+        V[u] = g < nvec ? ld<f32x4, DDL_NT_LOAD>(vv, g) : f32x4(0.0f);
 #endif
         if (g < nvec) {
 #pragma unroll
-            for (int j = 0; j < MQ; ++j) raw[u][j] = ld<typename L::raw, true>(lp[j], g);
-            T[u] = ld<f32x4, true>(th, g);
+            for (int j = 0; j < MQ; ++j) raw[u][j] = ld<typename L::raw, DDL_NT_LOAD>(lp[j], g);
+            T[u] = ld<f32x4, DDL_NT_LOAD>(th, g);
         } else {  // lanes past the end of the group hold a zero outer gradient
 #pragma unroll
             for (int j = 0; j < MQ; ++j) raw[u][j] = typename L::raw(0);
@@ -479,6 +645,16 @@ __device__ __forceinline__ void rda_row_body(uint64_t th, uint64_t vv, uint64_t 
             for (int j = 0; j < MQ; ++j) d[k][j] = t4[k] - x[j][k];
     };
 
+    // Sweep 1: the learners' norms over the group.  (DDL_RDA_DIAG_NO_SWEEPS is a measurement
+    // build that leaves both reductions out -- Delta = sum_j w_j d_j, i.e. direct averaging in
+    // this kernel's shape -- to show what the row-per-workgroup structure alone costs.)
+    float c[MQ];
+    float scale = 1.0f;
+#ifdef DDL_RDA_DIAG_NO_SWEEPS
+#pragma unroll
+    for (int j = 0; j < MQ; ++j) c[j] = w[j];
+    (void)lds;
+#else
     float ss[MQ];
 #pragma unroll
     for (int j = 0; j < MQ; ++j) ss[j] = 0.0f;
@@ -491,7 +667,6 @@ __device__ __forceinline__ void rda_row_body(uint64_t th, uint64_t vv, uint64_t 
 #pragma unroll
             for (int j = 0; j < MQ; ++j) ss[j] = fmaf(d[k][j], d[k][j], ss[j]);
     }
-    float c[MQ];
     float R = 0.0f;
     block_sum_all<NTH, MQ>(ss, lds);
 #pragma unroll
@@ -500,51 +675,55 @@ __device__ __forceinline__ void rda_row_body(uint64_t th, uint64_t vv, uint64_t 
         R = fmaf(w[j], N, R);
         c[j] = N > 0.0f ? w[j] / N : 0.0f;
     }
-
 #pragma unroll
     for (int u = 0; u < K; ++u)
 #pragma unroll
         for (int j = 0; j < MQ; ++j) launder(raw[u][j]);
+#endif
+
+    // Sweep 2: the mean direction u = sum_j c_j d_j, kept in registers (the packed learner
+    // values are dead from here on, so this costs no extra registers), and its norm.
+    f32x4 dir[K];
     float uu = 0.0f;
 #pragma unroll
     for (int u = 0; u < K; ++u) {
         float d[4][MQ];
         diffs(u, d);
+        float x[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const float x = direction<MQ>(d[k], c);
-            uu = fmaf(x, x, uu);
+            x[k] = direction<MQ>(d[k], c);
+            uu = fmaf(x[k], x[k], uu);
         }
+        dir[u] = f32x4{x[0], x[1], x[2], x[3]};
     }
+#ifndef DDL_RDA_DIAG_NO_SWEEPS
     float usum[1] = {uu};
     block_sum_all<NTH, 1>(usum, lds);
     const float U = sqrtf(usum[0]);
-    const float scale = U > 0.0f ? R / U : 0.0f;
-#pragma unroll
-    for (int j = 0; j < MQ; ++j) c[j] *= scale;
+    scale = U > 0.0f ? R / U : 0.0f;
+#else
+    (void)uu;
+#endif
 
-#pragma unroll
-    for (int u = 0; u < K; ++u)
-#pragma unroll
-        for (int j = 0; j < MQ; ++j) launder(raw[u][j]);
+    // Sweep 3: Delta = scale * u, outer step.
 #if !DDL_RDA_V_EARLY
     f32x4 V[K];
 #pragma unroll
     for (int u = 0; u < K; ++u) {
         const uint32_t g = threadIdx.x + u * NTH;
-        V[u] = g < nvec ? ld<f32x4, true>(vv, g) : f32x4(0.0f);
+        V[u] = g < nvec ? ld<f32x4, DDL_NT_LOAD>(vv, g) : f32x4(0.0f);
     }
 #endif
 #pragma unroll
     for (int u = 0; u < K; ++u) {
         const uint32_t g = threadIdx.x + u * NTH;
-        float d[4][MQ];
-        diffs(u, d);
         float t4[4] = {T[u].x, T[u].y, T[u].z, T[u].w};
         float v4[4] = {V[u].x, V[u].y, V[u].z, V[u].w};
+        const float x[4] = {dir[u].x, dir[u].y, dir[u].z, dir[u].w};
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const float delta = direction<MQ>(d[k], c);
+            const float delta = scale * x[k];
             v4[k] = fmaf(mu, v4[k], delta);
             t4[k] = fmaf(-lr, fmaf(mu, v4[k], delta), t4[k]);
         }
@@ -595,7 +774,7 @@ struct DdlRdaRowsArgs {
     const DdlRdaRowRef* refs;  // first list entry of this launch
     const uint32_t* coarse;    // first coarse entry of this launch
     uint32_t coarse_shift;
-    uint32_t pad;
+    uint32_t row_base;      // first row this grid covers (a long launch goes out in parts)
     float lr, mu;
     float w[DDL_MAXL];      // normalised weights of the contributing learners, compacted
     uint8_t idx[DDL_MAXL];  // learner index of compacted entry j
@@ -606,7 +785,7 @@ __global__ void __launch_bounds__(NTH) rda_rows_kernel(const DdlRdaRowsArgs a)
 {
     __shared__ float lds[NTH / 64 * MQ];
     typedef typename L::elem elem;
-    const uint32_t r = blockIdx.x;
+    const uint32_t r = a.row_base + blockIdx.x;
     const DDL_CONST DdlRdaRowRef* refs =
         reinterpret_cast<const DDL_CONST DdlRdaRowRef*>(reinterpret_cast<uint64_t>(a.refs));
     const DDL_CONST uint32_t* coarse =
@@ -650,7 +829,7 @@ constexpr bool row_kernel_fits()
 {
     const int words = (int)(sizeof(typename L::raw) / 4) * MQ;  // packed learner words per slot
     if (NTH > 512) return words <= (K >= 4 ? 12 : K == 2 ? 16 : 24);
-    return K * (words + 8) <= 192;
+    return K * (words + 8) <= (DDL_RDA_V_EARLY ? 184 : 192);  // v held through the sweeps
 }
 
 typedef void (*rda_fn)(const DdlRdaArgs);
@@ -662,8 +841,8 @@ typedef void (*rda_rows_fn)(const DdlRdaRowsArgs);
 // does not fit the registers for this many learners (it keeps fewer groups per lane).
 #ifndef DDL_RDA_ROW_CLASSES
 #define DDL_RDA_ROW_CLASSES(X) \
-    X(0, 1, 256, 1, 256) X(1, 2, 256, 1, 512) X(2, 4, 256, 2, 512) X(3, 8, 256, 4, 512) \
-    X(4, 4, 1024, 8, 512)
+    X(0, 1, 256, 1, 256) X(1, 2, 256, 1, 512) X(2, 4, 256, 2, 512) X(3, 4, 512, 8, 256) \
+    X(4, 8, 512, 4, 1024)
 #endif
 struct RowClass {
     uint32_t max_len;
@@ -720,6 +899,7 @@ void pick_row(int cls, rda_fn& one, rda_rows_fn& many, uint32_t& threads)
 
 struct Kernels {
     rda_fn sumsq = nullptr, dirsq = nullptr, apply = nullptr, group = nullptr, row = nullptr;
+    rda_fn gram = nullptr, gram_reduce = nullptr;  // null beyond kGramMaxLearners
     rda_rows_fn rows = nullptr;
     uint32_t row_threads = 0;  // workgroup size of row / rows
 };
@@ -734,6 +914,10 @@ void pick(int Mq, int cls, Kernels& k)
         k.dirsq = rda_dirsq_kernel<L, q>;        \
         k.apply = rda_apply_kernel<L, q>;        \
         k.group = rda_group_kernel<L, q>;        \
+        if constexpr (q <= kGramMaxLearners) {   \
+            k.gram = rda_gram_kernel<L, q>;      \
+            k.gram_reduce = rda_gram_reduce_kernel<q>; \
+        }                                        \
         pick_row<L, q>(cls, k.row, k.rows, k.row_threads); \
         break;
         DDL_CASE(1) DDL_CASE(2) DDL_CASE(3) DDL_CASE(4) DDL_CASE(5) DDL_CASE(6) DDL_CASE(7)
@@ -756,6 +940,12 @@ struct Geometry {
     size_t off_partial1, off_coef, off_mean, off_partial2, off_scale, bytes;
 };
 
+// Floats per chunk that sweep 1 leaves behind, at most, for up to Mq contributing learners.
+int partial_width(int Mq)
+{
+    return Mq <= kGramMaxLearners ? gram_size(Mq) : std::max(Mq, gram_size(kGramMaxLearners));
+}
+
 // Workspace layout for n elements in groups of group_len with Mq contributing learners
 // (sized for Mq = M, the worst case, by the public size query).
 bool geometry(size_t n, size_t group_len, int Mq, Geometry& g)
@@ -772,7 +962,7 @@ bool geometry(size_t n, size_t group_len, int Mq, Geometry& g)
         off += ((size_t)floats * 4 + 255) & ~(size_t)255;
         return at;
     };
-    g.off_partial1 = take(g.chunks * Mq);
+    g.off_partial1 = take(g.chunks * (uint64_t)partial_width(Mq));
     g.off_coef = take(g.groups * Mq);
     g.off_mean = take(g.groups);
     g.off_partial2 = take(g.chunks);
@@ -818,16 +1008,31 @@ ddl_status launch_one(ddl_dtype dt, int Mq, DdlRdaArgs& a, const Geometry& g, vo
     const dim3 block(DDL_BLOCK);
     const uint32_t groups = (uint32_t)g.groups;
     if (k.row && a.vec_ok && a.n % 4 == 0 && groups >= kGroupKernelMinGroups) {
+        DDL_COUNT_GRID();
         hipLaunchKernelGGL(k.row, dim3(groups), dim3(k.row_threads), row_lds_cap(), stream,
                            a);
     } else if (a.group_len <= kGroupKernelMaxLen && groups >= kGroupKernelMinGroups) {
+        DDL_COUNT_GRID();
         hipLaunchKernelGGL(k.group, dim3(groups), block, row_lds_cap(), stream, a);
     } else {
         const dim3 grid((uint32_t)g.chunks), rgrid(groups);
-        hipLaunchKernelGGL(k.sumsq, grid, block, 0, stream, a);
-        hipLaunchKernelGGL(rda_norms_kernel, rgrid, block, 0, stream, a, Mq);
+        a.gram = k.gram ? 1u : 0u;
+        if (k.gram) {
+            DDL_COUNT_GRID();
+            hipLaunchKernelGGL(k.gram, grid, block, 0, stream, a);
+            DDL_COUNT_GRID();
+            hipLaunchKernelGGL(k.gram_reduce, rgrid, block, 0, stream, a);
+        } else {
+            DDL_COUNT_GRID();
+            hipLaunchKernelGGL(k.sumsq, grid, block, 0, stream, a);
+            DDL_COUNT_GRID();
+            hipLaunchKernelGGL(rda_norms_kernel, rgrid, block, 0, stream, a, Mq);
+        }
+        DDL_COUNT_GRID();
         hipLaunchKernelGGL(k.dirsq, grid, block, 0, stream, a);
+        DDL_COUNT_GRID();
         hipLaunchKernelGGL(rda_scale_kernel, rgrid, block, 0, stream, a);
+        DDL_COUNT_GRID();
         hipLaunchKernelGGL(k.apply, grid, block, 0, stream, a);
     }
     const hipError_t e = hipGetLastError();
@@ -1003,6 +1208,7 @@ extern "C" ddl_status ddl_rda_merge_fragment_static(float* theta, float* v,
 struct DdlRdaPlan {
     struct Class {
         uint32_t ref_begin = 0, num_refs = 0, rows = 0, coarse_begin = 0, coarse_shift = 0;
+        uint64_t elems = 0;  // elements of all its tensors
     };
     struct Frag {
         Class cls[kNumRowClasses];
@@ -1087,6 +1293,7 @@ extern "C" ddl_status ddl_plan_set_rda_groups(ddl_plan* plan, const size_t* grou
                 if (rows > 0x7fffffffull) break;
                 R->refs.push_back({d, (uint32_t)rows, (uint32_t)g, 0u});
                 rows += (T.segs[d].n + g - 1) / g;
+                k.elems += T.segs[d].n;
             }
             if (rows > 0x7fffffffull) {
                 delete R;
@@ -1221,6 +1428,7 @@ extern "C" ddl_status ddl_plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, 
             if (k.num_refs == 0) continue;
             Kernels fn;
             pick(f.dt, wk.q.Mq, c, fn);
+            const int sd_extra_bytes = 0;
             if (fn.rows) {
                 DdlRdaRowsArgs a;
                 std::memset(&a, 0, sizeof a);
@@ -1232,10 +1440,24 @@ extern "C" ddl_status ddl_plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, 
                 a.mu = wk.mu;
                 std::memcpy(a.w, wk.q.w, sizeof a.w);
                 std::memcpy(a.idx, wk.q.idx, sizeof a.idx);
-                hipLaunchKernelGGL(fn.rows, dim3(k.rows), dim3(fn.row_threads), row_lds_cap(),
-                                   stream, a);
-                const hipError_t e = hipGetLastError();
-                if (e != hipSuccess) return ddlh::runtime_error(e, "RDA rows kernel launch");
+                // Like the direct-averaging merge, a long launch goes out as several equal
+                // grids, which keeps the XCDs aligned: the limit in elements becomes rows.
+                const uint64_t max_tiles = ddlh::max_tiles_per_launch(
+                    f.dt == DDL_BF16 ? 2 : 4, wk.q.Mq, sd_extra_bytes);
+                uint64_t part = k.rows;
+                if (max_tiles != 0 && k.elems > max_tiles * DDL_TILE) {
+                    const uint64_t parts = (k.elems + max_tiles * DDL_TILE - 1) / (max_tiles * DDL_TILE);
+                    part = (k.rows + parts - 1) / parts;
+                }
+                for (uint64_t base = 0; base < k.rows; base += part) {
+                    a.row_base = (uint32_t)base;
+                    const uint32_t rows = (uint32_t)std::min<uint64_t>(part, k.rows - base);
+                    DDL_COUNT_GRID();
+                    hipLaunchKernelGGL(fn.rows, dim3(rows), dim3(fn.row_threads), row_lds_cap(),
+                                       stream, a);
+                    const hipError_t e = hipGetLastError();
+                    if (e != hipSuccess) return ddlh::runtime_error(e, "RDA rows kernel launch");
+                }
             } else {  // this many learners do not fit the registers of this class
                 for (uint32_t r = 0; r < k.num_refs; ++r) {
                     const ddl_status st = one_tensor(f, wk, R.refs[k.ref_begin + r].seg);

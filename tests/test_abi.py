@@ -237,7 +237,7 @@ int main(void) {
 
 
 def test_options(ddl):
-    assert ddl.get_option("tiles_per_block") >= 1
+    assert ddl.get_option("tiles_per_block") == -1          # the library chooses
     assert ddl.get_option("max_blocks_per_cu") == -1          # chosen by the library
     assert ddl.get_option("tile_rotate") == 64
     with pytest.raises(ddl.DdlError):

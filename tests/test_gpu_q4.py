@@ -181,3 +181,161 @@ def test_errors(ddl):
     ddl.q4_merge_fragment(theta[:0], v[:0], [c, c], [s, s], tokens, mask, B, 0.7, 0.9)   # n = 0
     torch.cuda.synchronize()
     assert not torch.equal(theta, keep)
+
+
+# ---- whole fragments of many tensors through a plan ---------------------------------------------
+def _q4_plan_case(ddl, wl, B, bcast_every=0, null_absent=True):
+    """Encodes every tensor of every contributing learner, builds a plan whose learner pointers
+    are all NULL (the 4-bit merge does not use them) and returns what a test needs."""
+    data, refs, sources, outs = [], [], [], []
+    for f in wl.fragments:
+        segs = ddl_synth.make_fragment(wl, f, DEV)
+        present = [bool(q) and t > 0 for q, t in zip(f.quorum_mask, f.token_counts)]
+        data.append(segs)
+        frag_refs = []
+        for si, s in enumerate(segs):
+            codes, scales = [], []
+            for m in range(f.M):
+                if not present[m] and null_absent:
+                    codes.append(None)
+                    scales.append(None)
+                elif s.theta.numel() == 0:
+                    codes.append(torch.zeros(0, dtype=torch.uint8, device=DEV))
+                    scales.append(torch.zeros(0, dtype=torch.float32, device=DEV))
+                else:
+                    c, sc = ddl.q4_encode(s.theta, s.learners[m], B)
+                    if not present[m]:
+                        sc.fill_(float("nan"))        # never read
+                    codes.append(c)
+                    scales.append(sc)
+            sources.append((codes, scales))
+            torch.cuda.synchronize()
+            frag_refs.append(oracle.q4_merge_fragment(
+                _host(s.theta), _host(s.v),
+                [_host(c) if (c is not None and p) else None for c, p in zip(codes, present)],
+                [_host(sc) if (sc is not None and p) else None for sc, p in zip(scales, present)],
+                f.token_counts, f.quorum_mask, B, f.lr, f.mu) if s.theta.numel() else None)
+            outs.append(torch.zeros(s.theta.numel(), dtype=torch.bfloat16, device=DEV)
+                        if bcast_every and (len(outs) % bcast_every == 0) else None)
+        refs.append(frag_refs)
+    k = 0
+    frags = []
+    for f, segs in zip(wl.fragments, data):
+        tup = []
+        for s in segs:
+            tup.append((s.theta, s.v, [None] * f.M, outs[k]))
+            k += 1
+        frags.append(ddl.Fragment(tup, M=f.M, learner_dtype=torch.bfloat16))
+    plan = ddl.Plan(frags)
+    plan.set_q4_sources(sources, B)
+    return plan, data, refs, outs
+
+
+@pytest.mark.parametrize("name,B", [("dense_block", 128), ("large_dense", 64), ("moe", 128),
+                                    ("moe", 24), ("streaming_model", 128), ("small_fragments", 8)])
+def test_plan_q4_reduced_workloads(ddl, name, B):
+    """Every tensor of every fragment against the oracle's 4-bit merge, element by element; a
+    third of the tensors also get the bf16 copy of the new Theta.  One fragment per call in
+    arrival order for the streaming model, all fragments in one call otherwise."""
+    wl = ddl_synth.reduced(name)
+    plan, data, refs, outs = _q4_plan_case(ddl, wl, B, bcast_every=3)
+    syncs = [(f.index, f.token_counts, f.quorum_mask, f.lr, f.mu) for f in wl.fragments]
+    print(f"q4 plan {name} B={B}", flush=True)
+    if name == "streaming_model":
+        for fi in wl.arrival_order:
+            plan.q4_merge([syncs[fi]])
+    else:
+        plan.q4_merge(syncs)
+    torch.cuda.synchronize()
+    k = 0
+    for fi, segs in enumerate(data):
+        for si, s in enumerate(segs):
+            ref = refs[fi][si]
+            if ref is not None:
+                assert_parity(_host(s.theta), ref[0], f"{name} f{fi} t{si} theta")
+                assert_parity(_host(s.v), ref[1], f"{name} f{fi} t{si} v")
+                if outs[k] is not None:                      # RNE bf16 of the fp32 result
+                    want = oracle.round_bf16(_host(s.theta))
+                    got = outs[k].view(torch.int16).cpu().numpy().view(np.uint16)
+                    assert np.array_equal(got, want), f"{name} f{fi} t{si} bf16 copy"
+            k += 1
+    plan.destroy()
+
+
+def test_plan_q4_equals_flat_calls_and_sizes(ddl):
+    """Tensors of awkward sizes (empty, shorter than a group, ragged tiles, several tiles, block
+    lengths that are no power of two) in one fragment: the plan result equals one
+    ddl_q4_merge_fragment call per tensor bit for bit, and the oracle within the bar."""
+    B, M, mask = 40, 5, [1, 0, 1, 1, 1]
+    sizes = [0, 1, 3, 4, 5, 39, 40, 41, 1023, 1024, 1025, 2048 + 7, 5 * 1024, 70001, 0, 12288]
+    tokens = [5, 7, 11, 13, 17]
+    segs, flat, sources = [], [], []
+    for i, n in enumerate(sizes):
+        th, v, ls, _, _ = random_problem(1700 + i, n, M, torch.bfloat16, DEV)
+        enc = [ddl.q4_encode(th, l, B) if n else
+               (torch.zeros(0, dtype=torch.uint8, device=DEV),
+                torch.zeros(0, dtype=torch.float32, device=DEV)) for l in ls]
+        codes = [c if q else None for (c, _), q in zip(enc, mask)]
+        scales = [s if q else None for (_, s), q in zip(enc, mask)]
+        segs.append((th, v, [None] * M))
+        sources.append((codes, scales))
+        flat.append((th.clone(), v.clone(), codes, scales))
+    torch.cuda.synchronize()
+    refs = [oracle.q4_merge_fragment(_host(th), _host(v), [None if c is None else _host(c) for c in cs],
+                                     [None if s is None else _host(s) for s in ss], tokens, mask, B,
+                                     0.7, 0.9) if th.numel() else None
+            for th, v, cs, ss in flat]
+    plan = ddl.Plan([ddl.Fragment(segs, M=M, learner_dtype=torch.bfloat16)])
+    plan.set_q4_sources(sources, B)
+    plan.q4_merge([(0, tokens, mask, 0.7, 0.9)])
+    for th, v, cs, ss in flat:
+        ddl.q4_merge_fragment(th, v, cs, ss, tokens, mask, B, 0.7, 0.9)
+    torch.cuda.synchronize()
+    for i, ((th, v, _), (fth, fv, _, _), ref) in enumerate(zip(segs, flat, refs)):
+        assert torch.equal(th, fth) and torch.equal(v, fv), f"tensor {i}: plan != flat call"
+        if ref is not None:
+            assert_parity(_host(th), ref[0], f"tensor {i} theta")
+            assert_parity(_host(v), ref[1], f"tensor {i} v")
+    plan.destroy()
+
+
+def test_plan_q4_errors(ddl):
+    n, B, M = 5000, 128, 2
+    th, v, ls, tokens, mask = random_problem(1800, n, M, torch.bfloat16, DEV)
+    c0, s0 = ddl.q4_encode(th, ls[0], B)
+    c1, s1 = ddl.q4_encode(th, ls[1], B)
+    keep = th.clone()
+    plan = ddl.Plan([ddl.Fragment([(th, v, [None] * M)], M=M, learner_dtype=torch.bfloat16)])
+    sync = [(0, tokens, mask, 0.7, 0.9)]
+    with pytest.raises(ddl.DdlError) as e:                       # sources never set
+        plan.q4_merge(sync)
+    assert e.value.status == ddl.DDL_ERR_INVALID_ARG
+    with pytest.raises(ddl.DdlError) as e:                       # wrong number of segments
+        plan.set_q4_sources([([c0, c1], [s0, s1])] * 2, B)
+    assert e.value.status == ddl.DDL_ERR_INVALID_ARG
+    with pytest.raises(ddl.DdlError) as e:                       # bad block length
+        plan.set_q4_sources([([c0, c1], [s0, s1])], 12)
+    assert e.value.status == ddl.DDL_ERR_INVALID_ARG
+    with pytest.raises(ddl.DdlError) as e:                       # codes without scales
+        plan.set_q4_sources([([c0, c1], [s0, None])], B)
+    assert e.value.status == ddl.DDL_ERR_INVALID_ARG
+    with pytest.raises(ddl.DdlError) as e:                       # scales alias v
+        plan.set_q4_sources([([c0, c1], [s0, v[:s1.numel()]])], B)
+    assert e.value.status == ddl.DDL_ERR_ALIAS
+    plan.set_q4_sources([([c0, None], [s0, None])], B)           # learner 1 has no sources
+    with pytest.raises(ddl.DdlError) as e:                       # ... so it cannot contribute
+        plan.q4_merge(sync)
+    assert e.value.status == ddl.DDL_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert torch.equal(th, keep)
+    plan.q4_merge([(0, tokens, [1, 0], 0.7, 0.9)])               # fine without it
+    torch.cuda.synchronize()
+    assert not torch.equal(th, keep)
+    # a misaligned Theta is refused when the sources are set
+    th2, v2, ls2, _, _ = random_problem(1801, n, M, torch.bfloat16, DEV, offset=1)
+    plan2 = ddl.Plan([ddl.Fragment([(th2, v2, [None] * M)], M=M, learner_dtype=torch.bfloat16)])
+    with pytest.raises(ddl.DdlError) as e:
+        plan2.set_q4_sources([([c0, c1], [s0, s1])], B)
+    assert e.value.status == ddl.DDL_ERR_INVALID_ARG
+    plan.destroy()
+    plan2.destroy()
