@@ -26,8 +26,8 @@
 //   sweep 2  Delta = scale * sum_j c_j d_j, outer step, write Theta and v
 //     -- two passes over HBM instead of three.  c' G c cancels when the outer gradients nearly
 //     oppose each other; a group whose c' G c is below kGramTrust of sum_jk |c_j c_k G_jk| gets
-//     its direction norm from a sweep of its own after all (the kernels of that sweep run for
-//     every tensor but return at once for the other groups).  More learners than that take
+//     its direction norm summed from the data after all, by the workgroup of the reduce kernel
+//     that found it so.  More learners than that take
 //   sweep 1  partial sums of d_j^2 per chunk              -> reduce: c_j, R
 //   sweep 2  partial sums of u^2 per chunk                -> reduce: scale = R / ||u||
 //   sweep 3  apply.
@@ -62,15 +62,13 @@ struct DdlRdaArgs {
     uint64_t n, group_len;
     uint32_t chunks_per_group;
     uint32_t vec_ok;            // all bases 16-byte aligned and group_len % 4 == 0
-    uint32_t gram;              // 1: sweep 1 built the Gram matrix (see the file header)
     float lr, mu;
     // workspace (device): floats
     uint64_t partial1;          // [chunks][Mq] sums of d_j^2, or [chunks][Mq (Mq + 1) / 2] of d_j d_k
     uint64_t coef;              // [groups][Mq]  w_j / N_j (0 where N_j = 0)
     uint64_t mean_norm;         // [groups]      R
     uint64_t partial2;          // [chunks]      sums of u^2
-    uint64_t scale;             // [groups]      R / ||u|| (0 where u = 0; < 0: still to be
-                                //               computed from partial2)
+    uint64_t scale;             // [groups]      R / ||u|| (0 where u = 0)
 };
 
 namespace {
@@ -232,6 +230,15 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_sumsq_kernel(const DdlRdaArgs a
     }
 }
 
+template <int MQ>
+__device__ __forceinline__ float direction(const float (&d)[MQ], const float (&c)[MQ])
+{
+    float u = 0.0f;
+#pragma unroll
+    for (int j = 0; j < MQ; ++j) u = fmaf(c[j], d[j], u);
+    return u;
+}
+
 // Contributing learners up to which the first sweep builds the Gram matrix (register budget
 // of the accumulators: Mq (Mq + 1) / 2 of them), and the cancellation it is trusted down to.
 constexpr int kGramMaxLearners = 11;
@@ -318,13 +325,18 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_gram_kernel(const DdlRdaArgs a)
 
 // One workgroup per group: the Gram matrix from the chunk partials (each thread sums its own
 // chunks in ascending order in double, then lanes by butterfly, then the waves in sequence),
-// and from it the coefficients c_j = w_j / N_j, the mean norm R and, where c' G c can be
-// trusted, scale = R / sqrt(c' G c); otherwise scale = -1 asks for the direct sweep.
-template <int MQ>
+// and from it the coefficients c_j = w_j / N_j, the mean norm R and scale = R / sqrt(c' G c).
+// Where c' G c cannot be trusted (the outer gradients nearly cancel) this workgroup walks its
+// group once more and sums the squares of the mean direction itself: slow, since it is one
+// workgroup for the whole group, but it concerns only such groups and keeps the common case
+// at three launches (Gram sweep, this kernel, apply).
+template <typename L, int MQ>
 __global__ void __launch_bounds__(DDL_BLOCK) rda_gram_reduce_kernel(const DdlRdaArgs a)
 {
     constexpr int P = gram_size(MQ);
     __shared__ double lds[DDL_BLOCK / 64][P];
+    __shared__ float coef_lds[MQ];
+    __shared__ float verdict[2];  // scale (< 0: not trusted), R
     const uint32_t r = blockIdx.x;
     const float* p1 = reinterpret_cast<const float*>(a.partial1) + (size_t)r * a.chunks_per_group * P;
     double g[P];
@@ -342,45 +354,91 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_gram_reduce_kernel(const DdlRda
         if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6][p] = g[p];
     }
     __syncthreads();
-    if (threadIdx.x != 0) return;
+    if (threadIdx.x == 0) {
 #pragma unroll
-    for (int p = 0; p < P; ++p) {
-        double s = 0.0;
+        for (int p = 0; p < P; ++p) {
+            double s = 0.0;
 #pragma unroll
-        for (int wv = 0; wv < DDL_BLOCK / 64; ++wv) s += lds[wv][p];
-        g[p] = s;
-    }
-    double c[MQ];
-    double R = 0.0;
-    {
-        int p = 0;
+            for (int wv = 0; wv < DDL_BLOCK / 64; ++wv) s += lds[wv][p];
+            g[p] = s;
+        }
+        double c[MQ];
+        double R = 0.0;
+        {
+            int p = 0;
+#pragma unroll
+            for (int j = 0; j < MQ; ++j) {
+                const double N = sqrt(g[p]);  // the diagonal entry G_jj
+                R += (double)a.w[j] * N;
+                c[j] = N > 0.0 ? (double)a.w[j] / N : 0.0;
+                p += MQ - j;
+            }
+        }
+        double q = 0.0, mass = 0.0;  // c' G c and the sum of the magnitudes of its terms
+        {
+            int p = 0;
+#pragma unroll
+            for (int j = 0; j < MQ; ++j)
+#pragma unroll
+                for (int k = j; k < MQ; ++k, ++p) {
+                    const double term = (j == k ? 1.0 : 2.0) * c[j] * c[k] * g[p];
+                    q += term;
+                    mass += fabs(term);
+                }
+        }
+        float* coef = reinterpret_cast<float*>(a.coef) + (size_t)r * MQ;
 #pragma unroll
         for (int j = 0; j < MQ; ++j) {
-            const double N = sqrt(g[p]);  // the diagonal entry G_jj
-            R += (double)a.w[j] * N;
-            c[j] = N > 0.0 ? (double)a.w[j] / N : 0.0;
-            p += MQ - j;
+            coef[j] = (float)c[j];
+            coef_lds[j] = (float)c[j];
         }
+        reinterpret_cast<float*>(a.mean_norm)[r] = (float)R;
+        float scale = 0.0f;                          // no direction at all: Delta = 0
+        if (mass > 0.0) scale = q >= kGramTrust * mass ? (float)(R / sqrt(q)) : -1.0f;
+        verdict[0] = scale;
+        verdict[1] = (float)R;
+        if (!(scale < 0.0f)) reinterpret_cast<float*>(a.scale)[r] = scale;
     }
-    double q = 0.0, mass = 0.0;  // c' G c and the sum of the magnitudes of its terms
-    {
-        int p = 0;
+    __syncthreads();
+    if (!(verdict[0] < 0.0f)) return;  // block-uniform
+
+    // The direct form for this group: ||sum_j c_j d_j||^2 summed from the data.
+    float c[MQ];
 #pragma unroll
-        for (int j = 0; j < MQ; ++j)
+    for (int j = 0; j < MQ; ++j) c[j] = coef_lds[j];
+    const uint64_t g0 = (uint64_t)r * a.group_len;
+    const uint64_t g1 = a.n - g0 < a.group_len ? a.n : g0 + a.group_len;
+    double uu = 0.0;  // per thread over the whole group: double keeps long groups exact enough
+    for (uint64_t begin = g0; begin < g1; begin += DDL_RDA_CHUNK) {
+        const uint64_t end = begin + DDL_RDA_CHUNK < g1 ? begin + DDL_RDA_CHUNK : g1;
+        float part = 0.0f;
+        sweep_chunk<L, MQ, false>(
+            a, begin, end, false,
+            [&](const float (&d)[4][MQ], const f32x4&, const f32x4&, uint32_t) {
 #pragma unroll
-            for (int k = j; k < MQ; ++k, ++p) {
-                const double term = (j == k ? 1.0 : 2.0) * c[j] * c[k] * g[p];
-                q += term;
-                mass += fabs(term);
-            }
+                for (int k = 0; k < 4; ++k) {
+                    const float u = direction<MQ>(d[k], c);
+                    part = fmaf(u, u, part);
+                }
+            },
+            [&](const float (&d)[MQ], float, float, uint32_t) {
+                const float u = direction<MQ>(d, c);
+                part = fmaf(u, u, part);
+            });
+        uu += (double)part;
     }
-    float* coef = reinterpret_cast<float*>(a.coef) + (size_t)r * MQ;
 #pragma unroll
-    for (int j = 0; j < MQ; ++j) coef[j] = (float)c[j];
-    reinterpret_cast<float*>(a.mean_norm)[r] = (float)R;
-    float scale = 0.0f;                              // no direction at all: Delta = 0
-    if (mass > 0.0) scale = q >= kGramTrust * mass ? (float)(R / sqrt(q)) : -1.0f;
-    reinterpret_cast<float*>(a.scale)[r] = scale;
+    for (int off = 32; off > 0; off >>= 1) uu += __shfl_xor(uu, off, 64);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6][0] = uu;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double U2 = 0.0;
+#pragma unroll
+        for (int wv = 0; wv < DDL_BLOCK / 64; ++wv) U2 += lds[wv][0];
+        const double U = sqrt(U2);
+        reinterpret_cast<float*>(a.scale)[r] = U > 0.0 ? (float)((double)verdict[1] / U) : 0.0f;
+    }
 }
 
 // One workgroup per group: norms from the chunk partials (in double, fixed order), then the
@@ -402,15 +460,6 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_norms_kernel(const DdlRdaArgs a
     if (threadIdx.x == 0) reinterpret_cast<float*>(a.mean_norm)[r] = (float)R;
 }
 
-template <int MQ>
-__device__ __forceinline__ float direction(const float (&d)[MQ], const float (&c)[MQ])
-{
-    float u = 0.0f;
-#pragma unroll
-    for (int j = 0; j < MQ; ++j) u = fmaf(c[j], d[j], u);
-    return u;
-}
-
 template <typename L, int MQ>
 __global__ void __launch_bounds__(DDL_BLOCK) rda_dirsq_kernel(const DdlRdaArgs a)
 {
@@ -418,8 +467,6 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_dirsq_kernel(const DdlRdaArgs a
     uint64_t begin, end;
     uint32_t group;
     chunk_range(a, blockIdx.x, begin, end, group);
-    // After the Gram reduce only groups whose scale is still open (< 0) need this sweep.
-    if (a.gram && !(reinterpret_cast<const float*>(a.scale)[group] < 0.0f)) return;
     float c[MQ];
 #pragma unroll
     for (int j = 0; j < MQ; ++j)
@@ -446,7 +493,6 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_scale_kernel(const DdlRdaArgs a
 {
     __shared__ double lds[DDL_BLOCK];
     const uint32_t r = blockIdx.x;
-    if (a.gram && !(reinterpret_cast<const float*>(a.scale)[r] < 0.0f)) return;
     const float* p2 = reinterpret_cast<const float*>(a.partial2) + (size_t)r * a.chunks_per_group;
     const double U = sqrt(block_sum_strided(p2, a.chunks_per_group, 1, lds));
     const double R = (double)reinterpret_cast<const float*>(a.mean_norm)[r];
@@ -916,7 +962,7 @@ void pick(int Mq, int cls, Kernels& k)
         k.group = rda_group_kernel<L, q>;        \
         if constexpr (q <= kGramMaxLearners) {   \
             k.gram = rda_gram_kernel<L, q>;      \
-            k.gram_reduce = rda_gram_reduce_kernel<q>; \
+            k.gram_reduce = rda_gram_reduce_kernel<L, q>; \
         }                                        \
         pick_row<L, q>(cls, k.row, k.rows, k.row_threads); \
         break;
@@ -1016,7 +1062,6 @@ ddl_status launch_one(ddl_dtype dt, int Mq, DdlRdaArgs& a, const Geometry& g, vo
         hipLaunchKernelGGL(k.group, dim3(groups), block, row_lds_cap(), stream, a);
     } else {
         const dim3 grid((uint32_t)g.chunks), rgrid(groups);
-        a.gram = k.gram ? 1u : 0u;
         if (k.gram) {
             DDL_COUNT_GRID();
             hipLaunchKernelGGL(k.gram, grid, block, 0, stream, a);
@@ -1027,11 +1072,11 @@ ddl_status launch_one(ddl_dtype dt, int Mq, DdlRdaArgs& a, const Geometry& g, vo
             hipLaunchKernelGGL(k.sumsq, grid, block, 0, stream, a);
             DDL_COUNT_GRID();
             hipLaunchKernelGGL(rda_norms_kernel, rgrid, block, 0, stream, a, Mq);
+            DDL_COUNT_GRID();
+            hipLaunchKernelGGL(k.dirsq, grid, block, 0, stream, a);
+            DDL_COUNT_GRID();
+            hipLaunchKernelGGL(rda_scale_kernel, rgrid, block, 0, stream, a);
         }
-        DDL_COUNT_GRID();
-        hipLaunchKernelGGL(k.dirsq, grid, block, 0, stream, a);
-        DDL_COUNT_GRID();
-        hipLaunchKernelGGL(rda_scale_kernel, rgrid, block, 0, stream, a);
         DDL_COUNT_GRID();
         hipLaunchKernelGGL(k.apply, grid, block, 0, stream, a);
     }
