@@ -175,10 +175,12 @@ DDL_API ddl_status ddl_merge_fragment_bcast(float* theta, float* v, void* theta_
  *   other arguments  as ddl_merge_fragment
  *
  * Allocates nothing.  Many groups of at most 16384 elements on 16-byte-aligned arrays (n and
- * group_len multiples of four) take one kernel that reads every byte once; other shapes make
- * three sweeps over the data (one kernel, or five for long or few groups: three sweeps and two
- * per-group reductions), i.e. up to three reads of the learners and of Theta, partly served
- * from the caches.  Results are reproducible (no atomics).
+ * group_len multiples of four) take one kernel that reads every byte once; many other moderate
+ * groups take one kernel that sweeps each group three times, the later sweeps served from the
+ * caches; long or few groups take three kernels that read the learners and Theta twice (a sweep
+ * for the Gram matrix of the outer gradients, a per-group reduction, the outer step) -- five
+ * kernels and three reads with more than eleven contributing learners.  Results are
+ * reproducible (no atomics).
  * Errors as ddl_merge_fragment, plus INVALID_ARG for group_len == 0 or a workspace that is
  * NULL, misaligned or too small, and ALIAS if the workspace overlaps any array of the call.
  */
@@ -199,8 +201,8 @@ DDL_API ddl_status ddl_rda_merge_fragment(float* theta, float* v, const void* co
  * its first call on a device looks the array's address up.
  *
  * A tensor and grouping that need more scratch than that -- ddl_rda_workspace_bytes(n,
- * group_len, M) above 4 MiB, which takes hundreds of millions of elements in one group or
- * hundreds of thousands of groups -- are refused with DDL_ERR_INVALID_ARG before anything is
+ * group_len, M) above 4 MiB, which takes about 10^8 elements in one group at sixteen learners
+ * (more with fewer) or about 10^5 groups -- are refused with DDL_ERR_INVALID_ARG before anything is
  * enqueued (ddl_last_error_message gives the sizes); use the workspace form for those.
  * All calls on one GPU share the one array and it keeps the last call's contents; nothing in
  * it has to start at zero (every kernel writes what it later reads).  Calls that may overlap
