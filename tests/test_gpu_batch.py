@@ -321,6 +321,69 @@ def test_tile_rotation_values(ddl, rot):
             ddl.set_option("tile_rotate", bad)
 
 
+@pytest.mark.parametrize("limit,tpb,rot", [(1, 1, 0), (7, 1, 2), (64, 1, 64), (100, 3, 0),
+                                           (128, 2, 0), (10, 1, 7), (5, 4, 3)])
+def test_split_launches(ddl, limit, tpb, rot):
+    """A sync of more tiles than max_tiles_per_launch goes out as several grids: every tile is
+    still visited exactly once, whatever the part size, tiles per workgroup and rotation group
+    (parts are whole workgroups and whole rotation groups; the last part may be ragged).
+    Direct averaging through batch and flat calls, the 4-bit merge and the RDA row kernels."""
+    old = [ddl.get_option(k) for k in ("max_tiles_per_launch", "tiles_per_block", "tile_rotate")]
+    try:
+        ddl.set_option("max_tiles_per_launch", limit)
+        ddl.set_option("tiles_per_block", tpb)
+        ddl.set_option("tile_rotate", rot)
+        for name in ("dense_block", "moe", "streaming_model"):
+            wl = ddl_synth.reduced(name)
+            data, refs = _materialise(wl)
+            g0 = ddl.get_option("grids_enqueued")
+            ddl.merge_batch([_fragment(ddl, f, segs) for f, segs in zip(wl.fragments, data)])
+            torch.cuda.synchronize()
+            if len(wl.fragments) == 1:          # 178 and 579 tiles: more than one part
+                assert ddl.get_option("grids_enqueued") - g0 > 1
+            _check_all(wl, data, refs)
+        n = 37 * 1024 + 5
+        th, v, ls, tok, mask = random_problem(limit * 7 + tpb, n, 3, torch.bfloat16, DEV)
+        ref = oracle.merge_fragment(ddl_synth.to_host_array(th), ddl_synth.to_host_array(v),
+                                    [ddl_synth.to_host_array(x) for x in ls], tok, mask, 0.7, 0.9)
+        ddl.merge_fragment(th, v, ls, tok, mask, 0.7, 0.9)
+        enc = [ddl.q4_encode(th, x, 24) for x in ls]              # of the state after the merge
+        torch.cuda.synchronize()
+        check_segment(ddl_synth.SegmentData(th, v, ls), ref, f"flat, parts of {limit}")
+        ref4 = oracle.q4_merge_fragment(
+            ddl_synth.to_host_array(th), ddl_synth.to_host_array(v),
+            [c.cpu().numpy() for c, _ in enc], [ddl_synth.to_host_array(s) for _, s in enc],
+            tok, mask, 24, 0.7, 0.9)
+        ddl.q4_merge_fragment(th, v, [c for c, _ in enc], [s for _, s in enc], tok, mask, 24,
+                              0.7, 0.9)
+        torch.cuda.synchronize()
+        check_segment(ddl_synth.SegmentData(th, v, ls), ref4, f"q4, parts of {limit}")
+        # RDA row kernels through the plan: 600 rows of 2048 in parts
+        rows, g = 600, 2048
+        th, v, ls, tok, mask = random_problem(limit + 99, rows * g, 3, torch.bfloat16, DEV)
+        pick = [0, 1, 299, 598, 599]
+        refs_r = [oracle.rda_merge_fragment(
+            ddl_synth.to_host_array(th[r * g:(r + 1) * g]), ddl_synth.to_host_array(v[r * g:(r + 1) * g]),
+            [ddl_synth.to_host_array(x[r * g:(r + 1) * g]) for x in ls], tok, mask, g, 0.7, 0.9)
+            for r in pick]
+        before = th.clone()
+        plan = ddl.Plan([ddl.Fragment([(th, v, ls)], M=3, learner_dtype=torch.bfloat16)])
+        plan.set_rda_groups([g])
+        ws = torch.empty(max(256, plan.rda_workspace_bytes), dtype=torch.uint8, device=DEV)
+        plan.rda_merge([(0, tok, mask, 0.7, 0.9)], ws)
+        torch.cuda.synchronize()
+        for r, ref_r in zip(pick, refs_r):
+            check_segment(ddl_synth.SegmentData(th[r * g:(r + 1) * g], v[r * g:(r + 1) * g], ls),
+                          ref_r, f"rda row {r}, parts of {limit}")
+        assert bool(((th != before).view(rows, g).any(dim=1)).all()), "a row was skipped"
+        plan.destroy()
+    finally:
+        for k, x in zip(("max_tiles_per_launch", "tiles_per_block", "tile_rotate"), old):
+            ddl.set_option(k, x)
+    with pytest.raises(ddl.DdlError):
+        ddl.set_option("max_tiles_per_launch", -2)
+
+
 def _random_workload(seed):
     """A seeded workload of random structure: 1-12 fragments of 0-30 tensors each, sizes from
     empty over tile edges to a few hundred thousand elements, random M, quorum, dtype, lr, mu."""
