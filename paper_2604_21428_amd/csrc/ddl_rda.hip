@@ -52,7 +52,13 @@
 #ifndef DDL_RDA_V_EARLY
 #define DDL_RDA_V_EARLY 0  // 1: the row kernels load v with the first sweep instead of the last
 #endif
+#ifndef DDL_RDA_GRAM_LOAD
+#define DDL_RDA_GRAM_LOAD 0  // load form of the Gram sweep (see ld<>): 0 cached, so that the apply
+                             // sweep of a tensor that fits the last-level cache finds it there
+#endif
+#ifndef DDL_RDA_CHUNK
 #define DDL_RDA_CHUNK 8192  // elements per workgroup and sweep: 8 groups of four per lane
+#endif
 
 struct DdlRdaArgs {
     uint64_t theta, v;          // device addresses
@@ -155,7 +161,7 @@ __device__ __forceinline__ u32x2 pack_bf16(const float (&t4)[4])
 
 // Walks the chunk: F(d[MQ], theta, v, element index within the chunk, is the first argument
 // pack a vector of 4).  VEC path: groups of four per lane; else element-wise.
-template <typename L, int MQ, bool NT, typename F4, typename F1>
+template <typename L, int MQ, int NT, typename F4, typename F1>
 __device__ __forceinline__ void sweep_chunk(const DdlRdaArgs& a, uint64_t begin, uint64_t end,
                                             bool need_v, F4&& f4, F1&& f1)
 {
@@ -283,14 +289,14 @@ struct WaveScatterSum {
 
 // Sweep 1 of the Gram form: per chunk, the sums of d_j d_k for j <= k, row-major upper triangle.
 template <typename L, int MQ>
-__global__ void __launch_bounds__(DDL_BLOCK) rda_gram_kernel(const DdlRdaArgs a)
+__device__ __forceinline__ void gram_body(const DdlRdaArgs& a, uint32_t chunk)
 {
     constexpr int P = gram_size(MQ);
     typedef WaveScatterSum<P> Sum;
     __shared__ float lds[DDL_BLOCK / 64][P];
     uint64_t begin, end;
     uint32_t group;
-    chunk_range(a, blockIdx.x, begin, end, group);
+    chunk_range(a, chunk, begin, end, group);
     float acc[P];
 #pragma unroll
     for (int p = 0; p < P; ++p) acc[p] = 0.0f;
@@ -301,7 +307,7 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_gram_kernel(const DdlRdaArgs a)
 #pragma unroll
             for (int k = j; k < MQ; ++k, ++p) acc[p] = fmaf(d[j], d[k], acc[p]);
     };
-    sweep_chunk<L, MQ, false>(
+    sweep_chunk<L, MQ, DDL_RDA_GRAM_LOAD>(
         a, begin, end, false,
         [&](const float (&d)[4][MQ], const f32x4&, const f32x4&, uint32_t) {
 #pragma unroll
@@ -314,13 +320,19 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_gram_kernel(const DdlRdaArgs a)
     for (int i = 0; i < Sum::slots; ++i)
         if (index[i] < P) lds[threadIdx.x >> 6][index[i]] = acc[i];
     __syncthreads();
-    float* out = reinterpret_cast<float*>(a.partial1) + (size_t)blockIdx.x * P;
+    float* out = reinterpret_cast<float*>(a.partial1) + (size_t)chunk * P;
     for (int p = threadIdx.x; p < P; p += DDL_BLOCK) {
         float s = 0.0f;
 #pragma unroll
         for (int wv = 0; wv < DDL_BLOCK / 64; ++wv) s += lds[wv][p];  // waves in a fixed order
         out[p] = s;
     }
+}
+
+template <typename L, int MQ>
+__global__ void __launch_bounds__(DDL_BLOCK) rda_gram_kernel(const DdlRdaArgs a)
+{
+    gram_body<L, MQ>(a, blockIdx.x);
 }
 
 // One workgroup per group: the Gram matrix from the chunk partials (each thread sums its own
@@ -331,13 +343,12 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_gram_kernel(const DdlRdaArgs a)
 // workgroup for the whole group, but it concerns only such groups and keeps the common case
 // at three launches (Gram sweep, this kernel, apply).
 template <typename L, int MQ>
-__global__ void __launch_bounds__(DDL_BLOCK) rda_gram_reduce_kernel(const DdlRdaArgs a)
+__device__ __forceinline__ void gram_reduce_body(const DdlRdaArgs& a, uint32_t r)
 {
     constexpr int P = gram_size(MQ);
     __shared__ double lds[DDL_BLOCK / 64][P];
     __shared__ float coef_lds[MQ];
     __shared__ float verdict[2];  // scale (< 0: not trusted), R
-    const uint32_t r = blockIdx.x;
     const float* p1 = reinterpret_cast<const float*>(a.partial1) + (size_t)r * a.chunks_per_group * P;
     double g[P];
 #pragma unroll
@@ -441,6 +452,12 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_gram_reduce_kernel(const DdlRda
     }
 }
 
+template <typename L, int MQ>
+__global__ void __launch_bounds__(DDL_BLOCK) rda_gram_reduce_kernel(const DdlRdaArgs a)
+{
+    gram_reduce_body<L, MQ>(a, blockIdx.x);
+}
+
 // One workgroup per group: norms from the chunk partials (in double, fixed order), then the
 // direction coefficients w_j / N_j and the mean norm.
 __global__ void __launch_bounds__(DDL_BLOCK) rda_norms_kernel(const DdlRdaArgs a, int Mq)
@@ -500,11 +517,11 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_scale_kernel(const DdlRdaArgs a
 }
 
 template <typename L, int MQ>
-__global__ void __launch_bounds__(DDL_BLOCK) rda_apply_kernel(const DdlRdaArgs a)
+__device__ __forceinline__ void apply_body(const DdlRdaArgs& a, uint32_t chunk)
 {
     uint64_t begin, end;
     uint32_t group;
-    chunk_range(a, blockIdx.x, begin, end, group);
+    chunk_range(a, chunk, begin, end, group);
     float c[MQ];
     const float scale = reinterpret_cast<const float*>(a.scale)[group];
 #pragma unroll
@@ -513,7 +530,7 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_apply_kernel(const DdlRdaArgs a
     const float lr = a.lr, mu = a.mu;
     const uint64_t th = a.theta + begin * 4, vv = a.v + begin * 4;
     const uint64_t tb = a.theta_bf16 ? a.theta_bf16 + begin * 2 : 0;
-    sweep_chunk<L, MQ, true>(
+    sweep_chunk<L, MQ, DDL_NT_LOAD>(
         a, begin, end, true,
         [&](const float (&d)[4][MQ], const f32x4& T, const f32x4& V, uint32_t g) {
             float t4[4] = {T.x, T.y, T.z, T.w};
@@ -538,6 +555,109 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_apply_kernel(const DdlRdaArgs a
             *(reinterpret_cast<DDL_GLOBAL float*>(vv) + e) = v_new;
             if (tb) *(reinterpret_cast<DDL_GLOBAL uint16_t*>(tb) + e) = (uint16_t)bf16_rne(t_new);
         });
+}
+
+template <typename L, int MQ>
+__global__ void __launch_bounds__(DDL_BLOCK) rda_apply_kernel(const DdlRdaArgs a)
+{
+    apply_body<L, MQ>(a, blockIdx.x);
+}
+
+// The long-group path for ALL such tensors of a fragment at once (through a plan): the three
+// kernels above with the tensor looked up per workgroup.  What is fixed per tensor sits in a
+// device table made when the groups are set (DdlRdaLongRef: descriptor, chunk and group
+// numbering within the fragment's launches, where its partial sums live in the workspace);
+// what changes per sync travels in the kernel arguments.
+struct DdlRdaLongRef {
+    uint32_t seg;               // descriptor index in the plan's table
+    uint32_t chunk_begin;       // first chunk of this tensor within the sweep launches
+    uint32_t group_begin;       // first group of this tensor within the reduce launch
+    uint32_t chunks_per_group;
+    uint64_t group_len;         // clamped to n
+    uint64_t off_partial1, off_coef, off_mean, off_scale;  // bytes into the workspace
+    uint32_t vec_all;           // every base 16-byte aligned and group_len a multiple of four
+    uint32_t pad;
+};
+
+struct DdlRdaLongArgs {
+    const DdlSegDesc* segs;
+    const DdlRdaLongRef* refs;  // the fragment's entries
+    uint32_t num_refs;
+    uint32_t by_group;          // 0: workgroups count chunks, 1: groups
+    uint32_t base;              // number of this grid's first workgroup (long sweeps go in parts)
+    uint32_t pad;
+    uint64_t workspace;
+    float lr, mu;
+    float w[DDL_MAXL];          // normalised weights of the contributing learners, compacted
+    uint8_t idx[DDL_MAXL];      // learner index of compacted entry j
+};
+
+// The tensor that holds chunk (or group) b of the launch, as the arguments the one-tensor
+// bodies take; `local` is b's number within that tensor.
+template <typename L, int MQ>
+__device__ __forceinline__ void long_locate(const DdlRdaLongArgs& m, uint32_t b, DdlRdaArgs& a,
+                                            uint32_t& local)
+{
+    typedef typename L::elem elem;
+    const DDL_CONST DdlRdaLongRef* refs =
+        reinterpret_cast<const DDL_CONST DdlRdaLongRef*>(reinterpret_cast<uint64_t>(m.refs));
+    uint32_t lo = 0, hi = m.num_refs - 1;  // last entry whose begin <= b
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi + 1) >> 1;
+        const uint32_t begin = m.by_group ? refs[mid].group_begin : refs[mid].chunk_begin;
+        if (begin <= b) lo = mid; else hi = mid - 1;
+    }
+    const DDL_CONST DdlRdaLongRef* ref = refs + lo;
+    const DDL_CONST DdlSegDesc* sp =
+        reinterpret_cast<const DDL_CONST DdlSegDesc*>(reinterpret_cast<uint64_t>(m.segs)) + ref->seg;
+    local = b - (m.by_group ? ref->group_begin : ref->chunk_begin);
+    a.theta = uniform(reinterpret_cast<uint64_t>(sp->theta));
+    a.v = uniform(reinterpret_cast<uint64_t>(sp->v));
+    a.theta_bf16 = uniform(reinterpret_cast<uint64_t>(sp->theta_bf16));
+#pragma unroll
+    for (int j = 0; j < MQ; ++j) {
+        a.learner[j] = uniform(reinterpret_cast<uint64_t>(sp->learner[m.idx[j]]));
+        a.w[j] = m.w[j];
+    }
+    a.n = sp->n;
+    a.group_len = ref->group_len;
+    a.chunks_per_group = ref->chunks_per_group;
+    a.vec_ok = ref->vec_all;
+    a.lr = m.lr;
+    a.mu = m.mu;
+    a.partial1 = m.workspace + ref->off_partial1;
+    a.coef = m.workspace + ref->off_coef;
+    a.mean_norm = m.workspace + ref->off_mean;
+    a.partial2 = 0;
+    a.scale = m.workspace + ref->off_scale;
+    (void)sizeof(elem);
+}
+
+template <typename L, int MQ>
+__global__ void __launch_bounds__(DDL_BLOCK) rda_long_gram_kernel(const DdlRdaLongArgs m)
+{
+    DdlRdaArgs a;
+    uint32_t chunk;
+    long_locate<L, MQ>(m, m.base + blockIdx.x, a, chunk);
+    gram_body<L, MQ>(a, chunk);
+}
+
+template <typename L, int MQ>
+__global__ void __launch_bounds__(DDL_BLOCK) rda_long_reduce_kernel(const DdlRdaLongArgs m)
+{
+    DdlRdaArgs a;
+    uint32_t group;
+    long_locate<L, MQ>(m, m.base + blockIdx.x, a, group);
+    gram_reduce_body<L, MQ>(a, group);
+}
+
+template <typename L, int MQ>
+__global__ void __launch_bounds__(DDL_BLOCK) rda_long_apply_kernel(const DdlRdaLongArgs m)
+{
+    DdlRdaArgs a;
+    uint32_t chunk;
+    long_locate<L, MQ>(m, m.base + blockIdx.x, a, chunk);
+    apply_body<L, MQ>(a, chunk);
 }
 
 // Launch shape (a): one workgroup makes all three sweeps over its own group.
@@ -880,6 +1000,7 @@ constexpr bool row_kernel_fits()
 
 typedef void (*rda_fn)(const DdlRdaArgs);
 typedef void (*rda_rows_fn)(const DdlRdaRowsArgs);
+typedef void (*rda_long_fn)(const DdlRdaLongArgs);
 
 // The register-resident shapes, smallest first: X(class, K groups of four per lane, workgroup
 // size, K and workgroup size of the second choice); a class holds groups of up to
@@ -946,6 +1067,7 @@ void pick_row(int cls, rda_fn& one, rda_rows_fn& many, uint32_t& threads)
 struct Kernels {
     rda_fn sumsq = nullptr, dirsq = nullptr, apply = nullptr, group = nullptr, row = nullptr;
     rda_fn gram = nullptr, gram_reduce = nullptr;  // null beyond kGramMaxLearners
+    rda_long_fn long_gram = nullptr, long_reduce = nullptr, long_apply = nullptr;  // likewise
     rda_rows_fn rows = nullptr;
     uint32_t row_threads = 0;  // workgroup size of row / rows
 };
@@ -963,6 +1085,9 @@ void pick(int Mq, int cls, Kernels& k)
         if constexpr (q <= kGramMaxLearners) {   \
             k.gram = rda_gram_kernel<L, q>;      \
             k.gram_reduce = rda_gram_reduce_kernel<L, q>; \
+            k.long_gram = rda_long_gram_kernel<L, q>;     \
+            k.long_reduce = rda_long_reduce_kernel<L, q>; \
+            k.long_apply = rda_long_apply_kernel<L, q>;   \
         }                                        \
         pick_row<L, q>(cls, k.row, k.rows, k.row_threads); \
         break;
@@ -1095,12 +1220,16 @@ extern "C" size_t ddl_rda_workspace_bytes(size_t n, size_t group_len, int M)
 
 namespace {
 
-// Shared by the two one-tensor entry points.  workspace: caller's or the library's scratch.
+ddl_status static_scratch(void** out);  // device address of the library's own scratch array
+
+// Shared by the two one-tensor entry points.  workspace: the caller's scratch, or NULL for the
+// library's own array of workspace_bytes bytes, whose address is looked up only once the
+// arguments have been found good (argument errors need no device).
 ddl_status rda_merge_one(float* theta, float* v, const void* const* learner_params,
                          ddl_dtype learner_dtype, const uint64_t* token_counts,
                          const uint8_t* quorum_mask, int M, size_t n, size_t group_len, float lr,
-                         float mu, void* workspace, size_t workspace_bytes, const char* who,
-                         void* hip_stream)
+                         float mu, void* workspace, size_t workspace_bytes, bool library_scratch,
+                         const char* who, void* hip_stream)
 {
     double w[DDL_MAX_LEARNERS];
     ddl_status st = ddl_compute_weights(token_counts, quorum_mask, M, w);
@@ -1143,12 +1272,16 @@ ddl_status rda_merge_one(float* theta, float* v, const void* const* learner_para
     }
     Geometry g;
     if (!geometry(n, group_len, Mq, g)) return DDL_ERR_INVALID_ARG;
-    if (!workspace || !aligned(workspace, 256)) return DDL_ERR_INVALID_ARG;
+    if (!library_scratch && (!workspace || !aligned(workspace, 256))) return DDL_ERR_INVALID_ARG;
     if (workspace_bytes < g.bytes) {
         ddlh::set_error_message((std::string(who) + ": this tensor and grouping need " +
                                  std::to_string(g.bytes) + " bytes of scratch, " +
                                  std::to_string(workspace_bytes) + " are there").c_str());
         return DDL_ERR_INVALID_ARG;
+    }
+    if (library_scratch) {
+        const ddl_status ws = static_scratch(&workspace);
+        if (ws != DDL_OK) return ws;
     }
     r[nr++] = {(uintptr_t)workspace, (uintptr_t)workspace + g.bytes, true};
     std::sort(r, r + nr, [](const Range& x, const Range& y) { return x.lo < y.lo; });
@@ -1180,8 +1313,8 @@ extern "C" ddl_status ddl_rda_merge_fragment(float* theta, float* v,
                                              size_t workspace_bytes, void* hip_stream)
 {
     return rda_merge_one(theta, v, learner_params, learner_dtype, token_counts, quorum_mask, M, n,
-                         group_len, lr, mu, workspace, workspace_bytes, "ddl_rda_merge_fragment",
-                         hip_stream);
+                         group_len, lr, mu, workspace, workspace_bytes, false,
+                         "ddl_rda_merge_fragment", hip_stream);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1236,13 +1369,10 @@ extern "C" ddl_status ddl_rda_merge_fragment_static(float* theta, float* v,
                                                     size_t group_len, float lr, float mu,
                                                     void* hip_stream)
 {
-    void* ws = nullptr;
-    const ddl_status st = static_scratch(&ws);
-    if (st != DDL_OK) return st;
     // Every kernel of the merge writes the part of the scratch it later reads (chunk sums,
     // coefficients, scales), so nothing has to be cleared between calls.
     return rda_merge_one(theta, v, learner_params, learner_dtype, token_counts, quorum_mask, M, n,
-                         group_len, lr, mu, ws, DDL_RDA_STATIC_SCRATCH_BYTES,
+                         group_len, lr, mu, nullptr, DDL_RDA_STATIC_SCRATCH_BYTES, true,
                          "ddl_rda_merge_fragment_static", hip_stream);
 }
 
@@ -1259,12 +1389,17 @@ struct DdlRdaPlan {
         Class cls[kNumRowClasses];
         std::vector<uint32_t> other;   // descriptors that always take the one-tensor path
         std::vector<uint32_t> direct;  // descriptors merged by direct averaging instead
+        // tensors of long or few groups: all of them in three launches (table entries
+        // [long_begin, long_begin + long_count) of long_refs)
+        uint32_t long_begin = 0, long_count = 0, long_chunks = 0, long_groups = 0;
     };
     std::vector<uint64_t> group_len;  // per descriptor, clamped to its n
     std::vector<Frag> frags;
     std::vector<DdlRdaRowRef> refs;
     std::vector<uint32_t> coarse;
-    void* d_image = nullptr;  // refs followed by the coarse index
+    std::vector<DdlRdaLongRef> long_refs;
+    void* d_image = nullptr;  // refs, then the coarse index, then long_refs (8-byte aligned)
+    size_t long_offset = 0;   // of long_refs within the image
     size_t workspace_bytes = 0;
 };
 
@@ -1307,6 +1442,7 @@ extern "C" ddl_status ddl_plan_set_rda_groups(ddl_plan* plan, const size_t* grou
         const ddlh::FragInfo& fi = T.frags[f];
         DdlRdaPlan::Frag& rf = R->frags[f];
         std::vector<uint32_t> members[kNumRowClasses];
+        uint64_t long_bytes = 0;  // workspace of the fragment's long-group tensors, side by side
         for (uint32_t d = fi.seg_begin; d < fi.seg_begin + fi.num_segs; ++d) {
             const DdlSegDesc& sd = T.segs[d];
             uint64_t g = group_len[T.origin[d]];
@@ -1323,11 +1459,44 @@ extern "C" ddl_status ddl_plan_set_rda_groups(ddl_plan* plan, const size_t* grou
                 return DDL_ERR_INVALID_ARG;
             }
             R->workspace_bytes = std::max(R->workspace_bytes, geo.bytes);
-            if (row_eligible(sd, fi.M, g))
+            if (row_eligible(sd, fi.M, g)) {
                 members[row_class_for(g)].push_back(d);
-            else
-                rf.other.push_back(d);
+            } else if (g <= kGroupKernelMaxLen && geo.groups >= kGroupKernelMinGroups) {
+                rf.other.push_back(d);  // many moderate groups: the one-workgroup-per-group kernel
+            } else {
+                // long or few groups: one entry of the fragment's three launches
+                if (rf.long_count == 0) rf.long_begin = (uint32_t)R->long_refs.size();
+                DdlRdaLongRef ref;
+                std::memset(&ref, 0, sizeof ref);
+                ref.seg = d;
+                ref.chunk_begin = rf.long_chunks;
+                ref.group_begin = rf.long_groups;
+                ref.chunks_per_group = (uint32_t)geo.chunks_per_group;
+                ref.group_len = g;
+                const uint32_t all = (1u << fi.M) - 1u;
+                ref.vec_all = sd.base_aligned && g % 4 == 0 &&
+                              (all & ~(uint32_t)sd.learner_aligned) == 0;
+                auto take = [&](uint64_t floats) {
+                    const uint64_t at = long_bytes;
+                    long_bytes += (floats * 4 + 255) & ~(uint64_t)255;
+                    return at;
+                };
+                ref.off_partial1 = take(geo.chunks * (uint64_t)partial_width(fi.M));
+                ref.off_coef = take(geo.groups * (uint64_t)fi.M);
+                ref.off_mean = take(geo.groups);
+                ref.off_scale = take(geo.groups);
+                if ((uint64_t)rf.long_chunks + geo.chunks > 0x7fffffffull ||
+                    (uint64_t)rf.long_groups + geo.groups > 0x7fffffffull) {
+                    delete R;
+                    return DDL_ERR_INVALID_ARG;
+                }
+                rf.long_chunks += (uint32_t)geo.chunks;
+                rf.long_groups += (uint32_t)geo.groups;
+                ++rf.long_count;
+                R->long_refs.push_back(ref);
+            }
         }
+        R->workspace_bytes = std::max<size_t>(R->workspace_bytes, (size_t)long_bytes);
         for (int c = 0; c < kNumRowClasses; ++c) {
             DdlRdaPlan::Class& k = rf.cls[c];
             k.ref_begin = (uint32_t)R->refs.size();
@@ -1363,11 +1532,15 @@ extern "C" ddl_status ddl_plan_set_rda_groups(ddl_plan* plan, const size_t* grou
         }
     }
     const size_t ref_bytes = R->refs.size() * sizeof(DdlRdaRowRef);
-    const size_t bytes = ref_bytes + R->coarse.size() * sizeof(uint32_t);
+    const size_t coarse_bytes = R->coarse.size() * sizeof(uint32_t);
+    R->long_offset = (ref_bytes + coarse_bytes + 7) & ~(size_t)7;
+    const size_t bytes = R->long_offset + R->long_refs.size() * sizeof(DdlRdaLongRef);
     if (bytes > 0) {
         std::vector<char> image(bytes);
         std::memcpy(image.data(), R->refs.data(), ref_bytes);
-        std::memcpy(image.data() + ref_bytes, R->coarse.data(), bytes - ref_bytes);
+        std::memcpy(image.data() + ref_bytes, R->coarse.data(), coarse_bytes);
+        std::memcpy(image.data() + R->long_offset, R->long_refs.data(),
+                    R->long_refs.size() * sizeof(DdlRdaLongRef));
         hipError_t e = hipMalloc(&R->d_image, bytes);
         if (e == hipSuccess) e = hipMemcpy(R->d_image, image.data(), bytes, hipMemcpyHostToDevice);
         if (e != hipSuccess) {
@@ -1513,6 +1686,57 @@ extern "C" ddl_status ddl_plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, 
         for (uint32_t d : rf.other) {
             const ddl_status st = one_tensor(f, wk, d);
             if (st != DDL_OK) return st;
+        }
+        if (rf.long_count > 0) {
+            Kernels fn;
+            pick(f.dt, wk.q.Mq, kNumRowClasses, fn);
+            if (fn.long_gram) {  // all these tensors in three launches
+                DdlRdaLongArgs a;
+                std::memset(&a, 0, sizeof a);
+                a.segs = d_segs;
+                a.refs = reinterpret_cast<const DdlRdaLongRef*>(
+                             static_cast<const char*>(R.d_image) + R.long_offset) + rf.long_begin;
+                a.num_refs = rf.long_count;
+                a.workspace = (uint64_t)(uintptr_t)workspace;
+                a.lr = wk.lr;
+                a.mu = wk.mu;
+                std::memcpy(a.w, wk.q.w, sizeof a.w);
+                std::memcpy(a.idx, wk.q.idx, sizeof a.idx);
+                const dim3 block(DDL_BLOCK);
+                // the two sweeps go out in equal parts like the merge (a chunk is 8 tiles)
+                const uint64_t max_tiles =
+                    ddlh::max_tiles_per_launch(f.dt == DDL_BF16 ? 2 : 4, wk.q.Mq);
+                uint64_t part = rf.long_chunks;
+                const uint64_t max_chunks = max_tiles / (DDL_RDA_CHUNK / DDL_TILE);
+                if (max_tiles != 0 && max_chunks > 0 && rf.long_chunks > max_chunks) {
+                    const uint64_t parts = (rf.long_chunks + max_chunks - 1) / max_chunks;
+                    part = (rf.long_chunks + parts - 1) / parts;
+                }
+                auto sweep = [&](rda_long_fn kernel) {
+                    for (uint64_t base = 0; base < rf.long_chunks; base += part) {
+                        a.base = (uint32_t)base;
+                        DDL_COUNT_GRID();
+                        hipLaunchKernelGGL(
+                            kernel, dim3((uint32_t)std::min<uint64_t>(part, rf.long_chunks - base)),
+                            block, 0, stream, a);
+                    }
+                };
+                a.by_group = 0;
+                sweep(fn.long_gram);
+                a.by_group = 1;
+                a.base = 0;
+                DDL_COUNT_GRID();
+                hipLaunchKernelGGL(fn.long_reduce, dim3(rf.long_groups), block, 0, stream, a);
+                a.by_group = 0;
+                sweep(fn.long_apply);
+                const hipError_t e = hipGetLastError();
+                if (e != hipSuccess) return ddlh::runtime_error(e, "RDA long-group kernel launch");
+            } else {  // more learners than the Gram form takes: tensor by tensor
+                for (uint32_t r = 0; r < rf.long_count; ++r) {
+                    const ddl_status st = one_tensor(f, wk, R.long_refs[rf.long_begin + r].seg);
+                    if (st != DDL_OK) return st;
+                }
+            }
         }
         for (uint32_t d : rf.direct) {
             const ddl_status st =

@@ -79,6 +79,20 @@ def main():
         rng = int(tile[recent].max() - tile[recent].min()) if recent.any() else 0
         print(f"  {frac:4.0%}   {min(cnt):7d} .. {max(cnt):7d}   spread {max(cnt) - min(cnt):5d}"
               f"            {int(recent.sum()):5d} tiles over an index range of {rng}")
+    # How unevenly the XCDs reach the end of each grid: per grid, when each XCD started its last
+    # workgroup; the gap between the first and the last XCD to get there is time the early ones
+    # spend idle before the next grid may start.
+    unit = 64                                       # parts are whole rotation groups
+    part = -(-(-(-tiles // grids)) // unit) * unit if grids > 1 else tiles
+    gaps = []
+    for g in range(grids):
+        sel = (tile >= g * part) & (tile < (g + 1) * part)
+        last = [int(clk[sel & (xcd == x)].max()) for x in range(8) if (sel & (xcd == x)).any()]
+        if len(last) == 8:
+            gaps.append((max(last) - min(last)) / 100.0)
+    if gaps:
+        print(f"  last workgroup start per XCD, first to last XCD: mean {sum(gaps) / len(gaps):.1f} us, "
+              f"max {max(gaps):.1f} us per grid ({len(gaps)} grids of about {span / 100 / grids:.0f} us)")
     plan.destroy()
 
 

@@ -162,7 +162,25 @@ def test_argument_errors_of_the_other_entry_points_need_no_device(ddl):
     assert lib.ddl_rda_workspace_bytes(n, 64, 17) == 0
     assert lib.ddl_rda_workspace_bytes(n, 64, 2) > 0
 
+    # the form on the library's own scratch: argument errors and the size refusal need no device
+    def rda_static(mask=ones, g=64, theta=th, count=n, lr=0.7):
+        return lib.ddl_rda_merge_fragment_static(theta, v, table, ddl.DDL_BF16, tok, mask, M,
+                                                 count, g, lr, 0.9, None)
+
+    assert lib.ddl_rda_static_scratch_bytes() == 4 << 20
+    assert rda_static(mask=zeros) == ddl.DDL_ERR_EMPTY_QUORUM
+    assert rda_static(g=0) == ddl.DDL_ERR_INVALID_ARG
+    assert rda_static(lr=float("inf")) == ddl.DDL_ERR_INVALID_ARG
+    assert rda_static(theta=None) == ddl.DDL_ERR_INVALID_ARG
+    assert rda_static(count=0) == ddl.DDL_OK
+    big = 1 << 24                                   # 16 M groups of one element: far above 4 MiB
+    assert lib.ddl_rda_workspace_bytes(big, 1, M) > lib.ddl_rda_static_scratch_bytes()
+    assert rda_static(count=big, g=1) == ddl.DDL_ERR_INVALID_ARG
+    assert b"bytes of scratch" in lib.ddl_last_error_message()
+
     assert lib.ddl_plan_rda_workspace_bytes(None) == 0
+    assert lib.ddl_plan_set_q4_sources(None, None, 0, 128) == ddl.DDL_ERR_INVALID_ARG
+    assert lib.ddl_plan_q4_merge(None, None, 0, None) == ddl.DDL_ERR_INVALID_ARG
     assert lib.ddl_plan_set_rda_groups(None, None, 0) == ddl.DDL_ERR_INVALID_ARG
     assert lib.ddl_plan_rda_merge(None, None, 0, None, 0, None) == ddl.DDL_ERR_INVALID_ARG
 
@@ -234,6 +252,21 @@ int main(void) {
     r = subprocess.run([str(exe)], capture_output=True, text=True)
     assert r.returncode == 0, (r.returncode, r.stderr)
     assert r.stdout.strip() == "01101 empty quorum"   # 7|5, 5+4, 7+3, 9+3
+
+
+def test_build_ids(ddl):
+    """The library names the sources it was built from, as a whole and per kernel family; the
+    build script computes the same strings from the source tree."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location(
+        "ddl_build", os.path.join(os.path.dirname(ddl.__file__), "build.py"))
+    b = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(b)
+    assert ddl.build_id() == b.source_id() and len(ddl.build_id()) == 12
+    for k in ("merge", "rda", "q4"):
+        assert ddl.kernel_build_id(k) == b.source_id(k)
+    assert ddl.kernel_build_id("no such kernel") == ""
+    assert len({ddl.kernel_build_id(k) for k in ("merge", "rda", "q4")}) == 3
 
 
 def test_options(ddl):
