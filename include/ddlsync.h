@@ -155,6 +155,24 @@ DDL_API ddl_status ddl_merge_fragment_bcast(float* theta, float* v, void* theta_
                                             float mu, void* hip_stream);
 
 /*
+ * As ddl_merge_fragment, and the same pass also writes the merged outer gradient it applied,
+ *
+ *     Delta_i = sum_m w_m (Theta_i - theta_{m,i})        (Appendix D.2, weighted direct averaging)
+ *
+ * into delta_out (device, n fp32 elements; it may overlap no other array of the call): for
+ * inspecting the outer gradient -- its norm, its cosine to a learner's, a caller's own outer
+ * optimiser run beside the fused one -- without another sweep over the learners' copies.
+ * Theta and v come out bit for bit as from ddl_merge_fragment.  delta_out == NULL makes the
+ * call ddl_merge_fragment itself.  Costs 4 more bytes of HBM traffic per parameter; no device
+ * allocation, no copy.
+ */
+DDL_API ddl_status ddl_merge_fragment_ex(float* theta, float* v, float* delta_out,
+                                         const void* const* learner_params,
+                                         ddl_dtype learner_dtype, const uint64_t* token_counts,
+                                         const uint8_t* quorum_mask, int M, size_t n, float lr,
+                                         float mu, void* hip_stream);
+
+/*
  * Radial-directional averaging (Appendix D.2, "Radial-directional averaging", weighted form)
  * as the merge, fused with the same outer Nesterov step, for one flat tensor.  With
  * d_m = Theta - theta_m over a group of elements and normalised weights w_m,

@@ -80,6 +80,9 @@ def _load() -> ctypes.CDLL:
     lib.ddl_merge_fragment_bcast.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, vpp,
                                              ctypes.c_int, u64p, u8p, ctypes.c_int, ctypes.c_size_t,
                                              ctypes.c_float, ctypes.c_float, ctypes.c_void_p]
+    lib.ddl_merge_fragment_ex.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, vpp,
+                                          ctypes.c_int, u64p, u8p, ctypes.c_int, ctypes.c_size_t,
+                                          ctypes.c_float, ctypes.c_float, ctypes.c_void_p]
     lib.ddl_merge_fragment_weighted.argtypes = [ctypes.c_void_p, ctypes.c_void_p, vpp,
                                                 ctypes.c_int, f64p, ctypes.c_int, ctypes.c_size_t,
                                                 ctypes.c_float, ctypes.c_float, ctypes.c_void_p]
@@ -132,7 +135,7 @@ def _load() -> ctypes.CDLL:
                  "ddl_copy_probe", "ddl_balanced_fragments", "ddl_merge_fragment_bcast",
                  "ddl_rda_merge_fragment", "ddl_plan_set_rda_groups", "ddl_plan_rda_merge",
                  "ddl_q4_encode", "ddl_q4_merge_fragment", "ddl_rda_merge_fragment_static",
-                 "ddl_plan_set_q4_sources", "ddl_plan_q4_merge"):
+                 "ddl_plan_set_q4_sources", "ddl_plan_q4_merge", "ddl_merge_fragment_ex"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -271,6 +274,23 @@ def merge_fragment_bcast(theta: torch.Tensor, v: torch.Tensor, theta_bf16: torch
                                          _bf16_ptr(theta_bf16, n), table, code,
                                          _u64(token_counts, M), _u8(quorum_mask, M), M, n, lr, mu,
                                          _stream_handle(stream)), "ddl_merge_fragment_bcast")
+
+
+def merge_fragment_ex(theta: torch.Tensor, v: torch.Tensor, delta_out: Optional[torch.Tensor],
+                      learner_params: Sequence[Optional[torch.Tensor]], token_counts, quorum_mask,
+                      lr: float, mu: float, stream=None, learner_dtype=None) -> None:
+    """ddl_merge_fragment_ex: merge_fragment that also writes the merged outer gradient into
+    ``delta_out`` (float32, n elements; None: plain merge_fragment)."""
+    n = theta.numel()
+    if v.numel() != n or (delta_out is not None and delta_out.numel() != n):
+        raise ValueError("theta, v and delta_out differ in size")
+    M = len(learner_params)
+    table, code = _learner_table(learner_params, n,
+                                 None if learner_dtype is None else _dtype_code(learner_dtype))
+    dptr = None if delta_out is None else _state_ptr(delta_out, "delta_out")
+    _check(_lib.ddl_merge_fragment_ex(_state_ptr(theta, "theta"), _state_ptr(v, "v"), dptr, table,
+                                      code, _u64(token_counts, M), _u8(quorum_mask, M), M, n, lr,
+                                      mu, _stream_handle(stream)), "ddl_merge_fragment_ex")
 
 
 def rda_workspace_bytes(n: int, group_len: int, M: int) -> int:

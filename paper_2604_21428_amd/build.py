@@ -19,7 +19,8 @@ LIB_PATH = os.path.join(HERE, "libddlsync.so")
 # The same library compiled with -DDDL_TRACE: every merge workgroup also records when it
 # started, on which XCD and with which tile (a diagnostic; see trace_tiles.py).
 TRACE_LIB_PATH = os.path.join(HERE, "libddlsync_trace.so")
-SOURCES = ["ddl_kernels.hip", "ddl_host.hip", "ddl_partition.hip", "ddl_rda.hip", "ddl_q4.hip"]
+SOURCES = ["ddl_kernels.hip", "ddl_host.hip", "ddl_partition.hip", "ddl_rda.hip", "ddl_q4.hip",
+           "ddl_delta.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 instructions are disabled on purpose: the compiler otherwise forms them from

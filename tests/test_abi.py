@@ -162,6 +162,21 @@ def test_argument_errors_of_the_other_entry_points_need_no_device(ddl):
     assert lib.ddl_rda_workspace_bytes(n, 64, 17) == 0
     assert lib.ddl_rda_workspace_bytes(n, 64, 2) > 0
 
+    # the sync that also writes Delta
+    def ex(mask=ones, delta=ws, theta=th, count=n, lr=0.7, tbl=table):
+        return lib.ddl_merge_fragment_ex(theta, v, delta, tbl, ddl.DDL_BF16, tok, mask, M, count,
+                                         lr, 0.9, None)
+
+    assert ex(mask=zeros) == ddl.DDL_ERR_EMPTY_QUORUM
+    assert ex(lr=float("nan")) == ddl.DDL_ERR_INVALID_ARG
+    assert ex(theta=None) == ddl.DDL_ERR_INVALID_ARG
+    assert ex(delta=ctypes.c_void_p(0x60000002)) == ddl.DDL_ERR_INVALID_ARG       # fp32 alignment
+    assert ex(delta=ctypes.c_void_p(0x40000000 + 4 * n - 4)) == ddl.DDL_ERR_ALIAS  # tail of theta
+    assert ex(delta=ctypes.c_void_p(0x20000000)) == ddl.DDL_ERR_ALIAS             # on a learner
+    assert ex(tbl=(ctypes.c_void_p * M)(0x10000000, None)) == ddl.DDL_ERR_INVALID_ARG
+    assert ex(count=0) == ddl.DDL_OK
+    assert ex(delta=None, count=0) == ddl.DDL_OK
+
     # the form on the library's own scratch: argument errors and the size refusal need no device
     def rda_static(mask=ones, g=64, theta=th, count=n, lr=0.7):
         return lib.ddl_rda_merge_fragment_static(theta, v, table, ddl.DDL_BF16, tok, mask, M,
