@@ -69,6 +69,8 @@ struct DdlRdaArgs {
     uint32_t chunks_per_group;
     uint32_t vec_ok;            // all bases 16-byte aligned and group_len % 4 == 0
     float lr, mu;
+    uint32_t piece_shift;       // apply sweep: a workgroup takes one of 1 << piece_shift slices of a chunk
+    uint32_t pad;
     // workspace (device): floats
     uint64_t partial1;          // [chunks][Mq] sums of d_j^2, or [chunks][Mq (Mq + 1) / 2] of d_j d_k
     uint64_t coef;              // [groups][Mq]  w_j / N_j (0 where N_j = 0)
@@ -516,12 +518,26 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_scale_kernel(const DdlRdaArgs a
     if (threadIdx.x == 0) reinterpret_cast<float*>(a.scale)[r] = U > 0.0 ? (float)(R / U) : 0.0f;
 }
 
+// The apply sweep of the long-group path runs in the merge kernel's shape: one tile per
+// workgroup (a chunk in DDL_RDA_CHUNK / DDL_TILE slices), workgroups rotated within groups of 64.
+constexpr uint32_t kLongApplyRotate = 64;
+constexpr uint32_t kLongApplyPieceShift = 3;
+static_assert((DDL_TILE << kLongApplyPieceShift) == DDL_RDA_CHUNK, "a slice is one tile");
+
+// piece, pieces: the workgroup takes only the piece-th of `pieces` equal slices of the chunk.
 template <typename L, int MQ>
-__device__ __forceinline__ void apply_body(const DdlRdaArgs& a, uint32_t chunk)
+__device__ __forceinline__ void apply_body(const DdlRdaArgs& a, uint32_t chunk, uint32_t piece = 0,
+                                           uint32_t pieces = 1)
 {
     uint64_t begin, end;
     uint32_t group;
     chunk_range(a, chunk, begin, end, group);
+    if (pieces > 1) {
+        const uint32_t len = DDL_RDA_CHUNK / pieces;
+        begin += (uint64_t)piece * len;
+        if (begin >= end) return;
+        if (begin + len < end) end = begin + len;
+    }
     float c[MQ];
     const float scale = reinterpret_cast<const float*>(a.scale)[group];
 #pragma unroll
@@ -560,7 +576,8 @@ __device__ __forceinline__ void apply_body(const DdlRdaArgs& a, uint32_t chunk)
 template <typename L, int MQ>
 __global__ void __launch_bounds__(DDL_BLOCK) rda_apply_kernel(const DdlRdaArgs a)
 {
-    apply_body<L, MQ>(a, blockIdx.x);
+    const uint32_t b = rotate_tile(blockIdx.x, gridDim.x, kLongApplyRotate);
+    apply_body<L, MQ>(a, b >> a.piece_shift, b & ((1u << a.piece_shift) - 1), 1u << a.piece_shift);
 }
 
 // The long-group path for ALL such tensors of a fragment at once (through a plan): the three
@@ -585,7 +602,8 @@ struct DdlRdaLongArgs {
     uint32_t num_refs;
     uint32_t by_group;          // 0: workgroups count chunks, 1: groups
     uint32_t base;              // number of this grid's first workgroup (long sweeps go in parts)
-    uint32_t pad;
+    uint32_t piece_shift;       // apply sweep: a workgroup takes one of 1 << piece_shift slices
+                                // of a chunk, and the grid's workgroups are rotated like tiles
     uint64_t workspace;
     float lr, mu;
     float w[DDL_MAXL];          // normalised weights of the contributing learners, compacted
@@ -656,8 +674,9 @@ __global__ void __launch_bounds__(DDL_BLOCK) rda_long_apply_kernel(const DdlRdaL
 {
     DdlRdaArgs a;
     uint32_t chunk;
-    long_locate<L, MQ>(m, m.base + blockIdx.x, a, chunk);
-    apply_body<L, MQ>(a, chunk);
+    const uint32_t b = m.base + rotate_tile(blockIdx.x, gridDim.x, kLongApplyRotate);
+    long_locate<L, MQ>(m, b >> m.piece_shift, a, chunk);
+    apply_body<L, MQ>(a, chunk, b & ((1u << m.piece_shift) - 1), 1u << m.piece_shift);
 }
 
 // Launch shape (a): one workgroup makes all three sweeps over its own group.
@@ -1202,8 +1221,11 @@ ddl_status launch_one(ddl_dtype dt, int Mq, DdlRdaArgs& a, const Geometry& g, vo
             DDL_COUNT_GRID();
             hipLaunchKernelGGL(rda_scale_kernel, rgrid, block, 0, stream, a);
         }
+        // (workgroup numbers are 32-bit: a sweep too long for slices keeps whole chunks)
+        a.piece_shift = g.chunks <= (0x7fffffffu >> kLongApplyPieceShift) ? kLongApplyPieceShift : 0;
         DDL_COUNT_GRID();
-        hipLaunchKernelGGL(k.apply, grid, block, 0, stream, a);
+        hipLaunchKernelGGL(k.apply, dim3((uint32_t)g.chunks << a.piece_shift), block,
+                           ddlh::merge_lds_cap_bytes(dt == DDL_BF16 ? 2 : 4, Mq), stream, a);
     }
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? DDL_OK : ddlh::runtime_error(e, "RDA kernel launch");
@@ -1712,23 +1734,32 @@ extern "C" ddl_status ddl_plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, 
                     const uint64_t parts = (rf.long_chunks + max_chunks - 1) / max_chunks;
                     part = (rf.long_chunks + parts - 1) / parts;
                 }
-                auto sweep = [&](rda_long_fn kernel) {
-                    for (uint64_t base = 0; base < rf.long_chunks; base += part) {
+                // `scale` workgroups per chunk; parts of whole rotation groups
+                auto sweep = [&](rda_long_fn kernel, uint64_t scale, uint32_t lds) {
+                    const uint64_t total = rf.long_chunks * scale;
+                    const uint64_t unit = kLongApplyRotate;
+                    const uint64_t step = (part * scale + unit - 1) / unit * unit;
+                    for (uint64_t base = 0; base < total; base += step) {
                         a.base = (uint32_t)base;
                         DDL_COUNT_GRID();
-                        hipLaunchKernelGGL(
-                            kernel, dim3((uint32_t)std::min<uint64_t>(part, rf.long_chunks - base)),
-                            block, 0, stream, a);
+                        hipLaunchKernelGGL(kernel,
+                                           dim3((uint32_t)std::min<uint64_t>(step, total - base)),
+                                           block, lds, stream, a);
                     }
                 };
                 a.by_group = 0;
-                sweep(fn.long_gram);
+                a.piece_shift = 0;
+                sweep(fn.long_gram, 1, 0);
                 a.by_group = 1;
                 a.base = 0;
                 DDL_COUNT_GRID();
                 hipLaunchKernelGGL(fn.long_reduce, dim3(rf.long_groups), block, 0, stream, a);
                 a.by_group = 0;
-                sweep(fn.long_apply);
+                // (workgroup numbers are 32-bit: a sweep too long for slices keeps whole chunks)
+                a.piece_shift =
+                    rf.long_chunks <= (0x7fffffffu >> kLongApplyPieceShift) ? kLongApplyPieceShift : 0;
+                sweep(fn.long_apply, 1u << a.piece_shift,
+                      ddlh::merge_lds_cap_bytes(f.dt == DDL_BF16 ? 2 : 4, wk.q.Mq));
                 const hipError_t e = hipGetLastError();
                 if (e != hipSuccess) return ddlh::runtime_error(e, "RDA long-group kernel launch");
             } else {  // more learners than the Gram form takes: tensor by tensor
