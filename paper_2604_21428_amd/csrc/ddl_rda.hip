@@ -23,7 +23,8 @@
 //     kGramMaxLearners contributing learners:
 //   sweep 1  partial sums of d_j d_k (j <= k) per chunk   -> reduce (fp64, fixed order): c_j, R,
 //                                                             c' G c, scale = R / sqrt(c' G c)
-//   sweep 2  Delta = scale * sum_j c_j d_j, outer step, write Theta and v
+//   sweep 2  Delta = scale * sum_j c_j d_j, outer step, write Theta and v (in the merge
+//            kernel's shape: one workgroup per tile, i.e. per eighth of a chunk)
 //     -- two passes over HBM instead of three.  c' G c cancels when the outer gradients nearly
 //     oppose each other; a group whose c' G c is below kGramTrust of sum_jk |c_j c_k G_jk| gets
 //     its direction norm summed from the data after all, by the workgroup of the reduce kernel
@@ -57,7 +58,7 @@
                              // sweep of a tensor that fits the last-level cache finds it there
 #endif
 #ifndef DDL_RDA_CHUNK
-#define DDL_RDA_CHUNK 8192  // elements per workgroup and sweep: 8 groups of four per lane
+#define DDL_RDA_CHUNK 8192  // elements per partial sum: 8 groups of four per lane in the reducing sweeps
 #endif
 
 struct DdlRdaArgs {
