@@ -1,5 +1,5 @@
-"""One tensor of more than 2^32 elements (64-bit element offsets everywhere): the flat merge,
-the table kernel through a plan, RDA with one norm per row, and the 4-bit path, each checked
+"""One tensor of more than 2^32 elements (64-bit element offsets everywhere): the flat merge
+(also the form that writes Delta), the table kernel through a plan, RDA with one norm per row, and the 4-bit path, each checked
 against the oracle on windows at the start, across the 2^32 boundary and at the ragged end."""
 import numpy as np
 import pytest
@@ -34,7 +34,7 @@ def _host(x):
 @pytest.fixture(scope="module")
 def state():
     free, _ = torch.cuda.mem_get_info()
-    need = N * (4 + 4 + 2 * 2 + 2 * 0.5) * 1.1
+    need = N * (4 + 4 + 4 + 2 * 2 + 2 * 0.5) * 1.1
     if free < need:
         pytest.skip(f"needs {need / 2**30:.0f} GiB of free device memory, {free / 2**30:.0f} free")
     g = torch.Generator(device=DEV)
@@ -81,6 +81,27 @@ def test_flat_merge(ddl, state):
     ddl.merge_fragment(theta, v, learners, TOKENS, MASK, 0.7, 0.9)
     torch.cuda.synchronize()
     _check(theta, v, refs, "flat")
+
+
+def test_merge_with_delta_out(ddl, state):
+    theta, v, learners = state
+    wins = _windows(N, 1024)
+    refs = [(lo, hi, oracle.merge_fragment(_host(theta[lo:hi]), _host(v[lo:hi]),
+                                           host_learners(learners, lo, hi), TOKENS, MASK, 0.7, 0.9))
+            for lo, hi in wins]
+    # with mu = 0 the oracle's new momentum is Delta itself
+    deltas = [oracle.merge_fragment(_host(theta[lo:hi]), _host(v[lo:hi]),
+                                    host_learners(learners, lo, hi), TOKENS, MASK, 0.7, 0.0)[1]
+              for lo, hi in wins]
+    delta = torch.empty(N, dtype=torch.float32, device=DEV)
+    print("merge with delta_out", flush=True)
+    ddl.merge_fragment_ex(theta, v, delta, learners, TOKENS, MASK, 0.7, 0.9)
+    torch.cuda.synchronize()
+    _check(theta, v, refs, "ex")
+    for (lo, hi), d in zip(wins, deltas):
+        assert_parity(_host(delta[lo:hi]), d, f"ex [{lo},{hi}) delta")
+    del delta
+    torch.cuda.empty_cache()
 
 
 def test_plan_merge_with_a_second_small_tensor(ddl, state):
