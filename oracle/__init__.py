@@ -83,6 +83,11 @@ def load(path: str | None = None) -> ctypes.CDLL:
                                                  ctypes.c_int, ctypes.c_size_t, ctypes.c_size_t,
                                                  ctypes.c_float, ctypes.c_float]
     lib.ddl_oracle_q4_merge_fragment.restype = ctypes.c_int
+    lib.ddl_oracle_q4_rda_merge_fragment.argtypes = [f64p, f64p, f32p, f32p, u8pp, u8pp, u64p, u8p,
+                                                     ctypes.c_int, ctypes.c_size_t,
+                                                     ctypes.c_size_t, ctypes.c_size_t,
+                                                     ctypes.c_float, ctypes.c_float]
+    lib.ddl_oracle_q4_rda_merge_fragment.restype = ctypes.c_int
     lib.ddl_oracle_round_bf16.argtypes = [f32p, ctypes.POINTER(ctypes.c_uint16), ctypes.c_size_t]
     lib.ddl_oracle_round_bf16.restype = None
     if path is None:
@@ -262,9 +267,10 @@ def q4_encode(theta: np.ndarray, learner: np.ndarray, block_len: int, lib=None):
 
 def q4_merge_fragment(theta: np.ndarray, v: np.ndarray, codes: Sequence[np.ndarray | None],
                       scales: Sequence[np.ndarray | None], token_counts, quorum_mask,
-                      block_len: int, lr: float, mu: float, lib=None):
+                      block_len: int, lr: float, mu: float, lib=None, rda_group_len: int = 0):
     """One fragment sync from 4-bit outer gradients (codes + per-block scales per learner).
-    Returns (theta_new, v_new) as float64 arrays."""
+    Returns (theta_new, v_new) as float64 arrays.  ``rda_group_len`` > 0: the merge is
+    radial-directional averaging with one norm per that many elements (q4_rda_merge_fragment)."""
     lib = lib or load()
     theta = np.ascontiguousarray(theta, dtype=np.float32)
     v = np.ascontiguousarray(v, dtype=np.float32)
@@ -286,11 +292,25 @@ def q4_merge_fragment(theta: np.ndarray, v: np.ndarray, codes: Sequence[np.ndarr
         keep += [c, s]
     theta_out = np.empty(n, dtype=np.float64)
     v_out = np.empty(n, dtype=np.float64)
-    rc = lib.ddl_oracle_q4_merge_fragment(
-        _ptr(theta_out, ctypes.c_double), _ptr(v_out, ctypes.c_double),
-        _ptr(theta, ctypes.c_float), _ptr(v, ctypes.c_float), ctab, stab,
-        _ptr(t, ctypes.c_uint64), _ptr(q, ctypes.c_uint8), M, n, block_len, lr, mu)
+    head = [_ptr(theta_out, ctypes.c_double), _ptr(v_out, ctypes.c_double),
+            _ptr(theta, ctypes.c_float), _ptr(v, ctypes.c_float), ctab, stab,
+            _ptr(t, ctypes.c_uint64), _ptr(q, ctypes.c_uint8), M, n, block_len]
+    if rda_group_len > 0:
+        rc = lib.ddl_oracle_q4_rda_merge_fragment(*head, rda_group_len, lr, mu)
+    else:
+        rc = lib.ddl_oracle_q4_merge_fragment(*head, lr, mu)
     del keep
     if rc != OK:
         raise OracleError(rc)
     return theta_out, v_out
+
+
+def q4_rda_merge_fragment(theta: np.ndarray, v: np.ndarray, codes, scales, token_counts,
+                          quorum_mask, block_len: int, group_len: int, lr: float, mu: float,
+                          lib=None):
+    """One tensor sync from 4-bit outer gradients with radial-directional averaging as the
+    merge, one norm per ``group_len`` consecutive elements."""
+    if group_len <= 0:
+        raise OracleError(BAD_ARG)
+    return q4_merge_fragment(theta, v, codes, scales, token_counts, quorum_mask, block_len, lr,
+                             mu, lib=lib, rda_group_len=group_len)

@@ -18,8 +18,9 @@
  * sums.
  *
  * PARITY UNPINNED (against the paper) for the 4-bit outer-gradient functions
- * ddl_oracle_q4_encode / ddl_oracle_q4_merge_fragment: the paper states only
- * the width; the block-wise format is this build's choice.  See their comment.
+ * ddl_oracle_q4_encode / ddl_oracle_q4_merge_fragment /
+ * ddl_oracle_q4_rda_merge_fragment: the paper states only the width; the
+ * block-wise format is this build's choice.  See their comment.
  */
 #include <math.h>
 #include <pthread.h>
@@ -433,6 +434,86 @@ int ddl_oracle_q4_merge_fragment(double* theta_out, double* v_out, const float* 
         double v_new = (double)mu * (double)v[i] + Delta;
         theta_out[i] = (double)theta[i] - (double)lr * (Delta + (double)mu * v_new);
         v_out[i] = v_new;
+    }
+    return ORACLE_OK;
+}
+
+/* The value learner data (cd, sc) stands for at element i: block scale times code. */
+static double q4_value(const uint8_t* cd, const float* sc, size_t i, size_t block_len)
+{
+    return (double)sc[i / block_len] * (double)q4_code(cd, i);
+}
+
+/*
+ * Radial-directional averaging of 4-bit outer gradients + OuterOpt: what the syncer computes
+ * when the outer gradients arrive compressed (Appendix D.3: they are compressed before the
+ * mergeFn of Algorithm 2) and the mergeFn is RDA (Appendix D.2, "Radial-directional
+ * averaging"; Section 5.1).  The outer gradient of learner m at element i is the value its
+ * (scale, code) pair stands for; norms are taken over groups of `group_len` consecutive
+ * elements of the tensor (groups and scale blocks need not line up), and
+ *
+ *     Delta = ( sum_m w_m ||d_m|| ) * phi( sum_m w_m phi(d_m) )
+ *
+ * with the same readings as ddl_oracle_rda_merge_fragment (weighted mean of the norms; a
+ * learner whose gradient is zero on a group adds no direction; a zero mean direction gives
+ * Delta = 0).  PARITY UNPINNED against the paper as far as the 4-bit format and the group
+ * length go, like the two functions it combines.
+ */
+int ddl_oracle_q4_rda_merge_fragment(double* theta_out, double* v_out, const float* theta,
+                                     const float* v, const uint8_t* const* codes,
+                                     const float* const* scales, const uint64_t* token_counts,
+                                     const uint8_t* quorum_mask, int M, size_t n,
+                                     size_t block_len, size_t group_len, float lr, float mu)
+{
+    double w[ORACLE_MAX_LEARNERS];
+    int rc = ddl_oracle_weights(token_counts, quorum_mask, M, w);
+    if (rc != ORACLE_OK)
+        return rc;
+    if (block_len == 0 || group_len == 0 || !codes || !scales)
+        return ORACLE_BAD_ARG;
+    if (!(lr >= 0.0f) || !(mu >= 0.0f) || isinf(lr) || isinf(mu))
+        return ORACLE_BAD_ARG;
+    if (n > 0 && (!theta_out || !v_out || !theta || !v))
+        return ORACLE_BAD_ARG;
+    for (int m = 0; m < M; ++m)
+        if (w[m] != 0.0 && n > 0 && (!codes[m] || !scales[m]))
+            return ORACLE_BAD_ARG;
+    for (size_t g0 = 0; g0 < n; g0 += group_len) {
+        size_t g1 = n - g0 < group_len ? n : g0 + group_len;
+        /* radial part: the weighted mean R of the norms over the group */
+        double len[ORACLE_MAX_LEARNERS];
+        double R = 0.0;
+        for (int m = 0; m < M; ++m) {
+            len[m] = 0.0;
+            if (w[m] == 0.0)
+                continue;
+            double acc = 0.0;
+            for (size_t i = g0; i < g1; ++i) {
+                double d = q4_value(codes[m], scales[m], i, block_len);
+                acc += d * d;
+            }
+            len[m] = sqrt(acc);
+            R += w[m] * len[m];
+        }
+        /* directional part: the weighted mean of the unit vectors (in v_out) and its norm */
+        double uu = 0.0;
+        for (size_t i = g0; i < g1; ++i) {
+            double u = 0.0;
+            for (int m = 0; m < M; ++m) {
+                if (w[m] == 0.0 || len[m] == 0.0)
+                    continue;
+                u += w[m] * (q4_value(codes[m], scales[m], i, block_len) / len[m]);
+            }
+            v_out[i] = u;
+            uu += u * u;
+        }
+        double U = sqrt(uu);
+        for (size_t i = g0; i < g1; ++i) {
+            double Delta = U > 0.0 ? R * (v_out[i] / U) : 0.0;
+            double vn = (double)mu * (double)v[i] + Delta;
+            theta_out[i] = (double)theta[i] - (double)lr * (Delta + (double)mu * vn);
+            v_out[i] = vn;
+        }
     }
     return ORACLE_OK;
 }

@@ -56,6 +56,10 @@ class OracleApi:
         return oracle.q4_merge_fragment(theta, v, codes, scales, t, q, block_len, lr, mu,
                                         lib=self.lib)
 
+    def q4_rda(self, theta, v, codes, scales, t, q, block_len, group_len, lr, mu):
+        return oracle.q4_rda_merge_fragment(theta, v, codes, scales, t, q, block_len, group_len,
+                                            lr, mu, lib=self.lib)
+
 
 def f32(x):
     return np.ascontiguousarray(np.asarray(x, dtype=np.float32))
@@ -749,6 +753,108 @@ def pin_q4_zero_codes_and_linearity(o: OracleApi):
     d2 = o.q4_merge(theta, f32(np.zeros(n)), [c], [f32(2 * s)], [1], [1], B, 1.0, 0.0)[1]
     assert np.array_equal(d2, 2 * d1)
     assert np.array_equal(d1, np.repeat(s.astype(np.float64), B)[:n] * _q4_unpack(c, n))
+
+
+# --------------------------------------------------------------------------------------
+# radial-directional averaging of 4-bit outer gradients
+# --------------------------------------------------------------------------------------
+
+def _q4_pack(q: np.ndarray) -> np.ndarray:
+    n = q.size
+    nib = (q & 0x0F).astype(np.uint8)
+    packed = np.zeros((n + 1) // 2, dtype=np.uint8)
+    packed[: n // 2] = nib[0:n - n % 2:2] | (nib[1::2] << 4)
+    if n % 2:
+        packed[-1] = nib[-1]
+    return packed
+
+
+def pin_q4_rda_hand_worked(o: OracleApi):
+    """Two learners, one group of two elements, scale 1: d_1 = [3, 4] (byte 0x43), d_2 = [-4, 3]
+    (byte 0x3C), both of norm 5 and orthogonal.  Equal weights: R = 5, mean unit direction
+    [-0.1, 0.7] of norm sqrt(0.5), Delta = 5 [-0.1, 0.7] / sqrt(0.5).  Tokens [1, 3]: w =
+    [1/4, 3/4], R = 5, direction [0.15 - 0.6, 0.2 + 0.45] = [-0.45, 0.65] of norm sqrt(0.625).
+    lr 1, mu 0: v' = Delta, Theta' = Theta - Delta."""
+    codes = [np.array([0x43], np.uint8), np.array([0x3C], np.uint8)]
+    scales = [f32([1.0]), f32([1.0])]
+    theta = f32([10.0, -20.0])
+    for tokens, u, uu in (([7, 7], [-0.1, 0.7], 0.5), ([1, 3], [-0.45, 0.65], 0.625)):
+        th, v = o.q4_rda(theta, f32([0, 0]), codes, scales, tokens, [1, 1], 8, 2, 1.0, 0.0)
+        d = 5.0 * np.asarray(u) / np.sqrt(uu)
+        assert np.allclose(v, d, rtol=0, atol=1e-14), (tokens, v)
+        assert abs(np.linalg.norm(v) - 5.0) < 1e-14          # equal norms are kept
+        assert np.allclose(th, theta.astype(np.float64) - d, rtol=0, atol=1e-13)
+    # the scale counts: learner 2 at scale 0.5 has norm 2.5 (R = 3.75 at equal weights), same directions
+    th, v = o.q4_rda(theta, f32([0, 0]), codes, [f32([1.0]), f32([0.5])], [7, 7], [1, 1], 8, 2,
+                     1.0, 0.0)
+    assert np.allclose(v, 3.75 * np.asarray([-0.1, 0.7]) / np.sqrt(0.5), rtol=0, atol=1e-14)
+
+
+def pin_q4_rda_matches_rda_on_exact_values(o: OracleApi):
+    """Learner values Theta - s q that fp32 holds exactly: RDA on the 4-bit data must equal the
+    (pinned) RDA oracle on those learners, for groups that do and do not line up with the
+    scale blocks, an absent learner (NULL data) and a ragged last group."""
+    rng = np.random.default_rng(31)
+    n, B, M = 300, 32, 4
+    nb = -(-n // B)
+    theta = f32(rng.integers(-512, 512, n) / 1024.0)
+    v = f32(rng.integers(-64, 64, n) / 4096.0)
+    codes, scales, learners = [], [], []
+    for m in range(M):
+        q = rng.integers(-7, 8, n)
+        s = (2.0 ** rng.integers(-12, -8, nb)).astype(np.float32)
+        learners.append(f32(theta.astype(np.float64) - np.repeat(s, B)[:n].astype(np.float64) * q))
+        codes.append(_q4_pack(q))
+        scales.append(s)
+    t, mask = [3, 5, 7, 11], [1, 0, 1, 1]
+    for g in (32, 50, 64, 7, 300, 1000):
+        ref = o.rda(theta, v, learners, t, mask, g, 0.7, 0.9)
+        got = o.q4_rda(theta, v, [codes[0], None, codes[2], codes[3]],
+                       [scales[0], None, scales[2], scales[3]], t, mask, B, g, 0.7, 0.9)
+        assert np.allclose(got[0], ref[0], rtol=0, atol=1e-15), g
+        assert np.allclose(got[1], ref[1], rtol=0, atol=1e-15), g
+
+
+def pin_q4_rda_zero_learner_and_scaling(o: OracleApi):
+    """A learner whose codes are all zero adds no direction but its zero norm enters the mean:
+    with weights [1/4, 3/4] and learner 1 zero, Delta = 3/4 d_2.  Doubling every scale doubles
+    Delta; all-zero data gives Delta = 0."""
+    rng = np.random.default_rng(32)
+    n, B, g = 96, 16, 24
+    theta, zero = f32(rng.normal(0, 0.02, n)), f32(np.zeros(n))
+    zc = np.zeros((n + 1) // 2, dtype=np.uint8)
+    c = rng.integers(0, 256, (n + 1) // 2).astype(np.uint8)
+    s = f32(2.0 ** rng.integers(-10, -6, n // B))
+    d2 = np.repeat(s.astype(np.float64), B) * _q4_unpack(c, n)
+    got = o.q4_rda(theta, zero, [zc, c], [s, s], [1, 3], [1, 1], B, g, 1.0, 0.0)[1]
+    assert np.allclose(got, 0.75 * d2, rtol=0, atol=1e-16)
+    twice = o.q4_rda(theta, zero, [zc, c], [s, f32(2 * s)], [1, 3], [1, 1], B, g, 1.0, 0.0)[1]
+    assert np.allclose(twice, 2 * got, rtol=0, atol=1e-16)
+    none = o.q4_rda(theta, zero, [zc, zc], [s, s], [1, 3], [1, 1], B, g, 1.0, 0.0)
+    assert not none[1].any() and np.array_equal(none[0], theta.astype(np.float64))
+
+
+def pin_q4_rda_momentum_and_errors(o: OracleApi):
+    """The outer step after the merge is the same as everywhere (checked through the direct
+    4-bit merge on one learner, where RDA is the identity), and bad arguments are refused."""
+    rng = np.random.default_rng(33)
+    n, B = 77, 8
+    theta, v = f32(rng.normal(0, 0.02, n)), f32(rng.normal(0, 1e-4, n))
+    c = rng.integers(0, 256, (n + 1) // 2).astype(np.uint8)
+    s = f32(rng.uniform(1e-4, 1e-3, -(-n // B)))
+    ref = o.q4_merge(theta, v, [c], [s], [9], [1], B, 0.7, 0.9)
+    got = o.q4_rda(theta, v, [c], [s], [9], [1], B, 11, 0.7, 0.9)
+    assert np.allclose(got[0], ref[0], rtol=0, atol=1e-15)
+    assert np.allclose(got[1], ref[1], rtol=0, atol=1e-15)
+    for bad in (dict(group_len=0), dict(block_len=0)):
+        kw = dict(block_len=B, group_len=11)
+        kw.update(bad)
+        try:
+            oracle.q4_rda_merge_fragment(theta, v, [c], [s], [9], [1], kw["block_len"],
+                                         kw["group_len"], 0.7, 0.9, lib=o.lib)
+        except (oracle.OracleError, AssertionError, ZeroDivisionError):
+            continue
+        raise AssertionError(f"accepted {bad}")
 
 
 ALL_PINS = [v for k, v in sorted(globals().items()) if k.startswith("pin_") and callable(v)]

@@ -72,6 +72,23 @@ MUTANTS = [
     ("q4_encode_sign", "float d = theta[i] - (float)learner_value(learner, learner_dtype, i);\n            float r =",
      "float d = (float)learner_value(learner, learner_dtype, i) - theta[i];\n            float r ="),
     ("q4_encode_pack_order", "(i & 1) ? nib << 4 : nib", "(i & 1) ? nib : nib << 4"),
+    ("q4_rda_norm_not_sqrt", "len[m] = sqrt(acc);", "len[m] = acc;"),
+    ("q4_rda_mean_norm_unweighted", "R += w[m] * len[m];", "R += len[m] / M;"),
+    ("q4_rda_direction_not_normalised",
+     "u += w[m] * (q4_value(codes[m], scales[m], i, block_len) / len[m]);",
+     "u += w[m] * q4_value(codes[m], scales[m], i, block_len);"),
+    ("q4_rda_direction_unweighted",
+     "u += w[m] * (q4_value(codes[m], scales[m], i, block_len) / len[m]);",
+     "u += (q4_value(codes[m], scales[m], i, block_len) / len[m]);"),
+    ("q4_rda_not_projected", "R * (v_out[i] / U)", "R * v_out[i]"),
+    ("q4_rda_groups_merged", "size_t g1 = n - g0 < group_len ? n : g0 + group_len;",
+     "size_t g1 = n; group_len = n;"),
+    ("q4_rda_scale_index", "(double)sc[i / block_len]", "(double)sc[0]"),
+    ("q4_rda_momentum_dropped", "double vn = (double)mu * (double)v[i] + Delta;",
+     "double vn = Delta;"),
+    ("q4_rda_zero_learner_divides",
+     "if (w[m] == 0.0 || len[m] == 0.0)\n                    continue;\n                u += w[m] * (q4_value",
+     "if (w[m] == 0.0)\n                    continue;\n                u += w[m] * (q4_value"),
     ("chunk_overlap", "size_t lo = per * (size_t)t;", "size_t lo = per * (size_t)t + (t ? 1 : 0);"),
 ]
 
