@@ -69,7 +69,7 @@ def parse_args():
     ap.add_argument("--balanced", type=int, default=0, metavar="P",
                     help="regroup the workload's tensors into P balanced fragments with "
                          "ddl_balanced_fragments (the paper uses P = 24)")
-    ap.add_argument("--merge", default="avg", choices=["avg", "rda", "q4"],
+    ap.add_argument("--merge", default="avg", choices=["avg", "rda", "q4", "q4rda"],
                     help="avg: weighted direct averaging (the metric's path); rda: "
                          "radial-directional averaging; q4: merge of 4-bit block-wise outer "
                          "gradients")
@@ -110,7 +110,7 @@ def profiled_traffic(ddl, workload, merge, default_shape):
     the value is null and the source string says why."""
     if not default_shape:
         return None, "not reported: launch-shape options differ from the profiled defaults"
-    here = ddl.kernel_build_id("rda" if merge.startswith("rda") else
+    here = ddl.kernel_build_id("rda" if merge.startswith(("rda", "q4rda")) else
                                "q4" if merge.startswith("q4") else "merge")
     stale = None
     pdir = os.path.join(ROOT, "profiles")
@@ -138,6 +138,17 @@ class Setup:
     pass
 
 
+def merge_label(args):
+    """How the merge of this run is named in the JSON line and in the profile summaries."""
+    if args.merge == "avg":
+        return "avg"
+    if args.merge == "q4":
+        return f"q4/block{args.q4_block}"
+    if args.merge == "q4rda":
+        return f"q4rda/block{args.q4_block}/{args.rda_group}"
+    return f"rda/{args.rda_group}"
+
+
 def build_setup(args, wl, ddl, ddl_synth, torch, replicas=None):
     """Generates ``replicas`` copies of the workload in HBM and marshals the calls of a step."""
     su = Setup()
@@ -152,7 +163,7 @@ def build_setup(args, wl, ddl, ddl_synth, torch, replicas=None):
     su.replicas = replicas
     dt = {"bf16": torch.bfloat16, "f32": torch.float32}
     rda_groups = None
-    if args.merge == "rda":
+    if args.merge in ("rda", "q4rda"):
         rda_groups = [[t.shape[-1] if args.rda_group == "row" else t.numel for t in f.tensors]
                       for f in wl.fragments]
     su.rda_groups = rda_groups
@@ -163,7 +174,7 @@ def build_setup(args, wl, ddl, ddl_synth, torch, replicas=None):
             for s in segs:
                 s.bcast = (torch.empty(s.theta.numel(), dtype=torch.bfloat16, device="cuda:0")
                            if args.bcast else None)
-        if args.merge == "q4":
+        if args.merge in ("q4", "q4rda"):
             # The learners' outer gradients are encoded once, tensor by tensor, outside the
             # timed region, as a learner would send them; the parameter copies are then dropped
             # (the 4-bit merge reads codes and scales only).
@@ -187,10 +198,15 @@ def build_setup(args, wl, ddl, ddl_synth, torch, replicas=None):
                                           M=f.M, learner_dtype=dt[f.learner_dtype])
                              for f, segs in zip(wl.fragments, data)])
             plan.set_q4_sources(sources, args.q4_block)
+            ws = None
+            if args.merge == "q4rda":     # RDA as the merge of the 4-bit outer gradients
+                plan.set_rda_groups([g for gs in rda_groups for g in gs])
+                ws = torch.empty(max(256, plan.rda_workspace_bytes), dtype=torch.uint8,
+                                 device="cuda:0")
             calls = [plan.prepare([(fi, wl.fragments[fi].token_counts,
                                     wl.fragments[fi].quorum_mask, wl.fragments[fi].lr,
                                     wl.fragments[fi].mu)]) for fi in wl.arrival_order]
-            copies.append((data, ("q4-plan", plan, None), calls))
+            copies.append((data, ("q4-plan", plan, ws), calls))
         elif args.merge == "rda" and args.api == "plan":
             plan = ddl.Plan([ddl.Fragment([(s.theta, s.v, s.learners, s.bcast) for s in segs],
                                           M=f.M, learner_dtype=dt[f.learner_dtype])
@@ -234,13 +250,17 @@ def build_setup(args, wl, ddl, ddl_synth, torch, replicas=None):
         _, plan, calls = copy
         out = []
         if isinstance(plan, tuple) and plan[0] == "q4-plan":
-            _, qplan, _ = plan
+            _, qplan, qws = plan
             for fi, c in zip(wl.arrival_order, calls):
                 nb = sum(s.theta.numel() * (16 + (2 if s.bcast is not None else 0)) +
                          sum(cc.numel() + 4 * sc.numel()
                              for cc, sc in zip(*s.q4) if cc is not None)
                          for s in copy[0][fi])
-                out.append((fi, nb, lambda c=c, qplan=qplan: qplan.q4_merge(c)))
+                if qws is None:
+                    out.append((fi, nb, lambda c=c, qplan=qplan: qplan.q4_merge(c)))
+                else:
+                    out.append((fi, nb, lambda c=c, qplan=qplan, qws=qws:
+                                qplan.q4_rda_merge(c, qws)))
         elif isinstance(plan, tuple):
             _, rplan, ws = plan
             for fi, c in zip(wl.arrival_order, calls):
@@ -265,7 +285,7 @@ def build_setup(args, wl, ddl, ddl_synth, torch, replicas=None):
 
     su.launch_lists = [launch_list(c) for c in copies]
     su.launches_per_step = (wl.num_segments if args.api == "tensor" else len(su.launch_lists[0]))
-    if args.merge == "q4":      # codes and scales as stored; the bf16 copy is counted there too
+    if args.merge in ("q4", "q4rda"):   # codes and scales as stored; the bf16 copy is counted too
         su.alg_bytes = sum(nb for _, nb, _ in su.launch_lists[0])
     else:
         su.alg_bytes = wl.algorithmic_bytes + (2 * wl.numel if args.bcast else 0)
@@ -292,7 +312,7 @@ def host_cores():
 
 
 def parity_supported(args):
-    return (args.merge in ("avg", "rda", "q4") and args.api in ("plan", "batch") and
+    return (args.merge in ("avg", "rda", "q4", "q4rda") and args.api in ("plan", "batch") and
             args.syncs_per_call == 1 and not (args.merge == "rda" and args.api == "batch"))
 
 
@@ -329,6 +349,8 @@ def oracle_leg(args, su, torch, ddl_synth, budget_s, single_core_s, must_cover=(
             n = th0.numel()
             g = (su.rda_groups[fi][si] if su.rda_groups else
                  args.q4_block if args.merge == "q4" else 1)   # chunks end on these boundaries
+            if args.merge == "q4rda" and g < n:                # ... of groups and scale blocks
+                g = g * args.q4_block // math.gcd(g, args.q4_block)
             # chunks end on group boundaries; a group longer than a chunk is taken whole
             chunk = max(g, PARITY_CHUNK // g * g) if g > 1 else PARITY_CHUNK
             for lo in range(0, n, chunk):
@@ -337,15 +359,17 @@ def oracle_leg(args, su, torch, ddl_synth, budget_s, single_core_s, must_cover=(
                 vv = ddl_synth.to_host_array(v0[lo:hi])
                 ls = [ddl_synth.to_host_array(x[lo:hi]) if (p and x is not None) else None
                       for x, p in zip(s.learners, present)]
-                if args.merge == "q4":
+                if args.merge in ("q4", "q4rda"):
                     B = args.q4_block
                     cs = [c[lo // 2:(hi + 1) // 2].cpu().numpy() if c is not None else None
                           for c in s.q4[0]]
                     ss = [x[lo // B:-(-hi // B)].cpu().numpy() if x is not None else None
                           for x in s.q4[1]]
                     t0 = time.perf_counter()
-                    ref = oracle.q4_merge_fragment(th, vv, cs, ss, f.token_counts, f.quorum_mask,
-                                                   B, f.lr, f.mu)
+                    ref = oracle.q4_merge_fragment(
+                        th, vv, cs, ss, f.token_counts, f.quorum_mask, B, f.lr, f.mu,
+                        rda_group_len=(min(su.rda_groups[fi][si], hi - lo)
+                                       if args.merge == "q4rda" else 0))
                     t_single += time.perf_counter() - t0
                     n_single += hi - lo
                 elif args.merge == "rda":
@@ -564,14 +588,13 @@ def measure(args, name, ddl, ddl_synth, torch, steps, warmup, parity_budget, mus
     detail = None
     if with_detail and not args.graph and not multi_stream:
         detail = detail_pass(torch, su, min(steps, 40),
-                             2 * wl.numel if (args.bcast and args.merge != "q4") else 0)
+                             2 * wl.numel if (args.bcast and not args.merge.startswith("q4")) else 0)
     # A step consists of merge-kernel grids only (no copies, no other kernels), so the event
     # time per step divided by the grids per step is the average duration of one kernel launch,
     # the gaps between back-to-back launches included.
     kernel_ms = gpu_ms / grids
     achieved = su.alg_bytes / grids / (kernel_ms * 1e-3) / 1e9
-    merge_tag = (args.merge if args.merge == "avg" else
-                 f"q4/block{args.q4_block}" if args.merge == "q4" else f"rda/{args.rda_group}")
+    merge_tag = merge_label(args)
     plain = default_shape and not (args.bcast or args.balanced or args.graph or multi_stream or
                                    args.api != "plan" or args.syncs_per_call != 1)
     traffic, traffic_source = profiled_traffic(ddl, wl.name, merge_tag, plain)
@@ -613,8 +636,8 @@ def main():
             "bench.py: this build is single-GPU by design (the synchronizer path is element-wise "
             "and has no collectives here); run with --gpus 1.\n")
         sys.exit(2)
-    if args.merge == "q4" and args.api != "plan":
-        sys.stderr.write("bench.py: --merge q4 goes through the plan\n")
+    if args.merge in ("q4", "q4rda") and args.api != "plan":
+        sys.stderr.write("bench.py: --merge q4 / q4rda go through the plan\n")
         sys.exit(2)
     if args.merge == "rda" and args.api == "batch":
         sys.stderr.write("bench.py: --merge rda goes with --api plan or --api tensor\n")
@@ -706,13 +729,12 @@ def main():
             "state_dtype": "f32",
             "lr": wl.fragments[0].lr,
             "mu": wl.fragments[0].mu,
-            "api": ("ddl_q4_merge_fragment" if args.merge == "q4" else
+            "api": ("ddl_plan_q4_merge" if args.merge == "q4" else
+                    "ddl_plan_q4_rda_merge" if args.merge == "q4rda" else
                     "ddl_rda_merge_fragment" if args.api == "tensor" else
                     "ddl_plan_rda_merge" if args.merge == "rda" else
                     "ddl_plan_merge" if args.api == "plan" else "ddl_merge_batch"),
-            "merge": (args.merge if args.merge == "avg" else
-                      f"q4/block{args.q4_block}" if args.merge == "q4" else
-                      f"rda/{args.rda_group}"),
+            "merge": merge_label(args),
             "calls_per_step": main_summary["calls_per_step"],
             "launches_per_step": main_summary["launches_per_step"],
             "syncs_per_call": args.syncs_per_call,
@@ -724,7 +746,7 @@ def main():
             "tile_rotate": ddl.get_option("tile_rotate"),
             "max_blocks_per_cu": ddl.get_option("max_blocks_per_cu"),
             "library_build": ddl.build_id(),
-            "kernel_build": ddl.kernel_build_id("rda" if args.merge == "rda" else
+            "kernel_build": ddl.kernel_build_id("rda" if args.merge in ("rda", "q4rda") else
                                                 "q4" if args.merge == "q4" else "merge"),
         },
         "achieved_gbps": main_summary["algorithmic_bytes_per_step"] /
@@ -739,7 +761,7 @@ def main():
             "traffic": main_summary["traffic"],
             "traffic_source": main_summary["traffic_source"],
             "kernel": ("ddl_merge_kernel" if args.merge == "avg" else
-                       "q4_merge_kernel" if args.merge == "q4" else
+                       "ddl_merge_kernel on 4-bit codes" if args.merge == "q4" else
                        "rda kernel(s) of one tensor" if args.api == "tensor" else
                        "rda kernel(s) of one fragment"),
             "avg_launch_ms": main_summary["avg_launch_ms"],

@@ -418,6 +418,36 @@ DDL_API ddl_status ddl_plan_q4_merge(ddl_plan* plan, const ddl_sync* syncs, int 
                                      void* hip_stream);
 
 /*
+ * Radial-directional averaging as the merge of 4-bit outer gradients: what the syncer runs
+ * when the outer gradients arrive compressed (Appendix D.3: they are compressed before the
+ * mergeFn of Algorithm 2) and the mergeFn is RDA (Appendix D.2; Section 5.1).  The outer
+ * gradient of learner m at element i is scale_m[i / block_len] * code_m[i]; norms are taken
+ * over groups of group_len consecutive elements of a tensor (groups and scale blocks need not
+ * line up), Delta is the RDA formula given at ddl_rda_merge_fragment, then the same outer
+ * Nesterov step.  Same kernels as the RDA merge of bf16 / fp32 learners, instantiated for codes
+ * and scales (the reducing sweeps then read neither Theta nor v).
+ *
+ * ddl_q4_rda_merge_fragment   one tensor: arguments of ddl_q4_merge_fragment plus group_len and
+ *                             the workspace of ddl_rda_merge_fragment
+ *                             (ddl_rda_workspace_bytes(n, group_len, M) bytes).
+ * ddl_plan_q4_rda_merge       whole fragments through a plan on which both
+ *                             ddl_plan_set_q4_sources and ddl_plan_set_rda_groups have been
+ *                             called; arguments and workspace as ddl_plan_rda_merge.  A tensor
+ *                             whose group length is (size_t)-1 takes the direct 4-bit merge.
+ * Both only enqueue kernels.  Errors as ddl_q4_merge_fragment / ddl_plan_rda_merge.
+ */
+DDL_API ddl_status ddl_q4_rda_merge_fragment(float* theta, float* v, const uint8_t* const* codes,
+                                             const float* const* scales,
+                                             const uint64_t* token_counts,
+                                             const uint8_t* quorum_mask, int M, size_t n,
+                                             size_t block_len, size_t group_len, float lr,
+                                             float mu, void* workspace, size_t workspace_bytes,
+                                             void* hip_stream);
+DDL_API ddl_status ddl_plan_q4_rda_merge(ddl_plan* plan, const ddl_sync* syncs, int count,
+                                         void* workspace, size_t workspace_bytes,
+                                         void* hip_stream);
+
+/*
  * Balanced tensor fragmentation (Section 5.1; Appendix C, "Balanced tensor fragmentation"):
  * greedy number partitioning of the model's tensors into num_fragments fragments -- tensors are
  * taken in descending order of size and each goes to the fragment whose total is the smallest

@@ -123,6 +123,12 @@ def _load() -> ctypes.CDLL:
                                             ctypes.c_size_t, ctypes.c_size_t]
     lib.ddl_plan_q4_merge.argtypes = [ctypes.c_void_p, ctypes.POINTER(_Sync), ctypes.c_int,
                                       ctypes.c_void_p]
+    lib.ddl_q4_rda_merge_fragment.argtypes = [ctypes.c_void_p, ctypes.c_void_p, vpp, vpp, u64p, u8p,
+                                              ctypes.c_int, ctypes.c_size_t, ctypes.c_size_t,
+                                              ctypes.c_size_t, ctypes.c_float, ctypes.c_float,
+                                              ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.ddl_plan_q4_rda_merge.argtypes = [ctypes.c_void_p, ctypes.POINTER(_Sync), ctypes.c_int,
+                                          ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     lib.ddl_balanced_fragments.argtypes = [u64p, ctypes.c_int, ctypes.c_int,
                                            ctypes.POINTER(ctypes.c_int)]
     lib.ddl_copy_probe.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
@@ -135,7 +141,8 @@ def _load() -> ctypes.CDLL:
                  "ddl_copy_probe", "ddl_balanced_fragments", "ddl_merge_fragment_bcast",
                  "ddl_rda_merge_fragment", "ddl_plan_set_rda_groups", "ddl_plan_rda_merge",
                  "ddl_q4_encode", "ddl_q4_merge_fragment", "ddl_rda_merge_fragment_static",
-                 "ddl_plan_set_q4_sources", "ddl_plan_q4_merge", "ddl_merge_fragment_ex"):
+                 "ddl_plan_set_q4_sources", "ddl_plan_q4_merge", "ddl_merge_fragment_ex",
+                 "ddl_q4_rda_merge_fragment", "ddl_plan_q4_rda_merge"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -367,15 +374,7 @@ def q4_encode(theta: torch.Tensor, learner: torch.Tensor, block_len: int,
     return codes, scales
 
 
-def q4_merge_fragment(theta: torch.Tensor, v: torch.Tensor,
-                      codes: Sequence[Optional[torch.Tensor]],
-                      scales: Sequence[Optional[torch.Tensor]], token_counts, quorum_mask,
-                      block_len: int, lr: float, mu: float, stream=None) -> None:
-    """ddl_q4_merge_fragment: in-place sync of one flat fragment from the learners' 4-bit
-    outer gradients (codes + per-block scales, as ``q4_encode`` writes them)."""
-    n = theta.numel()
-    if v.numel() != n:
-        raise ValueError("theta and v differ in size")
+def _q4_tables(codes, scales, n: int, block_len: int):
     M = len(codes)
     if len(scales) != M:
         raise ValueError("one scales tensor per codes tensor")
@@ -392,9 +391,42 @@ def q4_merge_fragment(theta: torch.Tensor, v: torch.Tensor,
             if block_len > 0 and s.numel() < -(-n // block_len):
                 raise ValueError("scales tensor too short")
             stab[m] = s.data_ptr()
+    return ctab, stab, M
+
+
+def q4_merge_fragment(theta: torch.Tensor, v: torch.Tensor,
+                      codes: Sequence[Optional[torch.Tensor]],
+                      scales: Sequence[Optional[torch.Tensor]], token_counts, quorum_mask,
+                      block_len: int, lr: float, mu: float, stream=None) -> None:
+    """ddl_q4_merge_fragment: in-place sync of one flat fragment from the learners' 4-bit
+    outer gradients (codes + per-block scales, as ``q4_encode`` writes them)."""
+    n = theta.numel()
+    if v.numel() != n:
+        raise ValueError("theta and v differ in size")
+    ctab, stab, M = _q4_tables(codes, scales, n, block_len)
     _check(_lib.ddl_q4_merge_fragment(_state_ptr(theta, "theta"), _state_ptr(v, "v"), ctab, stab,
                                       _u64(token_counts, M), _u8(quorum_mask, M), M, n, block_len,
                                       lr, mu, _stream_handle(stream)), "ddl_q4_merge_fragment")
+
+
+def q4_rda_merge_fragment(theta: torch.Tensor, v: torch.Tensor,
+                          codes: Sequence[Optional[torch.Tensor]],
+                          scales: Sequence[Optional[torch.Tensor]], token_counts, quorum_mask,
+                          block_len: int, group_len: int, lr: float, mu: float,
+                          workspace: torch.Tensor, stream=None) -> None:
+    """ddl_q4_rda_merge_fragment: q4_merge_fragment with radial-directional averaging as the
+    merge, one norm per ``group_len`` elements; ``workspace`` as for rda_merge_fragment."""
+    n = theta.numel()
+    if v.numel() != n:
+        raise ValueError("theta and v differ in size")
+    ctab, stab, M = _q4_tables(codes, scales, n, block_len)
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise TypeError("workspace must be a contiguous device tensor")
+    _check(_lib.ddl_q4_rda_merge_fragment(
+        _state_ptr(theta, "theta"), _state_ptr(v, "v"), ctab, stab, _u64(token_counts, M),
+        _u8(quorum_mask, M), M, n, block_len, group_len, lr, mu, workspace.data_ptr(),
+        workspace.numel() * workspace.element_size(), _stream_handle(stream)),
+        "ddl_q4_rda_merge_fragment")
 
 
 def merge_fragment_weighted(theta: torch.Tensor, v: torch.Tensor,
@@ -579,6 +611,20 @@ class Plan:
         arr, count, _keep = syncs
         _check(_lib.ddl_plan_q4_merge(self._h, arr, count, _stream_handle(stream)),
                "ddl_plan_q4_merge")
+
+    def q4_rda_merge(self, syncs, workspace: Optional[torch.Tensor], stream=None) -> None:
+        """ddl_plan_q4_rda_merge: ``rda_merge`` from the learners' 4-bit outer gradients."""
+        if not (isinstance(syncs, tuple) and len(syncs) == 3 and isinstance(syncs[1], int)):
+            syncs = self.prepare(syncs)
+        arr, count, _keep = syncs
+        if workspace is None:
+            ptr, nbytes = None, 0
+        else:
+            if not workspace.is_cuda or not workspace.is_contiguous():
+                raise TypeError("workspace must be a contiguous device tensor")
+            ptr, nbytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+        _check(_lib.ddl_plan_q4_rda_merge(self._h, arr, count, ptr, nbytes,
+                                          _stream_handle(stream)), "ddl_plan_q4_rda_merge")
 
     def destroy(self) -> None:
         if self._h:

@@ -115,6 +115,7 @@ struct ddl_plan {
     DdlRdaPlan* rda = nullptr;
     // 4-bit sources (ddl_plan_set_q4_sources): DdlQ4Desc per descriptor, on the device
     void* d_q4 = nullptr;
+    std::vector<DdlQ4Desc> q4_host;  // the same table on the host
     uint32_t q4_block_len = 0;
     std::vector<uint32_t> q4_nonnull_bits;  // per fragment: learners with codes and scales in
                                             // every tensor

@@ -269,6 +269,7 @@ extern "C" ddl_status ddl_plan_set_q4_sources(ddl_plan* plan, const ddl_q4_segme
     }
     if (plan->d_q4) (void)hipFree(plan->d_q4);
     plan->d_q4 = dev;
+    plan->q4_host = table;
     plan->q4_block_len = (uint32_t)block_len;
     plan->q4_nonnull_bits = nonnull;
     return DDL_OK;

@@ -7,6 +7,13 @@
 //     u     = sum_j (w_j / N_j) d_j       mean unit direction (learners with N_j = 0 left out)
 //     Delta = R * u / ||u||               (0 if u = 0)
 //
+// The learners' data are their copies theta_j of the tensor (fp32 or bf16), or -- the outer
+// gradients having been compressed for the wire (Appendix D.3) -- the d_j themselves as 4-bit
+// codes with block scales, d_j = scale * code: every kernel here is instantiated for the three
+// kinds (the 4-bit form then reads neither Theta nor v in the sweeps that only reduce, gets a
+// group-of-four's sum of squares from one 4-bit dot-product instruction, and folds the block's
+// scale into the direction coefficient).
+//
 // Two launch shapes.
 // (a) Groups of moderate length (a row of a weight matrix) and many of them: ONE kernel, one
 //     workgroup per group, which makes the three sweeps below over its own group back to back
@@ -53,6 +60,9 @@
 #ifndef DDL_RDA_V_EARLY
 #define DDL_RDA_V_EARLY 0  // 1: the row kernels load v with the first sweep instead of the last
 #endif
+#ifndef DDL_RDA_Q4_V_EARLY
+#define DDL_RDA_Q4_V_EARLY 0  // the same for the row kernels on 4-bit outer gradients only
+#endif
 #ifndef DDL_RDA_GRAM_LOAD
 #define DDL_RDA_GRAM_LOAD 0  // load form of the Gram sweep (see ld<>): 0 cached, so that the apply
                              // sweep of a tensor that fits the last-level cache finds it there
@@ -64,7 +74,11 @@
 struct DdlRdaArgs {
     uint64_t theta, v;          // device addresses
     uint64_t theta_bf16;        // optional bf16 copy of the new Theta (0: none)
-    uint64_t learner[DDL_MAXL]; // compacted: contributing learners only
+    uint64_t learner[DDL_MAXL]; // compacted: contributing learners only (their copies of the
+                                // tensor, or, for 4-bit outer gradients, their codes)
+    uint64_t scales[DDL_MAXL];  // 4-bit outer gradients: their block scales
+    uint32_t block_len;         // ... and the block length (block_shift: log2 of it, or
+    uint32_t block_shift;       // 0xffffffff if it is no power of two)
     float w[DDL_MAXL];          // their normalised weights
     uint64_t n, group_len;
     uint32_t chunks_per_group;
@@ -162,18 +176,35 @@ __device__ __forceinline__ u32x2 pack_bf16(const float (&t4)[4])
     return p;
 }
 
+// Byte offset of element e in a learner's array (4-bit codes: two elements per byte, e even).
+template <typename L>
+__device__ __forceinline__ uint64_t learner_offset(uint64_t e)
+{
+    return IsQ4<L>::value ? e / 2 : e * sizeof(typename L::elem);
+}
+
+// Number of the scale block that holds element e (4-bit outer gradients).
+__device__ __forceinline__ uint64_t q4_block_of(uint64_t e, uint32_t block_len, uint32_t block_shift)
+{
+    return block_shift != 0xffffffffu ? e >> block_shift : e / block_len;
+}
+
 // Walks the chunk: F(d[MQ], theta, v, element index within the chunk, is the first argument
-// pack a vector of 4).  VEC path: groups of four per lane; else element-wise.
+// pack a vector of 4).  VEC path: groups of four per lane; else element-wise.  d is the outer
+// gradient: Theta - theta_j, or, for 4-bit outer gradients, scale * code (Theta is then loaded
+// only where v is: the reducing sweeps of that kind read neither).
 template <typename L, int MQ, int NT, typename F4, typename F1>
 __device__ __forceinline__ void sweep_chunk(const DdlRdaArgs& a, uint64_t begin, uint64_t end,
                                             bool need_v, F4&& f4, F1&& f1)
 {
     typedef typename L::elem elem;
+    constexpr bool Q4 = IsQ4<L>::value;
+    const bool need_t = !Q4 || need_v;
     const uint32_t len = (uint32_t)(end - begin);
     const uint64_t th = a.theta + begin * 4, vv = a.v + begin * 4;
     uint64_t lp[MQ];
 #pragma unroll
-    for (int j = 0; j < MQ; ++j) lp[j] = a.learner[j] + begin * sizeof(elem);
+    for (int j = 0; j < MQ; ++j) lp[j] = a.learner[j] + learner_offset<L>(begin);
     uint32_t done = 0;
     if (a.vec_ok) {
         const uint32_t nvec = len / 4;
@@ -181,7 +212,15 @@ __device__ __forceinline__ void sweep_chunk(const DdlRdaArgs& a, uint64_t begin,
             typename L::raw raw[MQ];
 #pragma unroll
             for (int j = 0; j < MQ; ++j) raw[j] = ld<typename L::raw, NT>(lp[j], g);
-            const f32x4 T = ld<f32x4, NT>(th, g);
+            float scl[MQ];
+            if constexpr (Q4) {  // a group of four lies in one block (block_len % 4 == 0)
+                const uint64_t blk = q4_block_of(begin + 4ull * g, a.block_len, a.block_shift);
+#pragma unroll
+                for (int j = 0; j < MQ; ++j)
+                    scl[j] = reinterpret_cast<const DDL_GLOBAL float*>(a.scales[j])[blk];
+            }
+            f32x4 T = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (need_t) T = ld<f32x4, NT>(th, g);
             f32x4 V = {0.0f, 0.0f, 0.0f, 0.0f};
             if (need_v) V = ld<f32x4, NT>(vv, g);
             float x[MQ][4];
@@ -192,19 +231,36 @@ __device__ __forceinline__ void sweep_chunk(const DdlRdaArgs& a, uint64_t begin,
 #pragma unroll
             for (int k = 0; k < 4; ++k)
 #pragma unroll
-                for (int j = 0; j < MQ; ++j) d[k][j] = t4[k] - x[j][k];
+                for (int j = 0; j < MQ; ++j) {
+                    if constexpr (Q4)
+                        d[k][j] = scl[j] * x[j][k];
+                    else
+                        d[k][j] = t4[k] - x[j][k];
+                }
             f4(d, T, V, g);
         }
         done = nvec * 4;
     }
     for (uint32_t e = done + threadIdx.x; e < len; e += DDL_BLOCK) {
-        const float t = *(reinterpret_cast<const DDL_GLOBAL float*>(th) + e);
+        float t = 0.0f;
+        if (need_t) t = *(reinterpret_cast<const DDL_GLOBAL float*>(th) + e);
         float v = 0.0f;
         if (need_v) v = *(reinterpret_cast<const DDL_GLOBAL float*>(vv) + e);
         float d[MQ];
+        if constexpr (Q4) {  // by absolute element number: the chunk may start at an odd one
+            const uint64_t i = begin + e;
+            const uint64_t blk = q4_block_of(i, a.block_len, a.block_shift);
 #pragma unroll
-        for (int j = 0; j < MQ; ++j)
-            d[j] = t - L::widen1(*(reinterpret_cast<const DDL_GLOBAL elem*>(lp[j]) + e));
+            for (int j = 0; j < MQ; ++j) {
+                const uint32_t byte = reinterpret_cast<const DDL_GLOBAL uint8_t*>(a.learner[j])[i >> 1];
+                d[j] = reinterpret_cast<const DDL_GLOBAL float*>(a.scales[j])[blk] *
+                       LearnerQ4::nibble(byte, (int)(i & 1));
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < MQ; ++j)
+                d[j] = t - L::widen1(*(reinterpret_cast<const DDL_GLOBAL elem*>(lp[j]) + e));
+        }
         f1(d, t, v, e);
     }
 }
@@ -609,6 +665,9 @@ struct DdlRdaLongArgs {
     float lr, mu;
     float w[DDL_MAXL];          // normalised weights of the contributing learners, compacted
     uint8_t idx[DDL_MAXL];      // learner index of compacted entry j
+    // 4-bit outer gradients only: the table parallel to segs, and the block length of the scales
+    const DdlQ4Desc* q4;
+    uint32_t block_len, block_shift;
 };
 
 // The tensor that holds chunk (or group) b of the launch, as the arguments the one-tensor
@@ -617,7 +676,6 @@ template <typename L, int MQ>
 __device__ __forceinline__ void long_locate(const DdlRdaLongArgs& m, uint32_t b, DdlRdaArgs& a,
                                             uint32_t& local)
 {
-    typedef typename L::elem elem;
     const DDL_CONST DdlRdaLongRef* refs =
         reinterpret_cast<const DDL_CONST DdlRdaLongRef*>(reinterpret_cast<uint64_t>(m.refs));
     uint32_t lo = 0, hi = m.num_refs - 1;  // last entry whose begin <= b
@@ -633,11 +691,25 @@ __device__ __forceinline__ void long_locate(const DdlRdaLongArgs& m, uint32_t b,
     a.theta = uniform(reinterpret_cast<uint64_t>(sp->theta));
     a.v = uniform(reinterpret_cast<uint64_t>(sp->v));
     a.theta_bf16 = uniform(reinterpret_cast<uint64_t>(sp->theta_bf16));
+    if constexpr (IsQ4<L>::value) {
+        const DDL_CONST DdlQ4Desc* qp =
+            reinterpret_cast<const DDL_CONST DdlQ4Desc*>(reinterpret_cast<uint64_t>(m.q4)) +
+            ref->seg;
 #pragma unroll
-    for (int j = 0; j < MQ; ++j) {
-        a.learner[j] = uniform(reinterpret_cast<uint64_t>(sp->learner[m.idx[j]]));
-        a.w[j] = m.w[j];
+        for (int j = 0; j < MQ; ++j) {
+            a.learner[j] = uniform(reinterpret_cast<uint64_t>(qp->codes[m.idx[j]]));
+            a.scales[j] = uniform(reinterpret_cast<uint64_t>(qp->scales[m.idx[j]]));
+            a.w[j] = m.w[j];
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < MQ; ++j) {
+            a.learner[j] = uniform(reinterpret_cast<uint64_t>(sp->learner[m.idx[j]]));
+            a.w[j] = m.w[j];
+        }
     }
+    a.block_len = m.block_len;
+    a.block_shift = m.block_shift;
     a.n = sp->n;
     a.group_len = ref->group_len;
     a.chunks_per_group = ref->chunks_per_group;
@@ -649,7 +721,6 @@ __device__ __forceinline__ void long_locate(const DdlRdaLongArgs& m, uint32_t b,
     a.mean_norm = m.workspace + ref->off_mean;
     a.partial2 = 0;
     a.scale = m.workspace + ref->off_scale;
-    (void)sizeof(elem);
 }
 
 template <typename L, int MQ>
@@ -785,6 +856,29 @@ __device__ __forceinline__ void launder(u32x4& r)
 {
     asm volatile("" : "+v"(r.x), "+v"(r.y), "+v"(r.z), "+v"(r.w));
 }
+__device__ __forceinline__ void launder(uint32_t& r) { asm volatile("" : "+v"(r)); }
+
+// Whether the row kernels load v with everything else (one memory round trip fewer per row,
+// four more registers per group held through the sweeps) or only before the last sweep.
+template <typename L>
+constexpr bool row_loads_v_early()
+{
+    return DDL_RDA_V_EARLY || (IsQ4<L>::value && DDL_RDA_Q4_V_EARLY);
+}
+
+// What a lane of the row kernel keeps of a learner's four elements: the packed values as
+// loaded, or -- 4-bit outer gradients -- the four codes in one register (their block's scale
+// sits in a second one).
+template <typename L> struct RowRaw { typedef typename L::raw type; };
+template <> struct RowRaw<LearnerQ4> { typedef uint32_t type; };
+
+// Where a row's learner data lies beyond lp: 4-bit outer gradients only.
+template <int MQ>
+struct RowScales {
+    uint64_t sc[MQ];       // the tensor's block scales per contributing learner
+    uint64_t first;        // element number of the row's first element within the tensor
+    uint32_t block_len, block_shift;
+};
 
 // Launch shape (a'), for groups of at most K * 4 * NTH elements on the aligned path: the
 // workgroup loads its whole group ONCE into registers (learner values stay packed as loaded)
@@ -793,42 +887,61 @@ __device__ __forceinline__ void launder(u32x4& r)
 // Theta, 0 if none); nvec: its length in groups of four.
 template <typename L, int MQ, int K, int NTH>
 __device__ __forceinline__ void rda_row_body(uint64_t th, uint64_t vv, uint64_t tb,
-                                             const uint64_t (&lp)[MQ],
+                                             const uint64_t (&lp)[MQ], const RowScales<MQ>& rs,
                                              const float (&w)[MQ], uint32_t nvec, float lr,
                                              float mu, float* lds /* NTH / 64 * MQ floats */)
 {
-    typename L::raw raw[K][MQ];
+    constexpr bool Q4 = IsQ4<L>::value;
+    typedef typename RowRaw<L>::type raw_t;
+    raw_t raw[K][MQ];
+    float scl[Q4 ? K : 1][MQ];  // 4-bit outer gradients: the block scale of each group of four
     f32x4 T[K];
-#if DDL_RDA_V_EARLY
     f32x4 V[K];
-#endif
+    constexpr bool V_EARLY = row_loads_v_early<L>();
 #pragma unroll
     for (int u = 0; u < K; ++u) {
         const uint32_t g = threadIdx.x + u * NTH;
-#if DDL_RDA_V_EARLY
-        V[u] = g < nvec ? ld<f32x4, DDL_NT_LOAD>(vv, g) : f32x4(0.0f);
-#endif
+        if constexpr (V_EARLY) V[u] = g < nvec ? ld<f32x4, DDL_NT_LOAD>(vv, g) : f32x4(0.0f);
         if (g < nvec) {
 #pragma unroll
             for (int j = 0; j < MQ; ++j) raw[u][j] = ld<typename L::raw, DDL_NT_LOAD>(lp[j], g);
+            if constexpr (Q4) {
+                const uint64_t blk = q4_block_of(rs.first + 4ull * g, rs.block_len, rs.block_shift);
+#pragma unroll
+                for (int j = 0; j < MQ; ++j)
+                    scl[u][j] = reinterpret_cast<const DDL_GLOBAL float*>(rs.sc[j])[blk];
+            }
             T[u] = ld<f32x4, DDL_NT_LOAD>(th, g);
         } else {  // lanes past the end of the group hold a zero outer gradient
 #pragma unroll
-            for (int j = 0; j < MQ; ++j) raw[u][j] = typename L::raw(0);
+            for (int j = 0; j < MQ; ++j) raw[u][j] = raw_t(0);
+            if constexpr (Q4) {
+#pragma unroll
+                for (int j = 0; j < MQ; ++j) scl[u][j] = 0.0f;
+            }
             T[u] = f32x4(0.0f);
         }
     }
+    (void)scl;
 
     // outer gradients of group u, element k, recomputed from the packed registers on demand
     auto diffs = [&](int u, float (&d)[4][MQ]) {
-        float x[MQ][4];
+        if constexpr (Q4) {
 #pragma unroll
-        for (int j = 0; j < MQ; ++j) L::widen(raw[u][j], x[j]);
-        const float t4[4] = {T[u].x, T[u].y, T[u].z, T[u].w};
+            for (int k = 0; k < 4; ++k)
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
+                for (int j = 0; j < MQ; ++j)
+                    d[k][j] = scl[u][j] * LearnerQ4::nibble(raw[u][j], k);
+        } else {
+            float x[MQ][4];
 #pragma unroll
-            for (int j = 0; j < MQ; ++j) d[k][j] = t4[k] - x[j][k];
+            for (int j = 0; j < MQ; ++j) L::widen(raw[u][j], x[j]);
+            const float t4[4] = {T[u].x, T[u].y, T[u].z, T[u].w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int j = 0; j < MQ; ++j) d[k][j] = t4[k] - x[j][k];
+        }
     };
 
     // Sweep 1: the learners' norms over the group.  (DDL_RDA_DIAG_NO_SWEEPS is a measurement
@@ -846,12 +959,23 @@ __device__ __forceinline__ void rda_row_body(uint64_t th, uint64_t vv, uint64_t 
     for (int j = 0; j < MQ; ++j) ss[j] = 0.0f;
 #pragma unroll
     for (int u = 0; u < K; ++u) {
-        float d[4][MQ];
-        diffs(u, d);
+        if constexpr (Q4) {
+            // sum of (scale * code)^2 over the four codes = scale^2 times the sum of the squared
+            // codes, which one 4-bit dot-product instruction gives exactly (the upper four
+            // nibbles of the register are zero)
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
+            for (int j = 0; j < MQ; ++j) {
+                const int sq = __builtin_amdgcn_sdot8((int)raw[u][j], (int)raw[u][j], 0, false);
+                ss[j] = fmaf(scl[u][j] * scl[u][j], (float)sq, ss[j]);
+            }
+        } else {
+            float d[4][MQ];
+            diffs(u, d);
 #pragma unroll
-            for (int j = 0; j < MQ; ++j) ss[j] = fmaf(d[k][j], d[k][j], ss[j]);
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int j = 0; j < MQ; ++j) ss[j] = fmaf(d[k][j], d[k][j], ss[j]);
+        }
     }
     float R = 0.0f;
     block_sum_all<NTH, MQ>(ss, lds);
@@ -873,14 +997,26 @@ __device__ __forceinline__ void rda_row_body(uint64_t th, uint64_t vv, uint64_t 
     float uu = 0.0f;
 #pragma unroll
     for (int u = 0; u < K; ++u) {
-        float d[4][MQ];
-        diffs(u, d);
         float x[4];
+        if constexpr (Q4) {  // the block's scale goes into the coefficient, once per group
+            float cs[MQ];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            x[k] = direction<MQ>(d[k], c);
-            uu = fmaf(x[k], x[k], uu);
+            for (int j = 0; j < MQ; ++j) cs[j] = c[j] * scl[u][j];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                x[k] = 0.0f;
+#pragma unroll
+                for (int j = 0; j < MQ; ++j)
+                    x[k] = fmaf(cs[j], LearnerQ4::nibble(raw[u][j], k), x[k]);
+            }
+        } else {
+            float d[4][MQ];
+            diffs(u, d);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) x[k] = direction<MQ>(d[k], c);
         }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) uu = fmaf(x[k], x[k], uu);
         dir[u] = f32x4{x[0], x[1], x[2], x[3]};
     }
 #ifndef DDL_RDA_DIAG_NO_SWEEPS
@@ -893,14 +1029,13 @@ __device__ __forceinline__ void rda_row_body(uint64_t th, uint64_t vv, uint64_t 
 #endif
 
     // Sweep 3: Delta = scale * u, outer step.
-#if !DDL_RDA_V_EARLY
-    f32x4 V[K];
+    if constexpr (!V_EARLY) {
 #pragma unroll
-    for (int u = 0; u < K; ++u) {
-        const uint32_t g = threadIdx.x + u * NTH;
-        V[u] = g < nvec ? ld<f32x4, DDL_NT_LOAD>(vv, g) : f32x4(0.0f);
+        for (int u = 0; u < K; ++u) {
+            const uint32_t g = threadIdx.x + u * NTH;
+            V[u] = g < nvec ? ld<f32x4, DDL_NT_LOAD>(vv, g) : f32x4(0.0f);
+        }
     }
-#endif
 #pragma unroll
     for (int u = 0; u < K; ++u) {
         const uint32_t g = threadIdx.x + u * NTH;
@@ -928,20 +1063,24 @@ template <typename L, int MQ, int K, int NTH>
 __global__ void __launch_bounds__(NTH) rda_row_kernel(const DdlRdaArgs a)
 {
     __shared__ float lds[NTH / 64 * MQ];
-    typedef typename L::elem elem;
     const uint64_t g0 = (uint64_t)blockIdx.x * a.group_len;
     const uint64_t g1 = a.n - g0 < a.group_len ? a.n : g0 + a.group_len;
     const uint32_t nvec = (uint32_t)(g1 - g0) / 4;  // the host sends only multiples of four here
     uint64_t lp[MQ];
     float w[MQ];
+    RowScales<MQ> rs;
+    rs.first = g0;
+    rs.block_len = a.block_len;
+    rs.block_shift = a.block_shift;
 #pragma unroll
     for (int j = 0; j < MQ; ++j) {
-        lp[j] = a.learner[j] + g0 * sizeof(elem);
+        lp[j] = a.learner[j] + learner_offset<L>(g0);
+        rs.sc[j] = a.scales[j];
         w[j] = a.w[j];
     }
     rda_row_body<L, MQ, K, NTH>(a.theta + g0 * 4, a.v + g0 * 4,
-                                a.theta_bf16 ? a.theta_bf16 + g0 * 2 : 0, lp, w, nvec, a.lr, a.mu,
-                                lds);
+                                a.theta_bf16 ? a.theta_bf16 + g0 * 2 : 0, lp, rs, w, nvec, a.lr,
+                                a.mu, lds);
 }
 
 // Many tensors of one fragment in one launch: workgroup b takes row b of the concatenation
@@ -964,13 +1103,15 @@ struct DdlRdaRowsArgs {
     float lr, mu;
     float w[DDL_MAXL];      // normalised weights of the contributing learners, compacted
     uint8_t idx[DDL_MAXL];  // learner index of compacted entry j
+    // 4-bit outer gradients only: the table parallel to segs, and the block length of the scales
+    const DdlQ4Desc* q4;
+    uint32_t block_len, block_shift;
 };
 
 template <typename L, int MQ, int K, int NTH>
 __global__ void __launch_bounds__(NTH) rda_rows_kernel(const DdlRdaRowsArgs a)
 {
     __shared__ float lds[NTH / 64 * MQ];
-    typedef typename L::elem elem;
     const uint32_t r = a.row_base + blockIdx.x;
     const DDL_CONST DdlRdaRowRef* refs =
         reinterpret_cast<const DDL_CONST DdlRdaRowRef*>(reinterpret_cast<uint64_t>(a.refs));
@@ -997,12 +1138,30 @@ __global__ void __launch_bounds__(NTH) rda_rows_kernel(const DdlRdaRowsArgs a)
     const uint64_t tb = uniform(tb0 ? tb0 + g0 * 2 : 0);
     uint64_t lp[MQ];
     float w[MQ];
+    RowScales<MQ> rs;
+    rs.first = g0;
+    rs.block_len = a.block_len;
+    rs.block_shift = a.block_shift;
+    if constexpr (IsQ4<L>::value) {
+        const DDL_CONST DdlQ4Desc* qp =
+            reinterpret_cast<const DDL_CONST DdlQ4Desc*>(reinterpret_cast<uint64_t>(a.q4)) +
+            ref->seg;
 #pragma unroll
-    for (int j = 0; j < MQ; ++j) {
-        lp[j] = uniform(reinterpret_cast<uint64_t>(sp->learner[a.idx[j]]) + g0 * sizeof(elem));
-        w[j] = a.w[j];
+        for (int j = 0; j < MQ; ++j) {
+            lp[j] = uniform(reinterpret_cast<uint64_t>(qp->codes[a.idx[j]]) + g0 / 2);
+            rs.sc[j] = uniform(reinterpret_cast<uint64_t>(qp->scales[a.idx[j]]));
+            w[j] = a.w[j];
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < MQ; ++j) {
+            lp[j] = uniform(reinterpret_cast<uint64_t>(sp->learner[a.idx[j]]) +
+                            learner_offset<L>(g0));
+            rs.sc[j] = 0;
+            w[j] = a.w[j];
+        }
     }
-    rda_row_body<L, MQ, K, NTH>(th, vv, tb, lp, w, nvec, a.lr, a.mu, lds);
+    rda_row_body<L, MQ, K, NTH>(th, vv, tb, lp, rs, w, nvec, a.lr, a.mu, lds);
 }
 
 // Registers the row kernel keeps per lane: K groups of (packed learners + Theta + v), plus
@@ -1013,9 +1172,10 @@ __global__ void __launch_bounds__(NTH) rda_rows_kernel(const DdlRdaRowsArgs a)
 template <typename L, int MQ, int K, int NTH>
 constexpr bool row_kernel_fits()
 {
-    const int words = (int)(sizeof(typename L::raw) / 4) * MQ;  // packed learner words per slot
+    // packed learner words per slot (4-bit outer gradients: the codes and the block's scale)
+    const int words = (IsQ4<L>::value ? 2 : (int)(sizeof(typename L::raw) / 4)) * MQ;
     if (NTH > 512) return words <= (K >= 4 ? 12 : K == 2 ? 16 : 24);
-    return K * (words + 8) <= (DDL_RDA_V_EARLY ? 184 : 192);  // v held through the sweeps
+    return K * (words + 8) <= (row_loads_v_early<L>() ? 184 : 192);  // v held through the sweeps
 }
 
 typedef void (*rda_fn)(const DdlRdaArgs);
@@ -1118,13 +1278,20 @@ void pick(int Mq, int cls, Kernels& k)
     }
 }
 
-void pick(ddl_dtype dt, int Mq, int cls, Kernels& k)
+// src: what the learners' data is -- 0 fp32, 1 bf16 copies of the tensor (values of ddl_dtype),
+// DDL_SRC_Q4: their outer gradients as 4-bit codes with block scales.
+void pick(int src, int Mq, int cls, Kernels& k)
 {
-    if (dt == DDL_F32)
+    if (src == (int)DDL_F32)
         pick<LearnerF32>(Mq, cls, k);
-    else
+    else if (src == (int)DDL_BF16)
         pick<LearnerBF16>(Mq, cls, k);
+    else
+        pick<LearnerQ4>(Mq, cls, k);
 }
+
+// Bytes per learner element as the launch-shape choices of the merge kernels count them.
+int src_elem_bytes(int src) { return src == DDL_SRC_Q4 ? 0 : src == (int)DDL_BF16 ? 2 : 4; }
 
 struct Geometry {
     uint64_t groups, chunks_per_group, chunks;
@@ -1181,7 +1348,7 @@ uint32_t row_lds_cap()
 // Enqueues the RDA merge of ONE tensor.  `a` holds the tensor, the compacted learners and
 // weights, n, group_len (already clamped to n), vec_ok, lr and mu; the workspace fields are
 // filled in here.  g = geometry(n, group_len, Mq).
-ddl_status launch_one(ddl_dtype dt, int Mq, DdlRdaArgs& a, const Geometry& g, void* workspace,
+ddl_status launch_one(int src, int Mq, DdlRdaArgs& a, const Geometry& g, void* workspace,
                       hipStream_t stream)
 {
     a.chunks_per_group = (uint32_t)g.chunks_per_group;
@@ -1194,7 +1361,7 @@ ddl_status launch_one(ddl_dtype dt, int Mq, DdlRdaArgs& a, const Geometry& g, vo
 
     const int cls = row_class_for(a.group_len);
     Kernels k;
-    pick(dt, Mq, cls, k);
+    pick(src, Mq, cls, k);
     if (!k.sumsq) return DDL_ERR_INVALID_ARG;
     const dim3 block(DDL_BLOCK);
     const uint32_t groups = (uint32_t)g.groups;
@@ -1226,7 +1393,7 @@ ddl_status launch_one(ddl_dtype dt, int Mq, DdlRdaArgs& a, const Geometry& g, vo
         a.piece_shift = g.chunks <= (0x7fffffffu >> kLongApplyPieceShift) ? kLongApplyPieceShift : 0;
         DDL_COUNT_GRID();
         hipLaunchKernelGGL(k.apply, dim3((uint32_t)g.chunks << a.piece_shift), block,
-                           ddlh::merge_lds_cap_bytes(dt == DDL_BF16 ? 2 : 4, Mq), stream, a);
+                           ddlh::merge_lds_cap_bytes(src_elem_bytes(src), Mq), stream, a);
     }
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? DDL_OK : ddlh::runtime_error(e, "RDA kernel launch");
@@ -1323,7 +1490,8 @@ ddl_status rda_merge_one(float* theta, float* v, const void* const* learner_para
     a.vec_ok = vec_ok ? 1u : 0u;
     a.lr = lr;
     a.mu = mu;
-    return launch_one(learner_dtype, Mq, a, g, workspace, static_cast<hipStream_t>(hip_stream));
+    return launch_one((int)learner_dtype, Mq, a, g, workspace,
+                      static_cast<hipStream_t>(hip_stream));
 }
 
 }  // namespace
@@ -1338,6 +1506,79 @@ extern "C" ddl_status ddl_rda_merge_fragment(float* theta, float* v,
     return rda_merge_one(theta, v, learner_params, learner_dtype, token_counts, quorum_mask, M, n,
                          group_len, lr, mu, workspace, workspace_bytes, false,
                          "ddl_rda_merge_fragment", hip_stream);
+}
+
+namespace {
+
+uint32_t log2_or_none(uint32_t x)  // log2 of a power of two, else 0xffffffff
+{
+    if (x == 0 || (x & (x - 1))) return 0xffffffffu;
+    uint32_t sh = 0;
+    while ((1u << sh) < x) ++sh;
+    return sh;
+}
+
+bool q4_block_len_ok(size_t block_len)
+{
+    return block_len >= 8 && block_len % 8 == 0 && block_len <= 0x40000000u;
+}
+
+}  // namespace
+
+// RDA as the merge of 4-bit outer gradients, one tensor: the kernels above instantiated for
+// codes and block scales as the learners' data.
+extern "C" ddl_status ddl_q4_rda_merge_fragment(float* theta, float* v,
+                                                const uint8_t* const* codes,
+                                                const float* const* scales,
+                                                const uint64_t* token_counts,
+                                                const uint8_t* quorum_mask, int M, size_t n,
+                                                size_t block_len, size_t group_len, float lr,
+                                                float mu, void* workspace, size_t workspace_bytes,
+                                                void* hip_stream)
+{
+    double w[DDL_MAX_LEARNERS];
+    const ddl_status st = ddl_compute_weights(token_counts, quorum_mask, M, w);
+    if (st != DDL_OK) return st;
+    if (!ddlh::finite_nonneg(lr) || !ddlh::finite_nonneg(mu)) return DDL_ERR_INVALID_ARG;
+    if (!q4_block_len_ok(block_len) || group_len == 0) return DDL_ERR_INVALID_ARG;
+    if (n == 0) return DDL_OK;
+    if (!theta || !v || !codes || !scales || !aligned(theta, 16) || !aligned(v, 16))
+        return DDL_ERR_INVALID_ARG;
+    const uint64_t blocks = (n + block_len - 1) / block_len;
+    ddlh::Quorum q;
+    ddlh::compact(w, M, q);
+    DdlRdaArgs a;
+    std::memset(&a, 0, sizeof a);
+    std::vector<ddlh::Range> r;
+    if (!ddlh::add_range(theta, 4, n, true, r) || !ddlh::add_range(v, 4, n, true, r))
+        return DDL_ERR_INVALID_ARG;
+    for (int j = 0; j < q.Mq; ++j) {
+        const uint8_t* c = codes[q.idx[j]];
+        const float* sc = scales[q.idx[j]];
+        if (!c || !sc || !aligned(c, 4) || !aligned(sc, 4) ||
+            !ddlh::add_range(c, 1, (n + 1) / 2, false, r) ||
+            !ddlh::add_range(sc, 4, blocks, false, r))
+            return DDL_ERR_INVALID_ARG;
+        a.learner[j] = (uint64_t)(uintptr_t)c;
+        a.scales[j] = (uint64_t)(uintptr_t)sc;
+        a.w[j] = q.w[j];
+    }
+    Geometry g;
+    if (!geometry(n, group_len, q.Mq, g)) return DDL_ERR_INVALID_ARG;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < g.bytes)
+        return DDL_ERR_INVALID_ARG;
+    if (!ddlh::add_range(workspace, 1, g.bytes, true, r)) return DDL_ERR_INVALID_ARG;
+    if (ddlh::ranges_alias(r)) return DDL_ERR_ALIAS;
+    a.theta = (uint64_t)(uintptr_t)theta;
+    a.v = (uint64_t)(uintptr_t)v;
+    a.n = n;
+    a.group_len = std::min<uint64_t>(group_len, n);
+    a.vec_ok = a.group_len % 4 == 0 ? 1u : 0u;  // Theta and v are aligned, codes 4-byte aligned
+    a.block_len = (uint32_t)block_len;
+    a.block_shift = log2_or_none((uint32_t)block_len);
+    a.lr = lr;
+    a.mu = mu;
+    return launch_one(DDL_SRC_Q4, q.Mq, a, g, workspace, static_cast<hipStream_t>(hip_stream));
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1581,13 +1822,23 @@ extern "C" size_t ddl_plan_rda_workspace_bytes(const ddl_plan* plan)
     return plan && plan->rda ? plan->rda->workspace_bytes : 0;
 }
 
-extern "C" ddl_status ddl_plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, int count,
-                                         void* workspace, size_t workspace_bytes, void* hip_stream)
+namespace {
+
+// ddl_plan_rda_merge and ddl_plan_q4_rda_merge: the learners' data are their copies of the
+// tensors (the plan's descriptors), or -- q4 -- their outer gradients as 4-bit codes with
+// block scales (the plan's 4-bit sources).
+ddl_status plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, int count, void* workspace,
+                          size_t workspace_bytes, void* hip_stream, bool q4)
 {
     if (!plan || !plan->rda || count < 0 || (count > 0 && !syncs)) return DDL_ERR_INVALID_ARG;
+    if (q4 && (plan->q4_block_len == 0 || plan->q4_host.size() != plan->table.segs.size()))
+        return DDL_ERR_INVALID_ARG;
     if (count == 0) return DDL_OK;
     const ddlh::Table& T = plan->table;
     const DdlRdaPlan& R = *plan->rda;
+    const uint32_t block_len = q4 ? plan->q4_block_len : 0;
+    const uint32_t block_shift = log2_or_none(block_len);
+    const DdlQ4Desc* d_q4 = static_cast<const DdlQ4Desc*>(plan->d_q4);
     if (R.workspace_bytes > 0 &&
         (!workspace || !aligned(workspace, 256) || workspace_bytes < R.workspace_bytes))
         return DDL_ERR_INVALID_ARG;
@@ -1616,14 +1867,23 @@ extern "C" ddl_status ddl_plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, 
         wk.lr = s.lr;
         wk.mu = s.mu;
         ddlh::compact(w, f.M, wk.q);
-        if (f.num_segs > 0 && (wk.q.present_bits & ~f.nonnull_bits)) return DDL_ERR_INVALID_ARG;
+        const uint32_t have = q4 ? plan->q4_nonnull_bits[(size_t)s.fragment] : f.nonnull_bits;
+        if (f.num_segs > 0 && (wk.q.present_bits & ~have)) return DDL_ERR_INVALID_ARG;
         const size_t b = f.dt == DDL_BF16 ? 2 : 4;
         for (uint32_t d = f.seg_begin; d < f.seg_begin + f.num_segs; ++d) {
             const DdlSegDesc& sd = T.segs[d];
             bool hit = hits_workspace(sd.theta, 4 * sd.n) || hits_workspace(sd.v, 4 * sd.n) ||
                        hits_workspace(sd.theta_bf16, 2 * sd.n);
-            for (int j = 0; j < wk.q.Mq; ++j)
-                hit = hit || hits_workspace(sd.learner[wk.q.idx[j]], b * sd.n);
+            for (int j = 0; j < wk.q.Mq; ++j) {
+                if (q4) {
+                    const DdlQ4Desc& qd = plan->q4_host[d];
+                    hit = hit || hits_workspace(qd.codes[wk.q.idx[j]], (sd.n + 1) / 2) ||
+                          hits_workspace(qd.scales[wk.q.idx[j]],
+                                         4 * ((sd.n + block_len - 1) / block_len));
+                } else {
+                    hit = hit || hits_workspace(sd.learner[wk.q.idx[j]], b * sd.n);
+                }
+            }
             if (hit) return DDL_ERR_ALIAS;
         }
         work.push_back(wk);
@@ -1650,25 +1910,33 @@ extern "C" ddl_status ddl_plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, 
         bool vec_ok = aligned(sd.theta, 16) && aligned(sd.v, 16) && aligned(sd.theta_bf16, 8) &&
                       a.group_len % 4 == 0;
         for (int j = 0; j < wk.q.Mq; ++j) {
-            const void* p = sd.learner[wk.q.idx[j]];
-            vec_ok = vec_ok && aligned(p, 16);
-            a.learner[j] = (uint64_t)(uintptr_t)p;
+            if (q4) {  // codes and scales are 4-byte aligned (checked when they were set)
+                a.learner[j] = (uint64_t)(uintptr_t)plan->q4_host[d].codes[wk.q.idx[j]];
+                a.scales[j] = (uint64_t)(uintptr_t)plan->q4_host[d].scales[wk.q.idx[j]];
+            } else {
+                const void* p = sd.learner[wk.q.idx[j]];
+                vec_ok = vec_ok && aligned(p, 16);
+                a.learner[j] = (uint64_t)(uintptr_t)p;
+            }
             a.w[j] = wk.q.w[j];
         }
+        a.block_len = block_len;
+        a.block_shift = block_shift;
         a.vec_ok = vec_ok ? 1u : 0u;
         Geometry g;
         if (!geometry(sd.n, a.group_len, wk.q.Mq, g)) return DDL_ERR_INVALID_ARG;
-        return launch_one(f.dt, wk.q.Mq, a, g, workspace, stream);
+        return launch_one(q4 ? DDL_SRC_Q4 : (int)f.dt, wk.q.Mq, a, g, workspace, stream);
     };
 
     for (const RdaWork& wk : work) {
         const ddlh::FragInfo& f = T.frags[wk.frag];
         const DdlRdaPlan::Frag& rf = R.frags[wk.frag];
+        const int src = q4 ? DDL_SRC_Q4 : (int)f.dt;
         for (int c = 0; c < kNumRowClasses; ++c) {
             const DdlRdaPlan::Class& k = rf.cls[c];
             if (k.num_refs == 0) continue;
             Kernels fn;
-            pick(f.dt, wk.q.Mq, c, fn);
+            pick(src, wk.q.Mq, c, fn);
             const int sd_extra_bytes = 0;
             if (fn.rows) {
                 DdlRdaRowsArgs a;
@@ -1681,10 +1949,13 @@ extern "C" ddl_status ddl_plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, 
                 a.mu = wk.mu;
                 std::memcpy(a.w, wk.q.w, sizeof a.w);
                 std::memcpy(a.idx, wk.q.idx, sizeof a.idx);
+                a.q4 = d_q4;
+                a.block_len = block_len;
+                a.block_shift = block_shift;
                 // Like the direct-averaging merge, a long launch goes out as several equal
                 // grids, which keeps the XCDs aligned: the limit in elements becomes rows.
                 const uint64_t max_tiles = ddlh::max_tiles_per_launch(
-                    f.dt == DDL_BF16 ? 2 : 4, wk.q.Mq, sd_extra_bytes);
+                    src_elem_bytes(src), wk.q.Mq, sd_extra_bytes);
                 uint64_t part = k.rows;
                 if (max_tiles != 0 && k.elems > max_tiles * DDL_TILE) {
                     const uint64_t parts = (k.elems + max_tiles * DDL_TILE - 1) / (max_tiles * DDL_TILE);
@@ -1712,7 +1983,7 @@ extern "C" ddl_status ddl_plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, 
         }
         if (rf.long_count > 0) {
             Kernels fn;
-            pick(f.dt, wk.q.Mq, kNumRowClasses, fn);
+            pick(src, wk.q.Mq, kNumRowClasses, fn);
             if (fn.long_gram) {  // all these tensors in three launches
                 DdlRdaLongArgs a;
                 std::memset(&a, 0, sizeof a);
@@ -1725,10 +1996,13 @@ extern "C" ddl_status ddl_plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, 
                 a.mu = wk.mu;
                 std::memcpy(a.w, wk.q.w, sizeof a.w);
                 std::memcpy(a.idx, wk.q.idx, sizeof a.idx);
+                a.q4 = d_q4;
+                a.block_len = block_len;
+                a.block_shift = block_shift;
                 const dim3 block(DDL_BLOCK);
                 // the two sweeps go out in equal parts like the merge (a chunk is 8 tiles)
                 const uint64_t max_tiles =
-                    ddlh::max_tiles_per_launch(f.dt == DDL_BF16 ? 2 : 4, wk.q.Mq);
+                    ddlh::max_tiles_per_launch(src_elem_bytes(src), wk.q.Mq);
                 uint64_t part = rf.long_chunks;
                 const uint64_t max_chunks = max_tiles / (DDL_RDA_CHUNK / DDL_TILE);
                 if (max_tiles != 0 && max_chunks > 0 && rf.long_chunks > max_chunks) {
@@ -1760,7 +2034,7 @@ extern "C" ddl_status ddl_plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, 
                 a.piece_shift =
                     rf.long_chunks <= (0x7fffffffu >> kLongApplyPieceShift) ? kLongApplyPieceShift : 0;
                 sweep(fn.long_apply, 1u << a.piece_shift,
-                      ddlh::merge_lds_cap_bytes(f.dt == DDL_BF16 ? 2 : 4, wk.q.Mq));
+                      ddlh::merge_lds_cap_bytes(src_elem_bytes(src), wk.q.Mq));
                 const hipError_t e = hipGetLastError();
                 if (e != hipSuccess) return ddlh::runtime_error(e, "RDA long-group kernel launch");
             } else {  // more learners than the Gram form takes: tensor by tensor
@@ -1772,9 +2046,27 @@ extern "C" ddl_status ddl_plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, 
         }
         for (uint32_t d : rf.direct) {
             const ddl_status st =
-                ddlh::launch_one_direct(T.segs[d], f.dt, wk.q, wk.lr, wk.mu, hip_stream);
+                q4 ? ddlh::launch_flat(T.segs[d], DDL_SRC_Q4, wk.q, wk.lr, wk.mu, hip_stream,
+                                       &plan->q4_host[d], block_len)
+                   : ddlh::launch_one_direct(T.segs[d], f.dt, wk.q, wk.lr, wk.mu, hip_stream);
             if (st != DDL_OK) return st;
         }
     }
     return DDL_OK;
+}
+
+}  // namespace
+
+extern "C" ddl_status ddl_plan_rda_merge(ddl_plan* plan, const ddl_sync* syncs, int count,
+                                         void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return plan_rda_merge(plan, syncs, count, workspace, workspace_bytes, hip_stream, false);
+}
+
+// The same with the plan's 4-bit sources (ddl_plan_set_q4_sources) as the learners' data.
+extern "C" ddl_status ddl_plan_q4_rda_merge(ddl_plan* plan, const ddl_sync* syncs, int count,
+                                            void* workspace, size_t workspace_bytes,
+                                            void* hip_stream)
+{
+    return plan_rda_merge(plan, syncs, count, workspace, workspace_bytes, hip_stream, true);
 }

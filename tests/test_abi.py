@@ -177,6 +177,24 @@ def test_argument_errors_of_the_other_entry_points_need_no_device(ddl):
     assert ex(count=0) == ddl.DDL_OK
     assert ex(delta=None, count=0) == ddl.DDL_OK
 
+    # RDA on 4-bit outer gradients
+    codes = (ctypes.c_void_p * M)(0x10000000, 0x20000000)
+    scl = (ctypes.c_void_p * M)(0x30000000, 0x38000000)
+
+    def q4rda(mask=ones, g=64, B=64, work=ws, work_bytes=1 << 20, theta=th, ctab=codes):
+        return lib.ddl_q4_rda_merge_fragment(theta, v, ctab, scl, tok, mask, M, n, B, g, 0.7, 0.9,
+                                             work, work_bytes, None)
+
+    assert q4rda(mask=zeros) == ddl.DDL_ERR_EMPTY_QUORUM
+    assert q4rda(g=0) == ddl.DDL_ERR_INVALID_ARG
+    assert q4rda(B=12) == ddl.DDL_ERR_INVALID_ARG                                  # not a multiple of 8
+    assert q4rda(work=None) == ddl.DDL_ERR_INVALID_ARG
+    assert q4rda(work_bytes=16) == ddl.DDL_ERR_INVALID_ARG
+    assert q4rda(theta=ctypes.c_void_p(0x40000004)) == ddl.DDL_ERR_INVALID_ARG     # 16-byte alignment
+    assert q4rda(ctab=(ctypes.c_void_p * M)(0x10000000, None)) == ddl.DDL_ERR_INVALID_ARG
+    assert q4rda(work=ctypes.c_void_p(0x10000000)) == ddl.DDL_ERR_ALIAS            # on the codes
+    assert lib.ddl_plan_q4_rda_merge(None, None, 0, None, 0, None) == ddl.DDL_ERR_INVALID_ARG
+
     # the form on the library's own scratch: argument errors and the size refusal need no device
     def rda_static(mask=ones, g=64, theta=th, count=n, lr=0.7):
         return lib.ddl_rda_merge_fragment_static(theta, v, table, ddl.DDL_BF16, tok, mask, M,
