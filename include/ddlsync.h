@@ -354,8 +354,8 @@ DDL_API size_t ddl_plan_num_elements(const ddl_plan* plan);
  * Radial-directional averaging (Appendix D.2; see ddl_rda_merge_fragment for the formula and
  * the readings) through a plan: the fragments named by the syncs are merged tensor by tensor,
  * each tensor in groups of its own length, and all tensors of a fragment whose groups fit the
- * one-pass kernel go out in ONE launch per group-length class (up to 1024, 2048, 4096, 8192,
- * 16384 elements) instead of one launch per tensor.
+ * one-pass kernel go out in ONE launch per group-length class (up to 1024, 1536, 2048, 4096,
+ * 8192, 16384 elements) instead of one launch per tensor.
  *
  * ddl_plan_set_rda_groups   group_len[s] for every segment the plan was created with, empty
  *                           ones included, fragment by fragment in creation order

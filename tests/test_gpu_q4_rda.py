@@ -55,7 +55,7 @@ def _oracle(theta, v, codes, scales, tokens, mask, B, g):
 
 # (rows, group length): row classes 0..4, a ragged tensor of rows, groups that are no multiple
 # of four, the one-workgroup-per-group kernel, long and few groups, one group for the tensor
-SHAPES = [(700, 1024), (600, 1408), (520, 2048), (515, 4096), (513, 8192), (512, 14336),
+SHAPES = [(700, 1024), (600, 1408), (530, 1536), (540, 1028), (520, 2048), (515, 4096), (513, 8192), (512, 14336),
           (600, 1001), (530, 20000), (3, 70000), (2, 70001), (1, 300000), (40, 64)]
 
 

@@ -95,7 +95,10 @@ ROW_LAYOUTS = [(torch.bfloat16, 8, 8192), (torch.bfloat16, 11, 8192), (torch.bfl
                (torch.bfloat16, 16, 4096), (torch.bfloat16, 16, 2048),
                (torch.float32, 3, 16000), (torch.float32, 4, 16000), (torch.float32, 5, 12000),
                (torch.float32, 8, 8192), (torch.float32, 10, 5000), (torch.float32, 11, 5000),
-               (torch.float32, 16, 4096), (torch.float32, 16, 1024)]
+               (torch.float32, 16, 4096), (torch.float32, 16, 1024),
+               # the 192-thread class (rows of 1025 .. 1536): full, partly filled, barely used
+               (torch.bfloat16, 11, 1408), (torch.bfloat16, 3, 1536), (torch.bfloat16, 16, 1028),
+               (torch.float32, 6, 1408), (torch.float32, 16, 1536)]
 
 
 @pytest.mark.parametrize("dtype,Mq,g", ROW_LAYOUTS,
